@@ -1,0 +1,127 @@
+/*
+ * nm.h -- C ABI of libnm: N:M-sparse, low-bit-integer linear layers on MI355X (gfx950).
+ *
+ * Naming: N = weights kept per group, M = group width, groups run along the
+ * input (reduction) dimension.  The paper writes the same pattern the other way
+ * round ("4:2" there is N=2, M=4 here).
+ *
+ * Ownership and execution model (all entry points):
+ *   - every *_dev pointer is DEVICE memory owned by the caller; the library
+ *     allocates nothing, keeps no device state and never frees anything;
+ *   - work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns without synchronising;
+ *   - buffers of one call must not overlap;
+ *   - arguments are validated on the host before anything is launched; a
+ *     negative return value means nothing was enqueued.
+ */
+#ifndef NM_H
+#define NM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum nm_status {
+    NM_OK = 0,
+    NM_ERR_NULL = -1,     /* a required pointer is NULL                                   */
+    NM_ERR_DIM = -2,      /* rows/cols/tokens <= 0 or a leading dimension below its extent */
+    NM_ERR_PATTERN = -3,  /* M not in {4, 8}, N < 1, N >= M, or cols % M != 0              */
+    NM_ERR_BITS = -4,     /* bits not in {4, 8}                                            */
+    NM_ERR_DTYPE = -5,    /* unknown output dtype, or dtype set with a NULL output         */
+    NM_ERR_ALIGN = -6,    /* pointer or leading dimension violates a stated alignment      */
+    NM_ERR_HIP = -7       /* the HIP runtime reported an error at launch                   */
+};
+
+enum nm_out_dtype {
+    NM_OUT_NONE = 0,      /* no dequantised output (accumulators only)   */
+    NM_OUT_F32 = 1,       /* float                                       */
+    NM_OUT_BF16 = 2       /* bfloat16, round-to-nearest-even from float  */
+};
+
+/*
+ * Byte sizes of the three packed buffers of a rows x cols matrix (host only, no
+ * GPU needed).  Any of the three out-pointers may be NULL.
+ *
+ * Packed format (the paper leaves it open; this is the library's definition).
+ * kc = cols*N/M kept entries per row, entry e = g*N + j is the j-th kept column
+ * (ascending) of group g.
+ *   values : row-major, row stride ceil(kc*bits/8) bytes; bits=8: entry e is byte e;
+ *            bits=4: two's-complement nibbles, entry e in byte e/2, low nibble for
+ *            even e, high nibble for odd e.
+ *   meta   : row-major, row stride ceil(kc*ib/8) bytes, ib = 2 for M=4 and 4 for
+ *            M=8; entry e's column offset inside its group occupies ib bits at bit
+ *            e*ib of the row, LSB-first through the bytes.
+ *   scales : float[rows].
+ * Unused trailing bits of a row are zero.
+ */
+int nm_packed_sizes(int rows, int cols, int N, int M, int bits,
+                    size_t *vals_bytes, size_t *meta_bytes, size_t *scales_bytes);
+
+/*
+ * Constrain a trained fp32 matrix to N:M sparsity and `bits`-bit symmetric
+ * integers and pack it: the projection of Sec. 3.2 (Eq. 3: keep the N
+ * largest-magnitude entries of every M-wide group) followed by the max-rule scale
+ * of Sec. 3.3.1 and the quantiser of Sec. 3.3 (Eq. 5, offset 0), applied directly
+ * to the given weights as in Sec. 4.
+ *
+ *   W_dev      [rows][ldw] float, row-major; rows = output neurons, cols = inputs;
+ *              ldw (elements) >= cols; W_dev and ldw*4 must be 16-byte aligned.
+ *   vals_dev, meta_dev, scales_dev   outputs, sizes from nm_packed_sizes; 4-byte aligned.
+ *
+ * Definitions the paper leaves open: equal magnitudes keep the lower column; one
+ * scale per row, s = max|w| / (2^(bits-1)-1) with an all-zero row giving s = 1;
+ * code = clamp(rne(w / s), -(2^(bits-1)-1), +(2^(bits-1)-1)) using IEEE fp32
+ * divisions and round-half-to-even.  Non-finite weights give unspecified bytes.
+ */
+int nm_compress(const float *W_dev, int rows, int cols, int ldw,
+                int N, int M, int bits,
+                void *vals_dev, void *meta_dev, float *scales_dev,
+                void *hip_stream);
+
+/*
+ * Expand packed weights to the dense integer matrix Wq_dev[rows][cols] (int8,
+ * zeros at pruned positions, int4 codes sign-extended).  Inverse of the packing
+ * step; used to check that the sparse product equals the dense one.
+ */
+int nm_decompress_i8(const void *vals_dev, const void *meta_dev, int rows, int cols,
+                     int N, int M, int bits, int8_t *Wq_dev, void *hip_stream);
+
+/*
+ * The sparse integer linear layer of Sec. 5.3 with the dequantisation of Sec. 3.3
+ * (Eq. 4, offset 0) fused behind it:
+ *
+ *   acc[t][o] = sum over kept entries e of row o:  X[t][col(o,e)] * q[o][e]   (int32, exact)
+ *   y[t][o]   = float(acc[t][o]) * (act_scale * scales[o])  (+ bias[o])
+ *
+ *   X_dev      [tokens][ldx] int8 activations, ldx >= K; X_dev and ldx 16-byte aligned.
+ *   act_scale  per-tensor activation scale (host value).
+ *   vals_dev, meta_dev, scales_dev   packed weights of an O x K matrix as written by
+ *              nm_compress with the same N, M, bits.
+ *   bias_dev   float[O] or NULL.
+ *   acc_dev    int32 [tokens][ldo] or NULL (exact accumulators, optional).
+ *   out_dev    [tokens][ldo] of out_dtype, or NULL with NM_OUT_NONE.
+ *   ldo        leading dimension (elements) of acc_dev and out_dev, >= O.
+ *
+ * At least one of acc_dev / out_dev must be given.  Low-bit weights are widened to
+ * int8 in registers; products of pruned positions are never formed on the 2:4
+ * hardware path.  Results do not depend on launch shape (integer sums are exact;
+ * the epilogue is elementwise).
+ */
+int nm_gemm(const int8_t *X_dev, int tokens, int K, int ldx, float act_scale,
+            const void *vals_dev, const void *meta_dev, const float *scales_dev,
+            int O, int N, int M, int bits,
+            const float *bias_dev,
+            int32_t *acc_dev,
+            void *out_dev, int out_dtype,
+            int ldo, void *hip_stream);
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char *nm_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NM_H */

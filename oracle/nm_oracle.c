@@ -1,0 +1,335 @@
+/*
+ * nm_oracle.c -- plain CPU oracle for the N:M-sparse low-bit integer path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement
+ * of what the path computes.  It shares no code with the HIP library, is never
+ * linked into it, and is called only from the tests, the smoke check and the
+ * benchmark's CPU-baseline leg.
+ *
+ * Convention used everywhere: N = kept entries per group, M = group width
+ * (the paper writes the same pattern as "M:N", e.g. its "4:2" is 2:4 here).
+ * W is [rows = output neurons][cols = input features], row-major, and groups
+ * run along the input (reduction) dimension.
+ *
+ * What each function follows:
+ *   nmo_project        Sec. 3.2, Eq. 3: Euclidean projection onto the N:M set,
+ *                      i.e. keep the N largest-magnitude entries of each group.
+ *   nmo_row_scale      Sec. 3.3.1 "minimize error on the largest parameter":
+ *                      scale = largest magnitude / largest integer code.
+ *   nmo_quantize_one   Sec. 3.3, Eq. 5 with offset o = 0 (symmetric).
+ *   nmo_compress       Sec. 3.3.1 last paragraph: the two constraints solved in
+ *                      sequence, sparsity first; Sec. 4: constraining a trained
+ *                      matrix directly (no fine-tuning).
+ *   nmo_gemm_sparse    Sec. 5.3: only the kept products are computed, low-bit
+ *                      weights widened to the activation type, int32 sums.
+ *   nmo_dequant        Sec. 3.3, Eq. 4 with o = 0: x_d = s * x_q.
+ *
+ * Readings where the paper is silent (all listed in the design notes):
+ *   - "largest" means largest magnitude; equal magnitudes keep the lower column.
+ *   - one scale per output row; an all-zero row gets scale 1.
+ *   - fp32 arithmetic for the scale and the quotient: two true IEEE divisions
+ *     (amax / qmax, then w / s), round-half-to-even, clamp to [-qmax, +qmax],
+ *     qmax = 2^(b-1) - 1.
+ *   - packed format: see nmo_packed_sizes.
+ *   - the dequantized value is formed in double and rounded once.
+ *
+ * Build: gcc -O2 -std=c11 -fno-fast-math -ffp-contract=off -fopenmp -shared -fPIC
+ *
+ * Pins (tests/test_oracle_*.py): brute-force Euclidean projection over all
+ * supports, N=1 == argmax, idempotence, max-survives-pruning invariant,
+ * quantiser closed forms and half-way cases, an independent numpy decoder of
+ * the byte format, numpy int64 matmul on the decompressed matrix, dequant
+ * special cases.  The tie-break rule and the byte format are this build's own
+ * choices (the paper fixes neither): pinned by the written format description
+ * and the independent decoder, not by the paper.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+enum {
+    NMO_OK = 0,
+    NMO_ERR_NULL = -1,
+    NMO_ERR_DIM = -2,
+    NMO_ERR_PATTERN = -3,
+    NMO_ERR_BITS = -4,
+    NMO_ERR_NONFINITE = -5
+};
+
+static int index_bits(int M) { return M == 4 ? 2 : 4; }
+
+static int check_pattern(int rows, int cols, int N, int M, int bits)
+{
+    if (rows <= 0 || cols <= 0) return NMO_ERR_DIM;
+    if (M != 4 && M != 8) return NMO_ERR_PATTERN;
+    if (N < 1 || N >= M) return NMO_ERR_PATTERN;
+    if (cols % M != 0) return NMO_ERR_PATTERN;
+    if (bits != 4 && bits != 8) return NMO_ERR_BITS;
+    return NMO_OK;
+}
+
+/*
+ * Packed format (the paper does not discuss one; this is the library's own).
+ * kc = cols * N / M kept entries per row, numbered e = g*N + j in ascending
+ * column order (g = group, j = rank of the kept column inside the group).
+ *   values : row-major, row stride ceil(kc*bits/8) bytes.
+ *            bits = 8: entry e is byte e (two's complement).
+ *            bits = 4: entry e is a two's-complement nibble of byte e/2,
+ *                      low nibble when e is even, high nibble when e is odd.
+ *   meta   : row-major, row stride ceil(kc*ib/8) bytes, ib = 2 (M=4) or 4 (M=8).
+ *            Entry e's column offset inside its group sits in ib bits starting
+ *            at bit e*ib of the row, counted LSB-first through the bytes.
+ *   scales : one float per row.
+ * Unused trailing bits of a row are zero.
+ */
+int nmo_packed_sizes(int rows, int cols, int N, int M, int bits,
+                     size_t *vals_bytes, size_t *meta_bytes, size_t *scales_bytes)
+{
+    int rc = check_pattern(rows, cols, N, M, bits);
+    if (rc) return rc;
+    size_t kc = (size_t)cols / M * N;
+    if (vals_bytes) *vals_bytes = (size_t)rows * ((kc * bits + 7) / 8);
+    if (meta_bytes) *meta_bytes = (size_t)rows * ((kc * index_bits(M) + 7) / 8);
+    if (scales_bytes) *scales_bytes = (size_t)rows * sizeof(float);
+    return NMO_OK;
+}
+
+/*
+ * Eq. 3 for one group: choose the N of M entries that the projection keeps.
+ * Entries are ranked by magnitude, larger first; among equal magnitudes the
+ * lower column ranks first.  The N best are returned in ascending column order.
+ */
+static void project_group(const float *w, int N, int M, uint8_t *kept)
+{
+    int taken[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int pick = 0; pick < N; ++pick) {
+        int best = -1;
+        for (int c = 0; c < M; ++c) {
+            if (taken[c]) continue;
+            if (best < 0 || fabsf(w[c]) > fabsf(w[best])) best = c; /* strict: ties stay low */
+        }
+        taken[best] = 1;
+    }
+    int j = 0;
+    for (int c = 0; c < M; ++c)
+        if (taken[c]) kept[j++] = (uint8_t)c;
+}
+
+/* Eq. 3 over a matrix: kept[r][g*N + j] = column offset (0..M-1) inside group g. */
+int nmo_project(const float *W, int rows, int cols, int ldw, int N, int M, uint8_t *kept)
+{
+    int rc = check_pattern(rows, cols, N, M, 8);
+    if (rc) return rc;
+    if (!W || !kept) return NMO_ERR_NULL;
+    if (ldw < cols) return NMO_ERR_DIM;
+    int groups = cols / M;
+    for (int r = 0; r < rows; ++r)
+        for (int g = 0; g < groups; ++g) {
+            const float *w = W + (size_t)r * ldw + (size_t)g * M;
+            for (int c = 0; c < M; ++c)
+                if (!isfinite(w[c])) return NMO_ERR_NONFINITE;
+            project_group(w, N, M, kept + ((size_t)r * groups + g) * N);
+        }
+    return NMO_OK;
+}
+
+/* Sec. 3.3.1: scale = max |w| over the row / largest code.  All-zero row -> 1. */
+float nmo_row_scale(const float *w, int cols, int bits)
+{
+    float amax = 0.0f;
+    for (int c = 0; c < cols; ++c) {
+        float a = fabsf(w[c]);
+        if (a > amax) amax = a;
+    }
+    float qmax = (float)((1 << (bits - 1)) - 1);
+    volatile float s = amax / qmax; /* one fp32 division, kept in fp32 */
+    return amax == 0.0f ? 1.0f : s;
+}
+
+/* Eq. 5 with o = 0: divide by the scale, round half to even, clamp. */
+int nmo_quantize_one(float w, float s, int bits)
+{
+    int qmax = (1 << (bits - 1)) - 1;
+    volatile float t = w / s;      /* one fp32 division */
+    float r = nearbyintf(t);       /* default rounding mode: nearest, ties to even */
+    if (r > (float)qmax) r = (float)qmax;
+    if (r < (float)-qmax) r = (float)-qmax;
+    return (int)r;
+}
+
+static void put_bits(uint8_t *row, size_t bit_offset, int nbits, unsigned value)
+{
+    for (int b = 0; b < nbits; ++b) {
+        size_t pos = bit_offset + (size_t)b;
+        if ((value >> b) & 1u) row[pos >> 3] |= (uint8_t)(1u << (pos & 7));
+    }
+}
+
+static unsigned get_bits(const uint8_t *row, size_t bit_offset, int nbits)
+{
+    unsigned v = 0;
+    for (int b = 0; b < nbits; ++b) {
+        size_t pos = bit_offset + (size_t)b;
+        v |= (unsigned)((row[pos >> 3] >> (pos & 7)) & 1u) << b;
+    }
+    return v;
+}
+
+/* project (Eq. 3), then scale and quantise the kept entries (Eq. 5), then pack. */
+int nmo_compress(const float *W, int rows, int cols, int ldw, int N, int M, int bits,
+                 uint8_t *vals, uint8_t *meta, float *scales)
+{
+    int rc = check_pattern(rows, cols, N, M, bits);
+    if (rc) return rc;
+    if (!W || !vals || !meta || !scales) return NMO_ERR_NULL;
+    if (ldw < cols) return NMO_ERR_DIM;
+    int groups = cols / M;
+    int ib = index_bits(M);
+    size_t kc = (size_t)groups * N;
+    size_t vstride = (kc * bits + 7) / 8;
+    size_t mstride = (kc * ib + 7) / 8;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int r = 0; r < rows; ++r) {
+        const float *w = W + (size_t)r * ldw;
+        uint8_t *vrow = vals + (size_t)r * vstride;
+        uint8_t *mrow = meta + (size_t)r * mstride;
+        int finite = 1;
+        for (int c = 0; c < cols; ++c)
+            if (!isfinite(w[c])) finite = 0;
+        if (!finite) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
+        memset(vrow, 0, vstride);
+        memset(mrow, 0, mstride);
+        float s = nmo_row_scale(w, cols, bits);
+        scales[r] = s;
+        for (int g = 0; g < groups; ++g) {
+            uint8_t kept[8];
+            project_group(w + (size_t)g * M, N, M, kept);
+            for (int j = 0; j < N; ++j) {
+                size_t e = (size_t)g * N + j;
+                int q = nmo_quantize_one(w[(size_t)g * M + kept[j]], s, bits);
+                put_bits(vrow, e * bits, bits, (unsigned)q & ((1u << bits) - 1u));
+                put_bits(mrow, e * ib, ib, kept[j]);
+            }
+        }
+    }
+    return bad ? NMO_ERR_NONFINITE : NMO_OK;
+}
+
+static int sign_extend(unsigned v, int bits)
+{
+    int sh = 32 - bits;
+    return (int)((int32_t)(v << sh) >> sh);
+}
+
+/* Packed -> dense integer matrix Wq[rows][cols] (zeros where nothing was kept). */
+int nmo_decompress(const uint8_t *vals, const uint8_t *meta, int rows, int cols,
+                   int N, int M, int bits, int8_t *Wq)
+{
+    int rc = check_pattern(rows, cols, N, M, bits);
+    if (rc) return rc;
+    if (!vals || !meta || !Wq) return NMO_ERR_NULL;
+    int groups = cols / M;
+    int ib = index_bits(M);
+    size_t kc = (size_t)groups * N;
+    size_t vstride = (kc * bits + 7) / 8;
+    size_t mstride = (kc * ib + 7) / 8;
+    memset(Wq, 0, (size_t)rows * cols);
+    for (int r = 0; r < rows; ++r)
+        for (size_t e = 0; e < kc; ++e) {
+            int q = sign_extend(get_bits(vals + (size_t)r * vstride, e * bits, bits), bits);
+            unsigned off = get_bits(meta + (size_t)r * mstride, e * ib, ib);
+            size_t col = (e / N) * M + off;
+            Wq[(size_t)r * cols + col] = (int8_t)q;
+        }
+    return NMO_OK;
+}
+
+/*
+ * Sec. 5.3: acc[t][o] = sum over kept entries e of X[t][col(o,e)] * q[o][e],
+ * walking the metadata; nothing is computed for pruned positions.
+ */
+int nmo_gemm_sparse(const int8_t *X, int tokens, int K, int ldx,
+                    const uint8_t *vals, const uint8_t *meta,
+                    int O, int N, int M, int bits, int32_t *acc, int ldacc)
+{
+    int rc = check_pattern(O, K, N, M, bits);
+    if (rc) return rc;
+    if (!X || !vals || !meta || !acc) return NMO_ERR_NULL;
+    if (tokens <= 0 || ldx < K || ldacc < O) return NMO_ERR_DIM;
+    int ib = index_bits(M);
+    size_t kc = (size_t)K / M * N;
+    size_t vstride = (kc * bits + 7) / 8;
+    size_t mstride = (kc * ib + 7) / 8;
+#pragma omp parallel for schedule(static)
+    for (int o = 0; o < O; ++o) {
+        const uint8_t *vrow = vals + (size_t)o * vstride;
+        const uint8_t *mrow = meta + (size_t)o * mstride;
+        for (int t = 0; t < tokens; ++t) {
+            const int8_t *x = X + (size_t)t * ldx;
+            int32_t sum = 0;
+            for (size_t e = 0; e < kc; ++e) {
+                int q = sign_extend(get_bits(vrow, e * bits, bits), bits);
+                size_t col = (e / N) * M + get_bits(mrow, e * ib, ib);
+                sum += (int32_t)x[col] * (int32_t)q;
+            }
+            acc[(size_t)t * ldacc + o] = sum;
+        }
+    }
+    return NMO_OK;
+}
+
+/* The plain definition the sparse product must equal: acc = X * Wq^T, all K terms. */
+int nmo_gemm_dense(const int8_t *X, int tokens, int K, int ldx,
+                   const int8_t *Wq, int O, int32_t *acc, int ldacc)
+{
+    if (!X || !Wq || !acc) return NMO_ERR_NULL;
+    if (tokens <= 0 || K <= 0 || O <= 0 || ldx < K || ldacc < O) return NMO_ERR_DIM;
+#pragma omp parallel for schedule(static)
+    for (int o = 0; o < O; ++o)
+        for (int t = 0; t < tokens; ++t) {
+            int32_t sum = 0;
+            for (int k = 0; k < K; ++k)
+                sum += (int32_t)X[(size_t)t * ldx + k] * (int32_t)Wq[(size_t)o * K + k];
+            acc[(size_t)t * ldacc + o] = sum;
+        }
+    return NMO_OK;
+}
+
+/* float -> bfloat16 bits, round to nearest, ties to even (finite inputs). */
+static uint16_t bf16_rne(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+/*
+ * Eq. 4 with o = 0 applied to the product of two quantised operands:
+ * y = acc * s_act * s_w[o] (+ bias[o]), formed in double, rounded once to
+ * float; the bfloat16 result is that float rounded to nearest-even.
+ * bias, out_f32 and out_bf16 may each be NULL.
+ */
+int nmo_dequant(const int32_t *acc, int tokens, int O, int ldacc, float act_scale,
+                const float *scales, const float *bias,
+                float *out_f32, uint16_t *out_bf16, int ldo)
+{
+    if (!acc || !scales) return NMO_ERR_NULL;
+    if (tokens <= 0 || O <= 0 || ldacc < O || ldo < O) return NMO_ERR_DIM;
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < tokens; ++t)
+        for (int o = 0; o < O; ++o) {
+            double y = (double)acc[(size_t)t * ldacc + o] * (double)act_scale * (double)scales[o];
+            if (bias) y += (double)bias[o];
+            float yf = (float)y;
+            if (out_f32) out_f32[(size_t)t * ldo + o] = yf;
+            if (out_bf16) out_bf16[(size_t)t * ldo + o] = bf16_rne(yf);
+        }
+    return NMO_OK;
+}

@@ -1,0 +1,15 @@
+"""N:M-sparse low-bit integer linear layers for MI355X (gfx950).
+
+``nm_compress`` / ``nm_gemm`` and friends are thin marshalling wrappers over the
+C-ABI library built from ``csrc/``; every step of the path runs in its HIP
+kernels.  ``synth`` holds the seeded input generators and workload tables.
+"""
+from .binding import (  # noqa: F401
+    NMError,
+    library_path,
+    nm_compress,
+    nm_decompress_i8,
+    nm_gemm,
+    nm_packed_sizes,
+    nm_status_string,
+)

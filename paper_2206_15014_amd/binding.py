@@ -1,0 +1,136 @@
+"""ctypes binding of libnm (declared in include/nm.h): argument marshalling only.
+
+Tensors are torch CUDA tensors used purely as device buffers; the current torch
+stream is handed to the library.  There is no CPU fallback: a missing library is
+an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libnm.so")
+
+NM_OUT_NONE, NM_OUT_F32, NM_OUT_BF16 = 0, 1, 2
+
+_lib = None
+
+
+class NMError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        super().__init__("%s failed: %s (%d)" % (where, nm_status_string(code), code))
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            "libnm.so is not built (%s); run `python -c 'import __graft_entry__ as g; g.build()'`"
+            % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    c_int, c_vp, c_f = ctypes.c_int, ctypes.c_void_p, ctypes.c_float
+    szp = ctypes.POINTER(ctypes.c_size_t)
+    lib.nm_packed_sizes.restype = c_int
+    lib.nm_packed_sizes.argtypes = [c_int] * 5 + [szp] * 3
+    lib.nm_compress.restype = c_int
+    lib.nm_compress.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
+    lib.nm_decompress_i8.restype = c_int
+    lib.nm_decompress_i8.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp]
+    lib.nm_gemm.restype = c_int
+    lib.nm_gemm.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp,
+                            c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_int, c_int, c_vp]
+    lib.nm_status_string.restype = ctypes.c_char_p
+    lib.nm_status_string.argtypes = [c_int]
+    _lib = lib
+    return lib
+
+
+def raw():
+    """The loaded ctypes library (for callers that marshal pointers themselves)."""
+    return _load()
+
+
+def nm_status_string(status: int) -> str:
+    return _load().nm_status_string(int(status)).decode()
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def nm_packed_sizes(rows: int, cols: int, N: int, M: int, bits: int) -> Tuple[int, int, int]:
+    v, m, s = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    rc = _load().nm_packed_sizes(rows, cols, N, M, bits, ctypes.byref(v), ctypes.byref(m), ctypes.byref(s))
+    if rc:
+        raise NMError(rc, "nm_packed_sizes")
+    return v.value, m.value, s.value
+
+
+def nm_compress(W, N: int, M: int, bits: int, vals=None, meta=None, scales=None, stream=None):
+    """W: float32 CUDA tensor [rows, cols] (row stride may exceed cols).
+
+    Returns (vals uint8 [rows, vstride], meta uint8 [rows, mstride], scales float32 [rows]).
+    """
+    import torch
+    rows, cols = W.shape
+    vb, mb, _ = nm_packed_sizes(rows, cols, N, M, bits)
+    if vals is None:
+        vals = torch.empty((rows, vb // rows), dtype=torch.uint8, device=W.device)
+    if meta is None:
+        meta = torch.empty((rows, mb // rows), dtype=torch.uint8, device=W.device)
+    if scales is None:
+        scales = torch.empty(rows, dtype=torch.float32, device=W.device)
+    rc = _load().nm_compress(_ptr(W), rows, cols, W.stride(0), N, M, bits,
+                             _ptr(vals), _ptr(meta), _ptr(scales), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_compress")
+    return vals, meta, scales
+
+
+def nm_decompress_i8(vals, meta, rows: int, cols: int, N: int, M: int, bits: int, out=None, stream=None):
+    import torch
+    if out is None:
+        out = torch.empty((rows, cols), dtype=torch.int8, device=vals.device)
+    rc = _load().nm_decompress_i8(_ptr(vals), _ptr(meta), rows, cols, N, M, bits, _ptr(out), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_decompress_i8")
+    return out
+
+
+def nm_gemm(X, act_scale: float, vals, meta, scales, O: int, N: int, M: int, bits: int,
+            bias=None, acc=None, out=None, out_dtype: int = NM_OUT_NONE, ldo: Optional[int] = None,
+            stream=None):
+    """X: int8 CUDA tensor [tokens, K].  acc (int32) and out (float32 / bfloat16), when
+    given, are [tokens, ldo] buffers written in place; returns (acc, out)."""
+    tokens, K = X.shape
+    if ldo is None:
+        ref = out if out is not None else acc
+        ldo = ref.stride(0) if ref is not None and hasattr(ref, "stride") else O
+    rc = _load().nm_gemm(_ptr(X), tokens, K, X.stride(0), float(act_scale),
+                         _ptr(vals), _ptr(meta), _ptr(scales), O, N, M, bits,
+                         _ptr(bias), _ptr(acc), _ptr(out), out_dtype, ldo, _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_gemm")
+    return acc, out
