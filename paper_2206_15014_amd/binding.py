@@ -36,6 +36,9 @@ def _load():
         raise ImportError(
             "libnm.so is not built (%s); run `python -c 'import __graft_entry__ as g; g.build()'`"
             % _LIB_PATH)
+    # torch first: the process must hold ONE HIP runtime, and torch brings its own copy; with it
+    # already loaded, libnm's dependency on libamdhip64 resolves to that same copy.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     c_int, c_vp, c_f = ctypes.c_int, ctypes.c_void_p, ctypes.c_float
     szp = ctypes.POINTER(ctypes.c_size_t)

@@ -1,0 +1,106 @@
+// C-ABI front end of libnm (declared in include/nm.h): host-side argument validation and dispatch.
+// Nothing here touches the GPU before the arguments have been accepted.
+#include <hip/hip_runtime.h>
+
+#include "nm.h"
+#include "nm_internal.h"
+
+namespace {
+
+int check_pattern(int rows, int cols, int N, int M, int bits)
+{
+    if (rows <= 0 || cols <= 0) return NM_ERR_DIM;
+    if (M != 4 && M != 8) return NM_ERR_PATTERN;
+    if (N < 1 || N >= M) return NM_ERR_PATTERN;
+    if (cols % M != 0) return NM_ERR_PATTERN;
+    if (bits != 4 && bits != 8) return NM_ERR_BITS;
+    return NM_OK;
+}
+
+size_t row_bytes(size_t entries, int bits_per_entry) { return (entries * bits_per_entry + 7) / 8; }
+
+}  // namespace
+
+extern "C" {
+
+int nm_packed_sizes(int rows, int cols, int N, int M, int bits,
+                    size_t* vals_bytes, size_t* meta_bytes, size_t* scales_bytes)
+{
+    const int rc = check_pattern(rows, cols, N, M, bits);
+    if (rc) return rc;
+    const size_t kc = (size_t)cols / M * N;
+    if (vals_bytes) *vals_bytes = (size_t)rows * row_bytes(kc, bits);
+    if (meta_bytes) *meta_bytes = (size_t)rows * row_bytes(kc, M == 4 ? 2 : 4);
+    if (scales_bytes) *scales_bytes = (size_t)rows * sizeof(float);
+    return NM_OK;
+}
+
+int nm_compress(const float* W_dev, int rows, int cols, int ldw, int N, int M, int bits,
+                void* vals_dev, void* meta_dev, float* scales_dev, void* hip_stream)
+{
+    const int rc = check_pattern(rows, cols, N, M, bits);
+    if (rc) return rc;
+    if (!W_dev || !vals_dev || !meta_dev || !scales_dev) return NM_ERR_NULL;
+    if (ldw < cols) return NM_ERR_DIM;
+    if ((uintptr_t)W_dev % 4 || (uintptr_t)scales_dev % 4) return NM_ERR_ALIGN;
+    return nm::launch_compress(W_dev, rows, cols, ldw, N, M, bits, vals_dev, meta_dev, scales_dev,
+                               static_cast<hipStream_t>(hip_stream));
+}
+
+int nm_decompress_i8(const void* vals_dev, const void* meta_dev, int rows, int cols,
+                     int N, int M, int bits, int8_t* Wq_dev, void* hip_stream)
+{
+    const int rc = check_pattern(rows, cols, N, M, bits);
+    if (rc) return rc;
+    if (!vals_dev || !meta_dev || !Wq_dev) return NM_ERR_NULL;
+    return nm::launch_decompress(vals_dev, meta_dev, rows, cols, N, M, bits, Wq_dev,
+                                 static_cast<hipStream_t>(hip_stream));
+}
+
+int nm_gemm(const int8_t* X_dev, int tokens, int K, int ldx, float act_scale,
+            const void* vals_dev, const void* meta_dev, const float* scales_dev,
+            int O, int N, int M, int bits,
+            const float* bias_dev, int32_t* acc_dev, void* out_dev, int out_dtype,
+            int ldo, void* hip_stream)
+{
+    const int rc = check_pattern(O, K, N, M, bits);
+    if (rc) return rc;
+    if (tokens <= 0) return NM_ERR_DIM;
+    if (!X_dev || !vals_dev || !meta_dev || !scales_dev) return NM_ERR_NULL;
+    if (out_dtype != NM_OUT_NONE && out_dtype != NM_OUT_F32 && out_dtype != NM_OUT_BF16) return NM_ERR_DTYPE;
+    if ((out_dtype == NM_OUT_NONE) != (out_dev == nullptr)) return NM_ERR_DTYPE;
+    if (!acc_dev && !out_dev) return NM_ERR_NULL;
+    if (ldx < K || ldo < O) return NM_ERR_DIM;
+    if ((uintptr_t)scales_dev % 4 || (uintptr_t)bias_dev % 4 || (uintptr_t)acc_dev % 4 ||
+        (uintptr_t)out_dev % (out_dtype == NM_OUT_BF16 ? 2 : 4))
+        return NM_ERR_ALIGN;
+
+    nm::GemmArgs a;
+    a.X = X_dev; a.tokens = tokens; a.K = K; a.ldx = ldx; a.act_scale = act_scale;
+    a.vals = static_cast<const uint8_t*>(vals_dev);
+    a.meta = static_cast<const uint8_t*>(meta_dev);
+    a.scales = scales_dev;
+    a.O = O; a.N = N; a.M = M; a.bits = bits;
+    a.bias = bias_dev; a.acc = acc_dev; a.out = out_dev; a.out_dtype = out_dtype; a.ldo = ldo;
+    const size_t kc = (size_t)K / M * N;
+    a.vstride = (int)row_bytes(kc, bits);
+    a.mstride = (int)row_bytes(kc, M == 4 ? 2 : 4);
+    return nm::launch_gemm(a, static_cast<hipStream_t>(hip_stream));
+}
+
+const char* nm_status_string(int status)
+{
+    switch (status) {
+        case NM_OK: return "ok";
+        case NM_ERR_NULL: return "required pointer is null";
+        case NM_ERR_DIM: return "bad dimension or leading dimension";
+        case NM_ERR_PATTERN: return "unsupported N:M pattern for this width";
+        case NM_ERR_BITS: return "weight bits must be 4 or 8";
+        case NM_ERR_DTYPE: return "bad output dtype / output pointer combination";
+        case NM_ERR_ALIGN: return "pointer or leading dimension misaligned";
+        case NM_ERR_HIP: return "HIP launch error";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

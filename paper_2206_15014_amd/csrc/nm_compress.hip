@@ -1,0 +1,307 @@
+// nm_compress / nm_decompress_i8 kernels for gfx950.
+//
+// nm_compress applies, per output row, the N:M projection of Sec. 3.2 (Eq. 3), the
+// max-rule scale of Sec. 3.3.1 and the symmetric quantiser of Sec. 3.3 (Eq. 5, offset 0),
+// in that order (Sec. 3.3.1, last paragraph), and writes the packed format described in
+// include/nm.h.  The work is bound by reading the fp32 matrix once from HBM.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nm_internal.h"
+
+namespace nm {
+
+namespace {
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+
+// OR together the `lanes` consecutive lanes of each aligned lane group (lanes is a power of two).
+template <int LANES>
+__device__ __forceinline__ uint32_t group_or(uint32_t v)
+{
+#pragma unroll
+    for (int m = 1; m < LANES; m <<= 1) v |= (uint32_t)__shfl_xor((int)v, m, 64);
+    return v;
+}
+
+// Eq. 5 with offset 0: true fp32 division, round half to even, symmetric clamp.
+template <int BITS>
+__device__ __forceinline__ int quantize(float w, float s)
+{
+    constexpr float QMAX = (float)((1 << (BITS - 1)) - 1);
+    float r = rintf(w / s);
+    r = fminf(fmaxf(r, -QMAX), QMAX);
+    return (int)r;
+}
+
+// Eq. 3 on one group held in registers.  Returns a bit mask of the kept columns: an entry is
+// kept when fewer than N entries outrank it, where a larger magnitude outranks a smaller one
+// and, between equal magnitudes, the lower column outranks the higher.
+template <int N, int M>
+__device__ __forceinline__ uint32_t keep_mask(const float (&x)[M])
+{
+    float a[M];
+#pragma unroll
+    for (int c = 0; c < M; ++c) a[c] = fabsf(x[c]);
+    uint32_t mask = 0;
+#pragma unroll
+    for (int c = 0; c < M; ++c) {
+        int outranked = 0;
+#pragma unroll
+        for (int d = 0; d < M; ++d) {
+            if (d == c) continue;
+            outranked += (d < c) ? (a[d] >= a[c]) : (a[d] > a[c]);
+        }
+        mask |= (outranked < N ? 1u : 0u) << c;
+    }
+    return mask;
+}
+
+template <int M>
+__device__ __forceinline__ float pick(const float (&x)[M], int c)
+{
+    float v = x[0];
+#pragma unroll
+    for (int d = 1; d < M; ++d) v = (c == d) ? x[d] : v;
+    return v;
+}
+
+// One group -> its value bits (N codes of BITS bits, ascending columns) and index bits.
+template <int N, int M, int BITS>
+__device__ __forceinline__ void encode_group(const float (&x)[M], float s, uint32_t& vbits, uint32_t& mbits)
+{
+    constexpr int IB = (M == 4) ? 2 : 4;
+    uint32_t mask = keep_mask<N, M>(x);
+    vbits = 0;
+    mbits = 0;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        int c = __builtin_ctz(mask);
+        mask &= mask - 1;
+        int q = quantize<BITS>(pick<M>(x, c), s);
+        vbits |= ((uint32_t)q & ((1u << BITS) - 1u)) << (j * BITS);
+        mbits |= (uint32_t)c << (j * IB);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// One wavefront per row.  Lane l owns group j*64 + l of pass j, so the fp32 row is read with
+// lane-contiguous 16-byte loads, and the per-group value / index bits of neighbouring lanes are
+// OR-combined into whole dwords before they are stored.  Rows of up to 4096 columns stay in
+// registers between the amax pass and the encode pass; longer rows are read a second time.
+// Requires: N*BITS and N*IB in {2,4,8,16,32}, packed row strides that are multiples of 4 bytes,
+// ldw % 4 == 0 and a 16-byte aligned W.
+// ---------------------------------------------------------------------------------------------
+template <int N, int M, int BITS>
+__global__ void __launch_bounds__(256)
+compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
+                     uint32_t* __restrict__ vals, uint32_t* __restrict__ meta, float* __restrict__ scales,
+                     int vstride_dw, int mstride_dw)
+{
+    constexpr int IB = (M == 4) ? 2 : 4;
+    constexpr int VB = N * BITS;           // value bits per group
+    constexpr int MB = N * IB;             // index bits per group
+    constexpr int VL = 32 / VB;            // lanes per value dword
+    constexpr int ML = 32 / MB;            // lanes per index dword
+    constexpr int F4 = M / 4;              // 16-byte loads per group
+    constexpr int RES = 16 / F4;           // register-resident passes (64 floats per lane)
+    constexpr float QMAX = (float)((1 << (BITS - 1)) - 1);
+
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;               // whole wavefront leaves together; no block barrier is used
+
+    const float4* __restrict__ w4 = reinterpret_cast<const float4*>(W + (size_t)row * ldw);
+    const int groups = cols / M;
+    const int passes = (groups + 63) >> 6;
+    const bool resident = passes <= RES;
+
+    float x[RES][M];
+    float amax = 0.0f;
+    if (resident) {
+#pragma unroll
+        for (int j = 0; j < RES; ++j) {
+            if (j < passes) {
+                int g = j * 64 + lane;
+#pragma unroll
+                for (int f = 0; f < F4; ++f) {
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (g < groups) v = w4[(size_t)g * F4 + f];
+                    x[j][4 * f + 0] = v.x; x[j][4 * f + 1] = v.y; x[j][4 * f + 2] = v.z; x[j][4 * f + 3] = v.w;
+                    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+                }
+            }
+        }
+    } else {
+        for (int g = lane; g < groups; g += 64)
+#pragma unroll
+            for (int f = 0; f < F4; ++f) {
+                float4 v = w4[(size_t)g * F4 + f];
+                amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+            }
+    }
+    amax = wave_max(amax);
+    // Sec. 3.3.1: largest magnitude over the largest code; an all-zero row keeps scale 1
+    const float s = (amax == 0.0f) ? 1.0f : amax / QMAX;
+    if (lane == 0) scales[row] = s;
+
+    uint32_t* __restrict__ vrow = vals + (size_t)row * vstride_dw;
+    uint32_t* __restrict__ mrow = meta + (size_t)row * mstride_dw;
+
+    auto emit = [&](const float (&grp)[M], int g) {
+        uint32_t vb = 0, mb = 0;
+        if (g < groups) encode_group<N, M, BITS>(grp, s, vb, mb);
+        vb = group_or<VL>(vb << ((lane % VL) * VB));
+        mb = group_or<ML>(mb << ((lane % ML) * MB));
+        if (g < groups && lane % VL == 0) vrow[g / VL] = vb;
+        if (g < groups && lane % ML == 0) mrow[g / ML] = mb;
+    };
+
+    if (resident) {
+#pragma unroll
+        for (int j = 0; j < RES; ++j)
+            if (j < passes) emit(x[j], j * 64 + lane);
+    } else {
+        for (int j = 0; j < passes; ++j) {
+            int g = j * 64 + lane;
+            float grp[M];
+#pragma unroll
+            for (int f = 0; f < F4; ++f) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (g < groups) v = w4[(size_t)g * F4 + f];
+                grp[4 * f + 0] = v.x; grp[4 * f + 1] = v.y; grp[4 * f + 2] = v.z; grp[4 * f + 3] = v.w;
+            }
+            emit(grp, g);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Any pattern, any width, any alignment: one thread per row, bytes written one at a time.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(64)
+compress_generic_kernel(const float* __restrict__ W, int rows, int cols, int ldw, int N, int M, int bits,
+                        uint8_t* __restrict__ vals, uint8_t* __restrict__ meta, float* __restrict__ scales,
+                        int vstride, int mstride)
+{
+    const int row = blockIdx.x * 64 + threadIdx.x;
+    if (row >= rows) return;
+    const float* w = W + (size_t)row * ldw;
+    const int ib = (M == 4) ? 2 : 4;
+    const int qmaxi = (1 << (bits - 1)) - 1;
+    float amax = 0.0f;
+    for (int c = 0; c < cols; ++c) amax = fmaxf(amax, fabsf(w[c]));
+    const float s = (amax == 0.0f) ? 1.0f : amax / (float)qmaxi;
+    scales[row] = s;
+    uint8_t* vrow = vals + (size_t)row * vstride;
+    uint8_t* mrow = meta + (size_t)row * mstride;
+    uint32_t vacc = 0, macc = 0;
+    int vfill = 0, mfill = 0, vpos = 0, mpos = 0;
+    for (int g = 0; g < cols / M; ++g) {
+        float x[8];
+        for (int c = 0; c < 8; ++c) x[c] = (c < M) ? w[g * M + c] : 0.0f;
+        for (int c = 0; c < M; ++c) {
+            int outranked = 0;
+            for (int d = 0; d < M; ++d) {
+                if (d == c) continue;
+                float ad = fabsf(x[d]), ac = fabsf(x[c]);
+                outranked += (d < c) ? (ad >= ac) : (ad > ac);
+            }
+            if (outranked >= N) continue;
+            float r = rintf(x[c] / s);
+            r = fminf(fmaxf(r, (float)-qmaxi), (float)qmaxi);
+            vacc |= ((uint32_t)(int)r & ((1u << bits) - 1u)) << vfill;
+            vfill += bits;
+            macc |= (uint32_t)c << mfill;
+            mfill += ib;
+            while (vfill >= 8) { vrow[vpos++] = (uint8_t)vacc; vacc >>= 8; vfill -= 8; }
+            while (mfill >= 8) { mrow[mpos++] = (uint8_t)macc; macc >>= 8; mfill -= 8; }
+        }
+    }
+    if (vfill > 0) vrow[vpos] = (uint8_t)vacc;
+    if (mfill > 0) mrow[mpos] = (uint8_t)macc;
+}
+
+// Packed -> dense int8, one thread per (row, group).
+__global__ void __launch_bounds__(256)
+decompress_kernel(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int rows, int cols,
+                  int N, int M, int bits, int vstride, int mstride, int8_t* __restrict__ Wq)
+{
+    const int groups = cols / M;
+    const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (long long)rows * groups) return;
+    const int row = (int)(id / groups), g = (int)(id % groups);
+    const int ib = (M == 4) ? 2 : 4;
+    const uint8_t* vrow = vals + (size_t)row * vstride;
+    const uint8_t* mrow = meta + (size_t)row * mstride;
+    int8_t out[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j = 0; j < N; ++j) {
+        const int e = g * N + j;
+        int q, off;
+        if (bits == 8) q = (int8_t)vrow[e];
+        else { int nib = (vrow[e >> 1] >> ((e & 1) * 4)) & 15; q = (nib ^ 8) - 8; }
+        if (ib == 2) off = (mrow[e >> 2] >> ((e & 3) * 2)) & 3;
+        else off = (mrow[e >> 1] >> ((e & 1) * 4)) & 15;
+        out[off & 7] = (int8_t)q;
+    }
+    int8_t* dst = Wq + (size_t)row * cols + (size_t)g * M;
+    for (int c = 0; c < M; ++c) dst[c] = out[c];
+}
+
+template <int N, int M, int BITS>
+void launch_wave(const float* W, int rows, int cols, int ldw, void* vals, void* meta, float* scales,
+                 int vstride, int mstride, hipStream_t st)
+{
+    hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS>), dim3((rows + 3) / 4), dim3(256), 0, st,
+                       W, rows, cols, ldw, (uint32_t*)vals, (uint32_t*)meta, scales, vstride / 4, mstride / 4);
+}
+
+}  // namespace
+
+int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, int bits,
+                    void* vals, void* meta, float* scales, hipStream_t st)
+{
+    const int ib = (M == 4) ? 2 : 4;
+    const size_t kc = (size_t)cols / M * N;
+    const int vstride = (int)((kc * bits + 7) / 8);
+    const int mstride = (int)((kc * ib + 7) / 8);
+    const bool aligned = ((uintptr_t)W % 16 == 0) && (ldw % 4 == 0) && ((uintptr_t)vals % 4 == 0) &&
+                         ((uintptr_t)meta % 4 == 0) && (kc * bits % 32 == 0) && (kc * ib % 32 == 0);
+    bool done = false;
+    begin_launch();
+    if (aligned) {
+        done = true;
+#define NM_CASE(n, m, b) else if (N == n && M == m && bits == b) launch_wave<n, m, b>(W, rows, cols, ldw, vals, meta, scales, vstride, mstride, st)
+        if (false) {}
+        NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4);
+        NM_CASE(1, 8, 8); NM_CASE(2, 8, 8); NM_CASE(4, 8, 8);
+        NM_CASE(1, 8, 4); NM_CASE(2, 8, 4); NM_CASE(4, 8, 4);
+        else done = false;
+#undef NM_CASE
+    }
+    if (!done)
+        hipLaunchKernelGGL(compress_generic_kernel, dim3((rows + 63) / 64), dim3(64), 0, st,
+                           W, rows, cols, ldw, N, M, bits, (uint8_t*)vals, (uint8_t*)meta, scales, vstride, mstride);
+    return launch_status();
+}
+
+int launch_decompress(const void* vals, const void* meta, int rows, int cols, int N, int M, int bits,
+                      int8_t* Wq, hipStream_t st)
+{
+    const int ib = (M == 4) ? 2 : 4;
+    const size_t kc = (size_t)cols / M * N;
+    const int vstride = (int)((kc * bits + 7) / 8);
+    const int mstride = (int)((kc * ib + 7) / 8);
+    const long long total = (long long)rows * (cols / M);
+    begin_launch();
+    hipLaunchKernelGGL(decompress_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const uint8_t*)vals, (const uint8_t*)meta, rows, cols, N, M, bits, vstride, mstride, Wq);
+    return launch_status();
+}
+
+}  // namespace nm

@@ -1,0 +1,68 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every declared
+symbol, sizes buffers like the oracle, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+import paper_2206_15014_amd as nm
+from paper_2206_15014_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "nm.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", header))
+    assert names >= {"nm_packed_sizes", "nm_compress", "nm_decompress_i8", "nm_gemm", "nm_status_string"}
+    lib = ctypes.CDLL(binding.library_path())
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+@pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (1, 4, 4), (2, 8, 4), (3, 4, 8), (7, 8, 4), (1, 8, 8)])
+def test_sizes_agree_with_oracle(N, M, bits):
+    for rows, cols in [(768, 768), (3072, 768), (1, M), (5, 3 * M), (1024, 4096)]:
+        assert nm.nm_packed_sizes(rows, cols, N, M, bits) == oracle.packed_sizes(rows, cols, N, M, bits)
+
+
+def test_bad_patterns_are_rejected():
+    for args, code in [((0, 8, 2, 4, 8), -2), ((8, 0, 2, 4, 8), -2), ((8, 8, 0, 4, 8), -3), ((8, 8, 4, 4, 8), -3),
+                       ((8, 8, 2, 5, 8), -3), ((8, 10, 2, 4, 8), -3), ((8, 8, 2, 4, 6), -4), ((8, 8, 2, 16, 8), -3)]:
+        with pytest.raises(nm.NMError) as e:
+            nm.nm_packed_sizes(*args)
+        assert e.value.code == code
+
+
+def test_entry_points_validate_before_launch():
+    lib = binding.raw()
+    P = 0x1000          # never dereferenced on the host; validation fails first
+    assert lib.nm_compress(None, 8, 8, 8, 2, 4, 8, P, P, P, None) == -1
+    assert lib.nm_compress(P, 8, 8, 4, 2, 4, 8, P, P, P, None) == -2          # ldw < cols
+    assert lib.nm_compress(P, 8, 8, 8, 2, 4, 5, P, P, P, None) == -4
+    assert lib.nm_compress(P + 2, 8, 8, 8, 2, 4, 8, P, P, P, None) == -6
+    assert lib.nm_decompress_i8(P, None, 8, 8, 2, 4, 8, P, None) == -1
+    g = lambda **k: lib.nm_gemm(*[k.get(n, d) for n, d in [
+        ("X", P), ("T", 4), ("K", 8), ("ldx", 8), ("s", 1.0), ("v", P), ("m", P), ("sc", P), ("O", 8), ("N", 2),
+        ("M", 4), ("bits", 8), ("bias", None), ("acc", P), ("out", None), ("dt", 0), ("ldo", 8), ("st", None)]])
+    assert g(X=None) == -1
+    assert g(T=0) == -2
+    assert g(ldx=4) == -2
+    assert g(ldo=4) == -2
+    assert g(N=4) == -3
+    assert g(K=6) == -3
+    assert g(bits=16) == -4
+    assert g(dt=3, out=P) == -5
+    assert g(dt=1) == -5                     # dtype set but no output buffer
+    assert g(out=P) == -5                    # output buffer but dtype none
+    assert g(acc=None) == -1                 # nothing to write
+    assert g(acc=P + 1) == -6
+
+
+def test_status_strings():
+    assert nm.nm_status_string(0) == "ok"
+    assert all(nm.nm_status_string(c) not in ("", "unknown status") for c in range(-7, 1))
+    assert nm.nm_status_string(-99) == "unknown status"

@@ -1,0 +1,292 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Bars: packed values / indices / scales and int32 accumulators bit-exact; fp32 output within
+1e-5 * (|acc| * s_act * s_w + |bias|); bf16 output within one bf16 step of the oracle's rounding.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2206_15014_amd as nm
+from paper_2206_15014_amd import synth
+from paper_2206_15014_amd.binding import NM_OUT_BF16, NM_OUT_F32, NM_OUT_NONE
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+FAST_SCHEMES = [(2, 4, 8), (1, 4, 8), (2, 4, 4), (1, 4, 4), (2, 8, 4), (2, 8, 8), (1, 8, 8), (1, 8, 4)]
+ALL_SCHEMES = FAST_SCHEMES + [(3, 4, 8), (3, 4, 4), (4, 8, 8), (4, 8, 4), (3, 8, 4), (5, 8, 8), (7, 8, 4)]
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def gpu_compress(W, N, M, bits, ldw=None):
+    Wt = torch.from_numpy(W).to(DEV)
+    if ldw is not None:
+        buf = torch.zeros((W.shape[0], ldw), dtype=torch.float32, device=DEV)
+        buf[:, :W.shape[1]] = Wt
+        Wt = buf[:, :W.shape[1]]
+    vals, meta, scales = nm.nm_compress(Wt, N, M, bits)
+    torch.cuda.synchronize()
+    return vals, meta, scales
+
+
+def assert_packed_equal(gpu, ref, what):
+    for name, g, r in zip(("values", "indices", "scales"), gpu, ref):
+        g = g.cpu().numpy()
+        assert g.shape == r.shape, (what, name, g.shape, r.shape)
+        if not np.array_equal(g, r):
+            bad = np.argwhere(g != r)
+            raise AssertionError("%s: %s differ at %d places, first %s: gpu %s ref %s"
+                                 % (what, name, len(bad), bad[0], g[tuple(bad[0])], r[tuple(bad[0])]))
+
+
+def bf16_order(bits):
+    b = bits.astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7FFF), b)
+
+
+def check_outputs(acc_ref, sx, scales_ref, bias, acc_gpu=None, f32_gpu=None, bf16_gpu=None, what=""):
+    ref_f32, ref_b16 = oracle.dequant(acc_ref, float(sx), scales_ref, bias)
+    if acc_gpu is not None:
+        assert np.array_equal(acc_gpu, acc_ref), "%s: int32 accumulators differ (%d places)" % (
+            what, np.count_nonzero(acc_gpu != acc_ref))
+    mag = np.abs(acc_ref).astype(np.float64) * float(sx) * scales_ref[None, :].astype(np.float64)
+    if bias is not None:
+        mag = mag + np.abs(bias)[None, :].astype(np.float64)
+    if f32_gpu is not None:
+        err = np.abs(f32_gpu.astype(np.float64) - ref_f32.astype(np.float64))
+        assert np.all(err <= 1e-5 * mag + 1e-37), "%s: fp32 output off, worst ratio %g" % (
+            what, np.max(err / (mag + 1e-37)))
+    if bf16_gpu is not None:
+        d = np.abs(bf16_order(bf16_gpu) - bf16_order(ref_b16))
+        assert d.max() <= 1, "%s: bf16 output more than one step off (max %d)" % (what, d.max())
+
+
+def run_gemm(Xq, sx, packed, O, N, M, bits, bias=None, want=("acc", "f32"), ldo=None):
+    vals, meta, scales = packed
+    X = torch.from_numpy(Xq).to(DEV)
+    T = Xq.shape[0]
+    ldo = ldo or O
+    b = None if bias is None else torch.from_numpy(bias).to(DEV)
+    res = {}
+    if "f32" in want or "acc" in want:
+        acc = torch.full((T, ldo), -7, dtype=torch.int32, device=DEV) if "acc" in want else None
+        out = torch.full((T, ldo), -7.0, dtype=torch.float32, device=DEV) if "f32" in want else None
+        nm.nm_gemm(X, float(sx), vals, meta, scales, O, N, M, bits, bias=b, acc=acc, out=out,
+                   out_dtype=NM_OUT_F32 if out is not None else NM_OUT_NONE, ldo=ldo)
+        torch.cuda.synchronize()
+        if acc is not None:
+            res["acc"] = acc.cpu().numpy()
+        if out is not None:
+            res["f32"] = out.cpu().numpy()
+    if "bf16" in want:
+        out = torch.zeros((T, ldo), dtype=torch.bfloat16, device=DEV)
+        nm.nm_gemm(X, float(sx), vals, meta, scales, O, N, M, bits, bias=b, out=out, out_dtype=NM_OUT_BF16, ldo=ldo)
+        torch.cuda.synchronize()
+        res["bf16"] = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    return res
+
+
+# ---- compress ---------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("N,M,bits", ALL_SCHEMES)
+@pytest.mark.parametrize("rows,cols", [(70, 768), (9, 4352), (5, 64), (3, 24), (130, 1024)])
+def test_compress_matches_oracle(N, M, bits, rows, cols):
+    if cols % M:
+        pytest.skip("width not a multiple of M")
+    say("compress", N, M, bits, rows, cols)
+    rng = np.random.default_rng([N, M, bits, rows, cols])
+    W = (rng.standard_normal((rows, cols)) * 0.02).astype(np.float32)
+    W[rows // 2, : cols // 2] = 0.0
+    ref = oracle.compress(W, N, M, bits)
+    assert_packed_equal(gpu_compress(W, N, M, bits), ref, "contiguous")
+    assert_packed_equal(gpu_compress(W, N, M, bits, ldw=cols + 12), ref, "strided")
+
+
+@pytest.mark.parametrize("N,M,bits", FAST_SCHEMES + [(3, 4, 8), (4, 8, 4)])
+def test_compress_degenerate_rows(N, M, bits):
+    say("compress degenerate", N, M, bits)
+    for K in (64, 256):
+        W = synth.structured_weight_cases(K)
+        assert_packed_equal(gpu_compress(W, N, M, bits), oracle.compress(W, N, M, bits), "K=%d" % K)
+
+
+def test_compress_single_group_rows():
+    for N, M, bits in [(2, 4, 8), (1, 4, 4), (2, 8, 4), (1, 8, 8)]:
+        W = np.array([[0.5, -1.0, 0.25, 1.0, -0.125, 0.0, 0.75, -0.75][:M]], np.float32)
+        assert_packed_equal(gpu_compress(W, N, M, bits), oracle.compress(W, N, M, bits), "K=M")
+
+
+def test_decompress_round_trip():
+    rng = np.random.default_rng(5)
+    for N, M, bits in ALL_SCHEMES:
+        W = (rng.standard_normal((19, 16 * M)) * 0.02).astype(np.float32)
+        vals, meta, _ = oracle.compress(W, N, M, bits)
+        out = nm.nm_decompress_i8(torch.from_numpy(vals).to(DEV), torch.from_numpy(meta).to(DEV), 19, 16 * M, N, M, bits)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), oracle.decompress(vals, meta, 19, 16 * M, N, M, bits))
+
+
+# ---- GEMM, small shapes spanning several tiles with ragged edges ------------------------------
+
+def small_case(N, M, bits, T, K, O, seed, with_bias=True):
+    rng = np.random.default_rng([N, M, bits, T, K, O, seed])
+    W = (rng.standard_normal((O, K)) * 0.02).astype(np.float32)
+    Xq, sx = synth.quantize_activations(rng.standard_normal((T, K)).astype(np.float32))
+    bias = (rng.standard_normal(O) * 0.02).astype(np.float32) if with_bias else None
+    ref = oracle.compress(W, N, M, bits)
+    acc_ref = oracle.gemm_sparse(Xq, ref[0], ref[1], O, N, M, bits)
+    return W, Xq, sx, bias, ref, acc_ref
+
+
+@pytest.mark.parametrize("tile", ["0", "1", "2", "3"])
+@pytest.mark.parametrize("N,M,bits", FAST_SCHEMES)
+def test_gemm_mfma_path_small(N, M, bits, tile):
+    say("gemm small", N, M, bits, "tile", tile)
+    os.environ["NM_GEMM_TILE"] = tile
+    try:
+        for T, K, O in [(200, 256, 136), (129, 128, 260), (16, 384, 64)]:
+            W, Xq, sx, bias, ref, acc_ref = small_case(N, M, bits, T, K, O, 1)
+            packed = gpu_compress(W, N, M, bits)
+            assert_packed_equal(packed, ref, "compress")
+            res = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("acc", "f32", "bf16"))
+            check_outputs(acc_ref, sx, ref[2], bias, res["acc"], res["f32"], res["bf16"], what="T%d K%d O%d" % (T, K, O))
+    finally:
+        os.environ.pop("NM_GEMM_TILE", None)
+
+
+@pytest.mark.parametrize("N,M,bits", ALL_SCHEMES)
+def test_gemm_generic_path_odd_shapes(N, M, bits):
+    say("gemm generic", N, M, bits)
+    for T, K, O in [(1, M, 1), (7, 3 * M, 5), (33, 40, 18), (3, 136, 129)]:
+        if K % M:
+            continue
+        W, Xq, sx, bias, ref, acc_ref = small_case(N, M, bits, T, K, O, 2)
+        packed = gpu_compress(W, N, M, bits)
+        assert_packed_equal(packed, ref, "compress")
+        res = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("acc", "f32", "bf16"))
+        check_outputs(acc_ref, sx, ref[2], bias, res["acc"], res["f32"], res["bf16"], what="T%d K%d O%d" % (T, K, O))
+
+
+def test_gemm_padded_output_rows_and_no_bias():
+    W, Xq, sx, _, ref, acc_ref = small_case(2, 4, 8, 150, 256, 128, 3, with_bias=False)
+    packed = gpu_compress(W, 2, 4, 8)
+    res = run_gemm(Xq, sx, packed, 128, 2, 4, 8, None, want=("acc", "f32", "bf16"), ldo=160)
+    assert np.all(res["acc"][:, 128:] == -7) and np.all(res["f32"][:, 128:] == -7.0)   # padding untouched
+    check_outputs(acc_ref, sx, ref[2], None, res["acc"][:, :128], res["f32"][:, :128], res["bf16"][:, :128])
+
+
+def test_gemm_extreme_codes_do_not_overflow():
+    K, O, T = 4096, 16, 16
+    W = np.ones((O, K), np.float32)
+    Xq = np.full((T, K), -127, np.int8)
+    packed = gpu_compress(W, 2, 4, 8)
+    res = run_gemm(Xq, 1.0, packed, O, 2, 4, 8, None, want=("acc",))
+    assert np.all(res["acc"] == -127 * 127 * (K // 2))
+
+
+def test_sparse_product_equals_dense_product_on_gpu():
+    W, Xq, sx, _, ref, acc_ref = small_case(2, 4, 8, 256, 512, 256, 4, with_bias=False)
+    packed = gpu_compress(W, 2, 4, 8)
+    Wq = nm.nm_decompress_i8(packed[0], packed[1], 256, 512, 2, 4, 8)
+    dense = (torch.from_numpy(Xq).to(DEV).float() @ Wq.float().T).round().to(torch.int32)   # exact: |sum| < 2^24
+    res = run_gemm(Xq, sx, packed, 256, 2, 4, 8, None, want=("acc",))
+    assert np.array_equal(res["acc"], dense.cpu().numpy())
+
+
+# ---- the five workloads -----------------------------------------------------------------------
+
+def test_config1_full():
+    g, W, Xq, sx = synth.config1_tensors()
+    ref = oracle.compress(W, g.N, g.M, g.bits)
+    packed = gpu_compress(W, g.N, g.M, g.bits)
+    assert_packed_equal(packed, ref, "config 1")
+    acc_ref = oracle.gemm_sparse(Xq, ref[0], ref[1], g.O, g.N, g.M, g.bits)
+    res = run_gemm(Xq, sx, packed, g.O, g.N, g.M, g.bits, None, want=("acc", "f32", "bf16"))
+    check_outputs(acc_ref, sx, ref[2], None, res["acc"], res["f32"], res["bf16"], what="config 1")
+
+
+def sampled_tokens(T, n=72, seed=0):
+    rng = np.random.default_rng(seed)
+    edge = np.array([0, 1, 15, 16, 63, 64, 127, 128, T - 129, T - 128, T - 17, T - 2, T - 1])
+    return np.unique(np.concatenate([edge[(edge >= 0) & (edge < T)], rng.integers(0, T, size=n)]))
+
+
+def full_size_case(g):
+    """Whole compress compared byte for byte; GEMM compared on sampled token rows, which the
+    oracle computes one by one, in the launch configuration the library picks for the full size."""
+    say("full size", g)
+    W = synth.weights(g)
+    Xq, sx = synth.activations(g)
+    bias = synth.bias(g)
+    ref = oracle.compress(W, g.N, g.M, g.bits)
+    packed = gpu_compress(W, g.N, g.M, g.bits)
+    assert_packed_equal(packed, ref, g.name)
+    rows = sampled_tokens(g.T, seed=g.seed[-1])
+    acc_ref = oracle.gemm_sparse(Xq[rows], ref[0], ref[1], g.O, g.N, g.M, g.bits)
+    res = run_gemm(Xq, sx, packed, g.O, g.N, g.M, g.bits, bias, want=("acc", "f32", "bf16"))
+    check_outputs(acc_ref, sx, ref[2], bias, res["acc"][rows], res["f32"][rows], res["bf16"][rows], what=str(g))
+    # every output element was written (the buffers were pre-filled with a sentinel)
+    assert not np.any(res["f32"] == -7.0) or np.count_nonzero(res["f32"] == -7.0) < 4
+
+
+@pytest.mark.parametrize("i", range(4))
+def test_config2_bert_base_2of4_int8(i):
+    full_size_case(synth.config2()[i])
+
+
+@pytest.mark.parametrize("i", range(4))
+def test_config3_bert_large_2of4_int8(i):
+    full_size_case(synth.config3()[i])
+
+
+@pytest.mark.parametrize("i", range(8))
+def test_config4_int4_1of4_and_2of8(i):
+    full_size_case(synth.config4()[i])
+
+
+def test_config5_heterogeneous_encoder_back_to_back():
+    gs = synth.config5()
+    say("config 5 schemes", [(g.N, g.M, g.bits) for g in gs])
+    # one X per distinct reduction width (768 / 3072) keeps host memory and time small; weights differ per GEMM
+    acts = {}
+    for g in gs:
+        if g.K not in acts:
+            acts[g.K] = synth.activations(g)
+    stream = torch.cuda.current_stream()
+    jobs = []
+    for g in gs:
+        W = synth.weights(g)
+        ref = oracle.compress(W, g.N, g.M, g.bits)
+        packed = nm.nm_compress(torch.from_numpy(W).to(DEV), g.N, g.M, g.bits)
+        Xq, sx = acts[g.K]
+        X = torch.from_numpy(Xq).to(DEV)
+        acc = torch.empty((g.T, g.O), dtype=torch.int32, device=DEV)
+        out = torch.empty((g.T, g.O), dtype=torch.bfloat16, device=DEV)
+        jobs.append((g, ref, packed, X, sx, acc, out))
+    torch.cuda.synchronize()
+    for g, ref, packed, X, sx, acc, out in jobs:          # all 48 launches back to back on one stream
+        nm.nm_gemm(X, float(sx), *packed, g.O, g.N, g.M, g.bits, acc=acc, out=out, out_dtype=NM_OUT_BF16, stream=stream)
+    torch.cuda.synchronize()
+    for g, ref, packed, X, sx, acc, out in jobs:
+        assert_packed_equal(packed, ref, str(g))
+        rows = sampled_tokens(g.T, n=24, seed=g.seed[1] * 4 + g.seed[2])
+        Xq = acts[g.K][0]
+        acc_ref = oracle.gemm_sparse(Xq[rows], ref[0], ref[1], g.O, g.N, g.M, g.bits)
+        check_outputs(acc_ref, sx, ref[2], None, acc.cpu().numpy()[rows], None,
+                      out.view(torch.int16).cpu().numpy().view(np.uint16)[rows], what=str(g))
+
+
+def test_results_do_not_depend_on_repetition():
+    g = synth.config2()[3]
+    W, (Xq, sx) = synth.weights(g), synth.activations(g)
+    packed = gpu_compress(W, g.N, g.M, g.bits)
+    a = run_gemm(Xq, sx, packed, g.O, g.N, g.M, g.bits, None, want=("acc",))["acc"]
+    b = run_gemm(Xq, sx, packed, g.O, g.N, g.M, g.bits, None, want=("acc",))["acc"]
+    assert np.array_equal(a, b)
