@@ -22,103 +22,30 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "nm_internal.h"
+#include "nm_gemm_common.h"
 
 namespace nm {
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v8i __attribute__((ext_vector_type(8)));
-
 // ---------------------------------------------------------------------------------------------
-// Weight units.  A unit is the slice of one packed weight row that covers 32 consecutive input
-// columns: what one lane feeds to one sparse MFMA.
-// ---------------------------------------------------------------------------------------------
-template <int N, int M, int BITS>
-struct Unit {
-    static constexpr int IB = (M == 4) ? 2 : 4;
-    static constexpr int EPU = 32 / M * N;          // kept entries per unit
-    static constexpr int VBYTES = EPU * BITS / 8;   // packed value bytes per unit (2, 4, 8 or 16)
-    static constexpr int MBYTES = EPU * IB / 8;     // packed index bytes per unit (2 or 4)
-    static constexpr bool IDENTITY = (N == 2 && M == 4 && BITS == 8);
-
-    struct Raw {
-        uint32_t v[(VBYTES + 3) / 4];
-        uint32_t m;
-    };
-
-    static __device__ __forceinline__ Raw load(const uint8_t* __restrict__ vrow, const uint8_t* __restrict__ mrow, int unit)
-    {
-        Raw r;
-        const uint8_t* pv = vrow + (size_t)unit * VBYTES;
-        if constexpr (VBYTES == 16) {
-            uint4 t = *reinterpret_cast<const uint4*>(pv);
-            r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
-        } else if constexpr (VBYTES == 8) {
-            uint2 t = *reinterpret_cast<const uint2*>(pv);
-            r.v[0] = t.x; r.v[1] = t.y;
-        } else if constexpr (VBYTES == 4) {
-            r.v[0] = *reinterpret_cast<const uint32_t*>(pv);
-        } else {
-            r.v[0] = *reinterpret_cast<const uint16_t*>(pv);
-        }
-        const uint8_t* pm = mrow + (size_t)unit * MBYTES;
-        if constexpr (MBYTES == 4) r.m = *reinterpret_cast<const uint32_t*>(pm);
-        else r.m = *reinterpret_cast<const uint16_t*>(pm);
-        return r;
-    }
-
-    // Packed unit -> MFMA operand: 16 int8 codes (zero where nothing is kept) and 16 2-bit positions.
-    static __device__ __forceinline__ void decode(const Raw& r, v4i& codes, int& pos)
-    {
-        if constexpr (IDENTITY) {
-            codes = v4i{(int)r.v[0], (int)r.v[1], (int)r.v[2], (int)r.v[3]};
-            pos = (int)r.m;
-        } else {
-            uint32_t hv[4] = {0u, 0u, 0u, 0u};
-            uint32_t hp = 0u;
-#pragma unroll
-            for (int e = 0; e < EPU; ++e) {
-                uint32_t q;
-                if constexpr (BITS == 8) {
-                    q = (r.v[e / 4] >> (8 * (e % 4))) & 0xFFu;
-                } else {
-                    uint32_t nib = (r.v[e / 8] >> (4 * (e % 8))) & 0xFu;
-                    q = ((nib ^ 8u) - 8u) & 0xFFu;                 // sign-extend 4 -> 8 bits
-                }
-                const uint32_t off = (r.m >> (e * IB)) & (uint32_t)(M - 1);
-                const int g = e / N, j = e % N;                    // group inside the unit, rank inside the group
-                if constexpr (M == 4) {
-                    const int he = 2 * g + j;                      // slot j of subgroup g
-                    hv[he / 4] |= q << (8 * (he % 4));
-                    hp |= off << (2 * he);
-                } else {
-                    const uint32_t byte = 2u * (off >> 2) + (uint32_t)j;   // subgroup 2g + off/4, slot j
-                    hv[g] |= q << (8u * byte);
-                    hp |= (off & 3u) << (2u * (4u * (uint32_t)g + byte));
-                }
-            }
-            codes = v4i{(int)hv[0], (int)hv[1], (int)hv[2], (int)hv[3]};
-            pos = (int)hp;
-        }
-    }
-};
-
-__device__ __forceinline__ uint32_t bf16_rne(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-
-// ---------------------------------------------------------------------------------------------
-// Sparse-MFMA GEMM.  One workgroup (4 wavefronts) computes a BT-token x BO-row output tile;
-// K advances 128 input columns per step through two LDS stages:
-//   X tile   BT rows x 128 bytes (row stride 144 to spread the fragment reads over the banks),
-//   codes    BO rows x 64 bytes  (row stride 80),
+// Sparse-MFMA GEMM.  One workgroup of WAVES_T x WAVES_O wavefronts computes a BT-token x BO-row
+// output tile; K advances 128 input columns per step.
+//
+// Data path per step:  global --(16-byte loads, DEPTH steps ahead, parked in registers)-->
+// registers --(decode of the weight units)--> LDS ring of STAGES stages --> MFMA fragments.
+//   X tile    BT rows x 128 bytes (row stride 144 to spread the fragment reads over the banks),
+//   codes     BO rows x 64 bytes  (row stride 80),
 //   positions BO rows x 16 bytes.
-// Global loads of step k+1 are issued before the MFMAs of step k and parked in registers.
+// At these layer shapes the first touch of X comes from HBM, about a microsecond away, while
+// one step's MFMAs take a fraction of that: the register ring keeps DEPTH steps of loads in
+// flight per wavefront so the stream is bound by bandwidth rather than by one latency per step.
+// With three LDS stages the stores of step k+2 are issued before the MFMAs of step k and only
+// one barrier per step is needed; with two stages they follow the MFMAs.
+//
 // Workgroups are numbered so that those sharing an XCD (blockIdx % 8) cover a contiguous token
 // range: each XCD's L2 then holds one slice of X plus the (small) packed weight matrix.
 // Requires K % 128 == 0, O % 4 == 0, 16-byte aligned X / ldx / values, ldo % 4 == 0.
@@ -129,18 +56,20 @@ struct TileGeom {
     static constexpr int STAGE = BT * XS + BO * WVS + BO * WMS;
 };
 
-template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O>
-__global__ void __launch_bounds__(256)
+template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int DEPTH, int STAGES>
+__global__ void __launch_bounds__(64 * WAVES_T * WAVES_O)
 gemm_smfmac_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
 {
     using U = Unit<N, M, BITS>;
     using G = TileGeom<BT, BO>;
-    static_assert(WAVES_T * WAVES_O == 4, "four wavefronts per workgroup");
+    constexpr int NT = 64 * WAVES_T * WAVES_O;
     constexpr int WT = BT / WAVES_T, WO = BO / WAVES_O;
     constexpr int FT = WT / 16, FO = WO / 16;
-    constexpr int XCH = BT * 8 / 256;          // 16-byte X chunks per thread per step
-    constexpr int WU = BO * 4 / 256;           // weight units per thread per step
-    static_assert(XCH >= 1 && WU >= 1, "tile too small for 256 threads");
+    static_assert(WT % 16 == 0 && WO % 16 == 0, "wave tile must be whole 16x16 fragments");
+    static_assert(STAGES == 2 || STAGES == 3, "two or three LDS stages");
+    constexpr int XCH = (BT * 8 + NT - 1) / NT;   // 16-byte X chunks per thread per step
+    constexpr int WU = (BO * 4 + NT - 1) / NT;    // weight units per thread per step
+    constexpr bool XFULL = (BT * 8) % NT == 0, WFULL = (BO * 4) % NT == 0;
 
     extern __shared__ __align__(16) uint8_t smem[];
 
@@ -156,11 +85,11 @@ gemm_smfmac_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
 
     const int nk = a.K >> 7;
 
-    // ---- global -> register staging -------------------------------------------------------
+    // ---- global -> register ring ------------------------------------------------------------
     const int8_t* xsrc[XCH];
 #pragma unroll
     for (int r = 0; r < XCH; ++r) {
-        const int c = tid + 256 * r;
+        const int c = min(tid + NT * r, BT * 8 - 1);
         const int row = min(t0 + (c >> 3), a.tokens - 1);
         xsrc[r] = a.X + (size_t)row * a.ldx + (c & 7) * 16;
     }
@@ -168,34 +97,39 @@ gemm_smfmac_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     const uint8_t* wmsrc[WU];
 #pragma unroll
     for (int r = 0; r < WU; ++r) {
-        const int u = tid + 256 * r;
+        const int u = min(tid + NT * r, BO * 4 - 1);
         const int row = min(o0 + (u >> 2), a.O - 1);
-        wvsrc[r] = a.vals + (size_t)row * a.vstride;
-        wmsrc[r] = a.meta + (size_t)row * a.mstride;
+        wvsrc[r] = a.vals + (size_t)row * a.vstride + (u & 3) * U::VBYTES;
+        wmsrc[r] = a.meta + (size_t)row * a.mstride + (u & 3) * U::MBYTES;
     }
-    v4i xr[XCH];
-    typename U::Raw wr[WU];
+    v4i xr[DEPTH][XCH];
+    typename U::Raw wr[DEPTH][WU];
 
-    auto gload = [&](int kt) {
+    auto gload = [&](int kt, auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value;
 #pragma unroll
-        for (int r = 0; r < XCH; ++r) xr[r] = *reinterpret_cast<const v4i*>(xsrc[r] + (size_t)kt * 128);
+        for (int r = 0; r < XCH; ++r) xr[slot][r] = *reinterpret_cast<const v4i*>(xsrc[r] + (size_t)kt * 128);
 #pragma unroll
-        for (int r = 0; r < WU; ++r) wr[r] = U::load(wvsrc[r], wmsrc[r], kt * 4 + ((tid + 256 * r) & 3));
+        for (int r = 0; r < WU; ++r) wr[slot][r] = U::load(wvsrc[r], wmsrc[r], kt * 4);
     };
-    auto sstore = [&](int stage) {
+    auto sstore = [&](int stage, auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value;
         uint8_t* base = smem + stage * G::STAGE;
 #pragma unroll
         for (int r = 0; r < XCH; ++r) {
-            const int c = tid + 256 * r;
-            *reinterpret_cast<v4i*>(base + (c >> 3) * G::XS + (c & 7) * 16) = xr[r];
+            const int c = tid + NT * r;
+            if (XFULL || c < BT * 8)
+                *reinterpret_cast<v4i*>(base + (c >> 3) * G::XS + (c & 7) * 16) = xr[slot][r];
         }
 #pragma unroll
         for (int r = 0; r < WU; ++r) {
-            const int u = tid + 256 * r;
-            v4i codes; int pos;
-            U::decode(wr[r], codes, pos);
-            *reinterpret_cast<v4i*>(base + BT * G::XS + (u >> 2) * G::WVS + (u & 3) * 16) = codes;
-            *reinterpret_cast<int*>(base + BT * G::XS + BO * G::WVS + (u >> 2) * G::WMS + (u & 3) * 4) = pos;
+            const int u = tid + NT * r;
+            if (WFULL || u < BO * 4) {
+                v4i codes; int pos;
+                U::decode(wr[slot][r], codes, pos);
+                *reinterpret_cast<v4i*>(base + BT * G::XS + (u >> 2) * G::WVS + (u & 3) * 16) = codes;
+                *reinterpret_cast<int*>(base + BT * G::XS + BO * G::WVS + (u >> 2) * G::WMS + (u & 3) * 4) = pos;
+            }
         }
     };
 
@@ -206,73 +140,66 @@ gemm_smfmac_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         for (int ft = 0; ft < FT; ++ft) acc[fo][ft] = v4i{0, 0, 0, 0};
 
     const int li = lane & 15, lg = lane >> 4;
+    const int frag_x = (wt * WT + li) * G::XS + 16 * lg;
+    const int frag_v = BT * G::XS + (wo * WO + li) * G::WVS + 16 * lg;
+    const int frag_p = BT * G::XS + BO * G::WVS + (wo * WO + li) * G::WMS + 4 * lg;
 
-    gload(0);
-    sstore(0);
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) gload(kt + 1);
-
-        const uint8_t* base = smem + (kt & 1) * G::STAGE;
-        const uint8_t* xs = base + (wt * WT + li) * G::XS + 16 * lg;
-        const uint8_t* wv = base + BT * G::XS + (wo * WO + li) * G::WVS + 16 * lg;
-        const uint8_t* wm = base + BT * G::XS + BO * G::WVS + (wo * WO + li) * G::WMS + 4 * lg;
-
+    auto compute = [&](int stage) {
+        const uint8_t* base = smem + stage * G::STAGE;
         v8i bfr[FT];
 #pragma unroll
         for (int ft = 0; ft < FT; ++ft) {
-            const v4i lo = *reinterpret_cast<const v4i*>(xs + ft * 16 * G::XS);
-            const v4i hi = *reinterpret_cast<const v4i*>(xs + ft * 16 * G::XS + 64);
+            const v4i lo = *reinterpret_cast<const v4i*>(base + frag_x + ft * 16 * G::XS);
+            const v4i hi = *reinterpret_cast<const v4i*>(base + frag_x + ft * 16 * G::XS + 64);
             bfr[ft] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         }
 #pragma unroll
         for (int fo = 0; fo < FO; ++fo) {
-            const v4i codes = *reinterpret_cast<const v4i*>(wv + fo * 16 * G::WVS);
-            const int pos = *reinterpret_cast<const int*>(wm + fo * 16 * G::WMS);
+            const v4i codes = *reinterpret_cast<const v4i*>(base + frag_v + fo * 16 * G::WVS);
+            const int pos = *reinterpret_cast<const int*>(base + frag_p + fo * 16 * G::WMS);
 #pragma unroll
             for (int ft = 0; ft < FT; ++ft)
                 acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(codes, bfr[ft], acc[fo][ft], pos, 0, 0);
         }
+    };
 
-        if (kt + 1 < nk) sstore((kt + 1) & 1);
-        __syncthreads();
-    }
+    // Register slot of step j is j % DEPTH; LDS stage of step j is j % STAGES.  The host only
+    // picks a DEPTH that divides the step count, and loads past the last step re-read the last
+    // step (in bounds, never consumed): the loop body is then free of data-dependent branches,
+    // which lets the compiler count exactly how many younger loads may stay in flight at each
+    // wait instead of draining the queue.
+    constexpr int LEAD = STAGES - 1;           // steps resident in LDS ahead of the one being computed
+    const int last = nk - 1;
+    int_for<DEPTH>([&](auto d) { gload(min((int)d.value, last), d); });
+    int_for<LEAD>([&](auto j) {
+        using Slot = std::integral_constant<int, j.value % DEPTH>;
+        sstore(j.value % STAGES, Slot{});
+        gload(min((int)j.value + DEPTH, last), Slot{});
+    });
+    __syncthreads();
 
-    // ---- epilogue: Eq. 4 with offset 0 on the product of two quantised operands --------------
-#pragma unroll
-    for (int fo = 0; fo < FO; ++fo) {
-        const int o = o0 + wo * WO + fo * 16 + 4 * lg;
-        if (o >= a.O) continue;
-        const float4 sw = *reinterpret_cast<const float4*>(a.scales + o);
-        const float sc[4] = {a.act_scale * sw.x, a.act_scale * sw.y, a.act_scale * sw.z, a.act_scale * sw.w};
-        float bs[4] = {0.f, 0.f, 0.f, 0.f};
-        if (a.bias) {
-            const float4 b = *reinterpret_cast<const float4*>(a.bias + o);
-            bs[0] = b.x; bs[1] = b.y; bs[2] = b.z; bs[3] = b.w;
-        }
-#pragma unroll
-        for (int ft = 0; ft < FT; ++ft) {
-            const int t = t0 + wt * WT + ft * 16 + li;
-            if (t >= a.tokens) continue;
-            const v4i c = acc[fo][ft];
-            const size_t at = (size_t)t * a.ldo + o;
-            if (a.acc) *reinterpret_cast<v4i*>(a.acc + at) = c;
-            if (a.out_dtype != 0) {
-                float y[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) y[r] = (float)c[r] * sc[r] + bs[r];
-                if (a.out_dtype == 1) {
-                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + at) = make_float4(y[0], y[1], y[2], y[3]);
-                } else {
-                    uint2 p;
-                    p.x = bf16_rne(y[0]) | (bf16_rne(y[1]) << 16);
-                    p.y = bf16_rne(y[2]) | (bf16_rne(y[3]) << 16);
-                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = p;
-                }
+    int stage_c = 0;                            // kt % STAGES
+    int stage_s = LEAD % STAGES;                // (kt + LEAD) % STAGES
+    for (int kt0 = 0; kt0 < nk; kt0 += DEPTH) {
+        int_for<DEPTH>([&](auto d) {
+            const int kt = kt0 + d.value;
+            using Slot = std::integral_constant<int, (d.value + LEAD) % DEPTH>;
+            if constexpr (STAGES == 3) {
+                sstore(stage_s, Slot{});
+                gload(min(kt + LEAD + DEPTH, last), Slot{});
+                compute(stage_c);
+            } else {
+                compute(stage_c);
+                sstore(stage_s, Slot{});
+                gload(min(kt + LEAD + DEPTH, last), Slot{});
             }
-        }
+            __syncthreads();
+            stage_c = (stage_c + 1 == STAGES) ? 0 : stage_c + 1;
+            stage_s = (stage_s + 1 == STAGES) ? 0 : stage_s + 1;
+        });
     }
+
+    store_tile<FO, FT>(a, acc, o0 + wo * WO, t0 + wt * WT, li, lg);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -307,15 +234,39 @@ gemm_generic_kernel(const GemmArgs a)
     }
 }
 
-template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O>
+template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int DEPTH, int STAGES>
 void launch_tile(const GemmArgs& a, hipStream_t st)
 {
+    if constexpr (DEPTH > 1) {
+        if ((a.K / 128) % DEPTH != 0) {         // the kernel's ring needs a whole number of rounds
+            launch_tile<N, M, BITS, BT, BO, WAVES_T, WAVES_O, 1, STAGES>(a, st);
+            return;
+        }
+    }
     const int tiles_t = (a.tokens + BT - 1) / BT, tiles_o = (a.O + BO - 1) / BO;
     const int n_tiles = tiles_t * tiles_o;
     const int grid = 8 * ((n_tiles + 7) / 8);
-    const size_t lds = 2 * (size_t)TileGeom<BT, BO>::STAGE;
-    hipLaunchKernelGGL((gemm_smfmac_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O>), dim3(grid), dim3(256), lds, st,
-                       a, tiles_o, n_tiles);
+    const size_t lds = STAGES * (size_t)TileGeom<BT, BO>::STAGE;
+    auto kern = gemm_smfmac_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O, DEPTH, STAGES>;
+    if (lds > 64 * 1024) {
+        static bool raised = false;             // per instantiation; the attribute is sticky
+        if (!raised) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WAVES_T * WAVES_O), lds, st, a, tiles_o, n_tiles);
+}
+
+// Ring depth: the deepest of 4, 3, 2, 1 that divides the number of 128-column steps.
+template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES>
+void launch_depth(const GemmArgs& a, hipStream_t st)
+{
+    const int nk = a.K / 128;
+    if (nk % 4 == 0) launch_tile<N, M, BITS, BT, BO, WAVES_T, WAVES_O, 4, STAGES>(a, st);
+    else if (nk % 3 == 0) launch_tile<N, M, BITS, BT, BO, WAVES_T, WAVES_O, 3, STAGES>(a, st);
+    else if (nk % 2 == 0) launch_tile<N, M, BITS, BT, BO, WAVES_T, WAVES_O, 2, STAGES>(a, st);
+    else launch_tile<N, M, BITS, BT, BO, WAVES_T, WAVES_O, 1, STAGES>(a, st);
 }
 
 template <int N, int M, int BITS>
@@ -326,9 +277,31 @@ void launch_pattern(const GemmArgs& a, hipStream_t st, int tile_cfg)
     const long long big = (long long)((a.tokens + 127) / 128) * ((a.O + 127) / 128);
     if (tile_cfg == 0) tile_cfg = (big >= 384) ? 1 : 2;
     switch (tile_cfg) {
-        case 1: launch_tile<N, M, BITS, 128, 128, 2, 2>(a, st); break;
-        case 2: launch_tile<N, M, BITS, 128, 64, 2, 2>(a, st); break;
-        default: launch_tile<N, M, BITS, 64, 64, 2, 2>(a, st); break;
+        case 1: launch_depth<N, M, BITS, 128, 128, 2, 2, 2>(a, st); break;
+        case 2: launch_depth<N, M, BITS, 128, 64, 2, 2, 2>(a, st); break;
+        case 3: launch_depth<N, M, BITS, 64, 64, 2, 2, 2>(a, st); break;
+        default:
+            if constexpr (N == 2 && M == 4 && BITS == 8) {
+                switch (tile_cfg) {
+                    case 4: launch_tile<N, M, BITS, 128, 128, 2, 2, 1, 2>(a, st); break;
+                    case 5: launch_depth<N, M, BITS, 128, 128, 2, 2, 3>(a, st); break;
+                    case 6: launch_tile<N, M, BITS, 128, 128, 2, 2, 6, 2>(a, st); break;
+                    case 7: launch_tile<N, M, BITS, 128, 128, 2, 2, 2, 2>(a, st); break;
+                    case 8: launch_depth<N, M, BITS, 128, 96, 2, 2, 3>(a, st); break;
+                    case 9: launch_depth<N, M, BITS, 128, 96, 2, 2, 2>(a, st); break;
+                    case 10: launch_depth<N, M, BITS, 64, 96, 2, 2, 3>(a, st); break;
+                    case 11: launch_depth<N, M, BITS, 64, 96, 2, 2, 2>(a, st); break;
+                    case 12: launch_depth<N, M, BITS, 128, 192, 2, 2, 2>(a, st); break;
+                    case 13: launch_depth<N, M, BITS, 128, 192, 2, 4, 2>(a, st); break;
+                    case 14: launch_depth<N, M, BITS, 256, 128, 4, 2, 2>(a, st); break;
+                    case 15: launch_depth<N, M, BITS, 128, 128, 2, 4, 3>(a, st); break;
+                    case 16: launch_depth<N, M, BITS, 64, 64, 2, 2, 3>(a, st); break;
+                    case 17: launch_depth<N, M, BITS, 64, 128, 2, 2, 3>(a, st); break;
+                    default: launch_depth<N, M, BITS, 128, 128, 2, 2, 2>(a, st); break;
+                }
+            } else {
+                launch_depth<N, M, BITS, 128, 128, 2, 2, 2>(a, st);
+            }
     }
 }
 
@@ -343,7 +316,12 @@ int launch_gemm(const GemmArgs& a, hipStream_t st)
     begin_launch();
     if (fast) {
         const char* env = getenv("NM_GEMM_TILE");   // tuning / test override of the tile choice
-        const int tile_cfg = env ? atoi(env) : 0;
+        int tile_cfg = env ? atoi(env) : 0;
+        // LDS-direct kernel first (tile_cfg 0 = its own choice, >= 100 = forced variant);
+        // 1..99 force the register-staged kernel below.
+        if ((tile_cfg == 0 || tile_cfg >= 100) && (uintptr_t)a.meta % 16 == 0 && launch_gemm_dma(a, st, tile_cfg))
+            return launch_status();
+        if (tile_cfg >= 100) tile_cfg = 0;
 #define NM_CASE(n, m, b) else if (a.N == n && a.M == m && a.bits == b) launch_pattern<n, m, b>(a, st, tile_cfg)
         if (false) {}
         NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4);

@@ -1,0 +1,189 @@
+// Device-side pieces shared by the nm_gemm kernels: MFMA operand types, the packed weight
+// "unit" (load + decode to the sparse-MFMA operand form), and small helpers.
+#ifndef NM_GEMM_COMMON_H
+#define NM_GEMM_COMMON_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <type_traits>
+
+namespace nm {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+
+// ---------------------------------------------------------------------------------------------
+// Weight units.  A unit is the slice of one packed weight row that covers 32 consecutive input
+// columns: what one lane feeds to one sparse MFMA.
+// ---------------------------------------------------------------------------------------------
+template <int N, int M, int BITS>
+struct Unit {
+    static constexpr int IB = (M == 4) ? 2 : 4;
+    static constexpr int EPU = 32 / M * N;          // kept entries per unit
+    static constexpr int VBYTES = EPU * BITS / 8;   // packed value bytes per unit (2, 4, 8 or 16)
+    static constexpr int MBYTES = EPU * IB / 8;     // packed index bytes per unit (2 or 4)
+    static constexpr bool IDENTITY = (N == 2 && M == 4 && BITS == 8);
+
+    struct Raw {
+        uint32_t v[(VBYTES + 3) / 4];
+        uint32_t m;
+    };
+
+    static __device__ __forceinline__ Raw load(const uint8_t* __restrict__ vrow, const uint8_t* __restrict__ mrow, int unit)
+    {
+        Raw r;
+        const uint8_t* pv = vrow + (size_t)unit * VBYTES;
+        if constexpr (VBYTES == 16) {
+            uint4 t = *reinterpret_cast<const uint4*>(pv);
+            r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+        } else if constexpr (VBYTES == 8) {
+            uint2 t = *reinterpret_cast<const uint2*>(pv);
+            r.v[0] = t.x; r.v[1] = t.y;
+        } else if constexpr (VBYTES == 4) {
+            r.v[0] = *reinterpret_cast<const uint32_t*>(pv);
+        } else {
+            r.v[0] = *reinterpret_cast<const uint16_t*>(pv);
+        }
+        const uint8_t* pm = mrow + (size_t)unit * MBYTES;
+        if constexpr (MBYTES == 4) r.m = *reinterpret_cast<const uint32_t*>(pm);
+        else r.m = *reinterpret_cast<const uint16_t*>(pm);
+        return r;
+    }
+
+    // Packed unit -> MFMA operand: 16 int8 codes (zero where nothing is kept) and 16 2-bit positions.
+    static __device__ __forceinline__ void decode(const Raw& r, v4i& codes, int& pos)
+    {
+        if constexpr (IDENTITY) {
+            codes = v4i{(int)r.v[0], (int)r.v[1], (int)r.v[2], (int)r.v[3]};
+            pos = (int)r.m;
+        } else {
+            uint32_t hv[4] = {0u, 0u, 0u, 0u};
+            uint32_t hp = 0u;
+#pragma unroll
+            for (int e = 0; e < EPU; ++e) {
+                uint32_t q;
+                if constexpr (BITS == 8) {
+                    q = (r.v[e / 4] >> (8 * (e % 4))) & 0xFFu;
+                } else {
+                    uint32_t nib = (r.v[e / 8] >> (4 * (e % 8))) & 0xFu;
+                    q = ((nib ^ 8u) - 8u) & 0xFFu;                 // sign-extend 4 -> 8 bits
+                }
+                const uint32_t off = (r.m >> (e * IB)) & (uint32_t)(M - 1);
+                const int g = e / N, j = e % N;                    // group inside the unit, rank inside the group
+                if constexpr (M == 4) {
+                    const int he = 2 * g + j;                      // slot j of subgroup g
+                    hv[he / 4] |= q << (8 * (he % 4));
+                    hp |= off << (2 * he);
+                } else {
+                    const uint32_t byte = 2u * (off >> 2) + (uint32_t)j;   // subgroup 2g + off/4, slot j
+                    hv[g] |= q << (8u * byte);
+                    hp |= (off & 3u) << (2u * (4u * (uint32_t)g + byte));
+                }
+            }
+            codes = v4i{(int)hv[0], (int)hv[1], (int)hv[2], (int)hv[3]};
+            pos = (int)hp;
+        }
+    }
+};
+
+// Compile-time counted loop: f(std::integral_constant<int, 0>{}) ... f(std::integral_constant<int, COUNT-1>{}).
+template <int COUNT, class F, int I = 0>
+__device__ __forceinline__ void int_for(F&& f)
+{
+    if constexpr (I < COUNT) {
+        f(std::integral_constant<int, I>{});
+        int_for<COUNT, F, I + 1>(static_cast<F&&>(f));
+    }
+}
+
+__device__ __forceinline__ uint32_t bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+
+// Epilogue shared by the MFMA kernels: Eq. 4 with offset 0 applied to the product of two quantised
+// operands.  acc[fo][ft] is the 16x16 accumulator fragment of weight rows o_base + fo*16 .. and
+// tokens t_base + ft*16 ..; lane (li, lg) holds rows 4*lg .. 4*lg+3 of token li.
+template <int FO, int FT, class Args>
+__device__ __forceinline__ void store_tile(const Args& a, const v4i (&acc)[FO][FT], int o_base, int t_base, int li, int lg)
+{
+#pragma unroll
+    for (int fo = 0; fo < FO; ++fo) {
+        const int o = o_base + fo * 16 + 4 * lg;
+        if (o >= a.O) continue;
+        const float4 sw = *reinterpret_cast<const float4*>(a.scales + o);
+        const float sc[4] = {a.act_scale * sw.x, a.act_scale * sw.y, a.act_scale * sw.z, a.act_scale * sw.w};
+        float bs[4] = {0.f, 0.f, 0.f, 0.f};
+        if (a.bias) {
+            const float4 b = *reinterpret_cast<const float4*>(a.bias + o);
+            bs[0] = b.x; bs[1] = b.y; bs[2] = b.z; bs[3] = b.w;
+        }
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft) {
+            const int t = t_base + ft * 16 + li;
+            if (t >= a.tokens) continue;
+            const v4i c = acc[fo][ft];
+            const size_t at = (size_t)t * a.ldo + o;
+            if (a.acc) *reinterpret_cast<v4i*>(a.acc + at) = c;
+            if (a.out_dtype != 0) {
+                float y[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) y[r] = (float)c[r] * sc[r] + bs[r];
+                if (a.out_dtype == 1) {
+                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + at) = make_float4(y[0], y[1], y[2], y[3]);
+                } else {
+                    uint2 p;
+                    p.x = bf16_rne(y[0]) | (bf16_rne(y[1]) << 16);
+                    p.y = bf16_rne(y[2]) | (bf16_rne(y[3]) << 16);
+                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = p;
+                }
+            }
+        }
+    }
+}
+
+// Same, with the row scales and biases already in registers (sw[fo], bw[fo] hold rows
+// o_base + fo*16 + 4*lg .. +3).
+template <int FO, int FT, class Args>
+__device__ __forceinline__ void store_tile_pre(const Args& a, const v4i (&acc)[FO][FT], const float4 (&sw)[FO], const float4 (&bw)[FO],
+                                               int o_base, int t_base, int li, int lg)
+{
+#pragma unroll
+    for (int fo = 0; fo < FO; ++fo) {
+        const int o = o_base + fo * 16 + 4 * lg;
+        if (o >= a.O) continue;
+        const float sc[4] = {a.act_scale * sw[fo].x, a.act_scale * sw[fo].y, a.act_scale * sw[fo].z, a.act_scale * sw[fo].w};
+        const float bs[4] = {bw[fo].x, bw[fo].y, bw[fo].z, bw[fo].w};
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft) {
+            const int t = t_base + ft * 16 + li;
+            if (t >= a.tokens) continue;
+            const v4i c = acc[fo][ft];
+            const size_t at = (size_t)t * a.ldo + o;
+            if (a.acc) *reinterpret_cast<v4i*>(a.acc + at) = c;
+            if (a.out_dtype != 0) {
+                float y[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) y[r] = (float)c[r] * sc[r] + bs[r];
+                if (a.out_dtype == 1) {
+                    *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + at) = make_float4(y[0], y[1], y[2], y[3]);
+                } else {
+                    uint2 p;
+                    p.x = bf16_rne(y[0]) | (bf16_rne(y[1]) << 16);
+                    p.y = bf16_rne(y[2]) | (bf16_rne(y[3]) << 16);
+                    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = p;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+}  // namespace nm
+
+#endif

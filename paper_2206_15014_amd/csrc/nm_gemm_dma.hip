@@ -1,0 +1,351 @@
+// nm_gemm, LDS-direct variant for gfx950: operands go global -> LDS with
+// global_load_lds_dwordx4 (no register staging, no LDS store instructions), through a ring of
+// STAGES stages, and the sparse MFMA reads its fragments from there.
+//
+// Why: at these layer shapes one workgroup per CU streams its X tile (first touch from HBM,
+// about a microsecond away) and its slice of the packed weights (from L2) at the CU's L1 fill
+// rate, which - not the MFMA pipe - bounds the kernel.  Keeping several stages of loads in
+// flight without spending registers or LDS-store issue slots is what the direct-to-LDS load is
+// for; the packed weight bytes travel in their compact form and are widened / re-encoded to the
+// MFMA operand in registers (Sec. 5.3: low-bit weights are widened for the ALUs).
+//
+// Stage layout (one 128-column K step).  A direct load writes 64 lanes x 16 bytes to 1 KB of
+// consecutive LDS in lane order, so every array is a sequence of 1 KB blocks and the layout
+// inside a block is chosen by which global chunk each lane fetches:
+//   X      [BT rows][128 B]; 16-byte chunk c of row r sits in slot c ^ ((r >> 1) & 7): eight
+//          consecutive lanes fetch one full 128-byte line, and the MFMA B-fragment reads
+//          (16 rows x one slot) spread over all banks;
+//   codes  [BO rows][RV B], RV = 4 units x packed value bytes per unit (64 B for 2:4 int8);
+//   index  [BO rows][16 B]  (patterns whose index bits fill 4 bytes per unit: N = 2).
+// Synchronisation per step: wait until this wavefront's own loads of the next step have landed
+// (s_waitcnt vmcnt with the count of younger loads), barrier (everyone's have, and everyone has
+// consumed the stage about to be refilled), issue the loads STAGES-1 steps ahead, read the next
+// step's fragments into registers, multiply the current one.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nm_internal.h"
+#include "nm_gemm_common.h"
+
+namespace nm {
+
+namespace {
+
+template <int N, int M, int BITS, int BT, int BO, int KU>
+struct DmaGeom {
+    using U = Unit<N, M, BITS>;
+    static constexpr int RV = 4 * U::VBYTES * KU;            // packed value bytes per row per stage
+    static constexpr int RM = 4 * U::MBYTES * KU;            // packed index bytes per row per stage
+    static_assert(RV % 16 == 0 && RM % 16 == 0, "rows must be whole 16-byte chunks");
+    static constexpr bool V_SWIZZLE = (RV == 128);           // 8 chunks per row: same XOR as the X rows
+    static constexpr int X_SUB = BT * 128;                   // bytes of one 128-column slice of X
+    static constexpr int X_BLOCKS = KU * BT * 128 / 1024;
+    static constexpr int V_BLOCKS = (BO * RV + 1023) / 1024;
+    static constexpr int M_BLOCKS = (BO * RM + 1023) / 1024;
+    static constexpr int X_OFF = 0;
+    static constexpr int V_OFF = X_BLOCKS * 1024;
+    static constexpr int M_OFF = V_OFF + V_BLOCKS * 1024;
+    static constexpr int BLOCKS = X_BLOCKS + V_BLOCKS + M_BLOCKS;
+};
+
+// One direct-to-LDS load: 64 lanes x 16 bytes, lane l from its own pointer to LDS lds_addr + 16*l.
+// (M0 carries the LDS address; one wait state between writing M0 and the load that reads it.)
+__device__ __forceinline__ void dma16(uint32_t lds_addr, const uint8_t* src)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(src)
+                 : "memory");
+}
+
+template <int CNT>
+__device__ __forceinline__ void wait_vm()
+{
+    static_assert(CNT >= 0 && CNT < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(CNT) : "memory");
+}
+
+// KU = 128-column slices per stage.  With KU = 2 a stage row of 2:4 int8 codes is one full
+// 128-byte line and the index rows are 32 bytes: the memory system sees a third fewer requests
+// per byte than with single-slice stages, at the price of a coarser ring.
+template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU>
+__global__ void __launch_bounds__(64 * WAVES_T * WAVES_O)
+gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
+{
+    using U = Unit<N, M, BITS>;
+    using G = DmaGeom<N, M, BITS, BT, BO, KU>;
+    constexpr int NW = WAVES_T * WAVES_O;
+    constexpr int WT = BT / WAVES_T, WO = BO / WAVES_O;
+    constexpr int FT = WT / 16, FO = WO / 16;
+    static_assert(WT % 16 == 0 && WO % 16 == 0, "wave tile must be whole 16x16 fragments");
+    static_assert(BT % 8 == 0, "X blocks hold 8 rows");
+    static_assert(KU == 1 || KU == 2, "one or two slices per stage");
+    constexpr int PER_WAVE = (G::BLOCKS + NW - 1) / NW;      // direct loads per wavefront per stage
+    constexpr int STAGE = PER_WAVE * NW * 1024;              // bytes (tail blocks of the last wave are padding)
+
+    extern __shared__ __align__(1024) uint8_t smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wt = wave % WAVES_T, wo = wave / WAVES_T;
+
+    const int per_xcd = (n_tiles + 7) >> 3;
+    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= n_tiles) return;               // whole workgroup leaves before any barrier
+    const int t0 = (tile / tiles_o) * BT;
+    const int o0 = (tile % tiles_o) * BO;
+    const int nk = a.K >> 7;                   // 128-column slices
+    const int ns = nk / KU;                    // stages to stream (host guarantees nk % KU == 0)
+
+    // Scales and bias of this wavefront's rows, requested before anything else so that their
+    // latency hides behind the main loop instead of standing at the head of the epilogue.
+    const int li = lane & 15, lg = lane >> 4;
+    float4 sw[FO], bw[FO];
+#pragma unroll
+    for (int fo = 0; fo < FO; ++fo) {
+        const int o = min(o0 + wo * WO + fo * 16 + 4 * lg, a.O - 4);
+        sw[fo] = *reinterpret_cast<const float4*>(a.scales + o);
+        bw[fo] = a.bias ? *reinterpret_cast<const float4*>(a.bias + o) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    // (Issued before every direct load: the in-order counter then never has to account for them.)
+
+    // ---- per-lane source pointers of this wavefront's PER_WAVE loads --------------------------
+    // Load p of wave w fills block b = p * NW + w of the stage; blocks past the last real one are
+    // padding and refetch it.
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint8_t* src[PER_WAVE];
+    uint32_t step[PER_WAVE];                   // bytes per stage along the source row
+#pragma unroll
+    for (int p = 0; p < PER_WAVE; ++p) {
+        const int b = min(p * NW + wave_u, G::BLOCKS - 1);
+        if (b < G::X_BLOCKS) {
+            const int sub = b / (BT / 8);
+            const int row = (b % (BT / 8)) * 8 + (lane >> 3);
+            const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+            const int trow = min(t0 + row, a.tokens - 1);
+            src[p] = reinterpret_cast<const uint8_t*>(a.X) + (size_t)trow * a.ldx + sub * 128 + chunk * 16;
+            step[p] = 128 * KU;
+        } else if (b < G::X_BLOCKS + G::V_BLOCKS) {
+            const int q = (b - G::X_BLOCKS) * 64 + lane;       // 16-byte slot index in the codes array
+            const int row = min(q / (G::RV / 16), BO - 1);
+            const int slot = q % (G::RV / 16);
+            const int chunk = G::V_SWIZZLE ? (slot ^ ((row >> 1) & 7)) : slot;
+            const int orow = min(o0 + row, a.O - 1);
+            src[p] = a.vals + (size_t)orow * a.vstride + chunk * 16;
+            step[p] = G::RV;
+        } else {
+            const int q = (b - G::X_BLOCKS - G::V_BLOCKS) * 64 + lane;
+            const int row = min(q / (G::RM / 16), BO - 1);
+            const int orow = min(o0 + row, a.O - 1);
+            src[p] = a.meta + (size_t)orow * a.mstride + (q % (G::RM / 16)) * 16;
+            step[p] = G::RM;
+        }
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
+
+    // Workgroups walk K in rotated order (stage j of this workgroup is K block (kstart + j) mod ns;
+    // integer sums do not care), so that workgroups sharing rows of X do not all miss on the same
+    // lines at the same moment.
+    const int kstart = (int)(((unsigned)tile * 7u) % (unsigned)ns);
+    auto issue = [&](int j, int stage) {
+        int k = kstart + j;
+        if (k >= ns) k -= ns;
+#pragma unroll
+        for (int p = 0; p < PER_WAVE; ++p)
+            dma16(lds0 + stage * STAGE + (p * NW + wave_u) * 1024, src[p] + (uint32_t)k * step[p]);
+    };
+
+    v4i acc[FO][FT];
+#pragma unroll
+    for (int fo = 0; fo < FO; ++fo)
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft) acc[fo][ft] = v4i{0, 0, 0, 0};
+
+    // Fragment addresses inside a stage, for slice s (added at use): B fragment rows start at
+    // multiples of 16, so the swizzle term (row >> 1) & 7 only depends on the lane.
+    const int xsw = (li >> 1) & 7;
+    const int frag_x_lo = G::X_OFF + (wt * WT + li) * 128 + ((lg ^ xsw) * 16);
+    const int frag_x_hi = G::X_OFF + (wt * WT + li) * 128 + (((lg + 4) ^ xsw) * 16);
+    int frag_v[KU];
+#pragma unroll
+    for (int s = 0; s < KU; ++s) {
+        const int off = (4 * s + lg) * U::VBYTES;              // byte offset of this lane's unit in the row
+        const int chunk = G::V_SWIZZLE ? ((off >> 4) ^ xsw) : (off >> 4);
+        frag_v[s] = G::V_OFF + (wo * WO + li) * G::RV + chunk * 16 + (off & 15);
+    }
+    const int frag_m = G::M_OFF + (wo * WO + li) * G::RM + lg * U::MBYTES;
+
+    // Fragments live in registers one slice ahead of the MFMAs: while the matrix pipe works on
+    // slice k, the LDS reads of slice k+1 are already in flight.
+    struct Frags {
+        v8i b[FT];
+        typename U::Raw w[FO];
+    };
+    auto fetch = [&](int stage, auto sub, Frags& f) {
+        constexpr int s = decltype(sub)::value;
+        const uint8_t* base = smem + stage * STAGE;
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft) {
+            const v4i lo = *reinterpret_cast<const v4i*>(base + s * G::X_SUB + frag_x_lo + ft * 16 * 128);
+            const v4i hi = *reinterpret_cast<const v4i*>(base + s * G::X_SUB + frag_x_hi + ft * 16 * 128);
+            f.b[ft] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
+#pragma unroll
+        for (int fo = 0; fo < FO; ++fo)
+            f.w[fo] = U::load(base + frag_v[s] + fo * 16 * G::RV, base + frag_m + s * 4 * U::MBYTES + fo * 16 * G::RM, 0);
+    };
+    auto mma = [&](const Frags& f) {
+#pragma unroll
+        for (int fo = 0; fo < FO; ++fo) {
+            v4i codes; int pos;
+            U::decode(f.w[fo], codes, pos);
+#pragma unroll
+            for (int ft = 0; ft < FT; ++ft)
+                acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(codes, f.b[ft], acc[fo][ft], pos, 0, 0);
+        }
+    };
+    auto interleave = [&]() {
+        // One MFMA, then one LDS read issued in its shadow.  A wavefront issues in order, so
+        // without this the reads of the next slice would all sit behind (or in front of) the
+        // MFMAs and the LDS would idle while the matrix pipe runs.
+#pragma unroll
+        for (int i = 0; i < FO * FT; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+        }
+    };
+
+    // ---- pipeline -----------------------------------------------------------------------------
+    // Ring of STAGES stages, stream stage j in ring slot j % STAGES.  While stage j is being
+    // multiplied, stages j+1 .. j+AHEAD are in flight or landed, and the slot of stage j-1 (whose
+    // reads every wavefront has consumed before the barrier) is refilled.
+    constexpr int AHEAD = STAGES - 2;
+    static_assert(AHEAD >= 1, "at least three stages");
+    static_assert(AHEAD * PER_WAVE < 64, "loads in flight must fit the counter");
+#pragma unroll
+    for (int j = 0; j <= AHEAD; ++j)
+        if (j < ns) issue(j, j % STAGES);
+
+    Frags fr[2];
+    if (ns > AHEAD) wait_vm<AHEAD * PER_WAVE>();             // stage 0 landed; the AHEAD behind it may still fly
+    else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    fetch(0, std::integral_constant<int, 0>{}, fr[0]);
+
+    int slot_c = 0;                             // ring slot of the stage being multiplied
+    int slot_i = (AHEAD + 1) % STAGES;          // ring slot the next issue refills
+    // Everything needed before the fragments of the first slice of stage j+1 can be read.
+    auto advance = [&](int j) {
+        if (j + 1 < ns) {
+            // stages j+1 .. min(j+AHEAD, ns-1) are in flight, oldest first
+            if (j + AHEAD < ns) wait_vm<(AHEAD - 1) * PER_WAVE>();
+            else wait_vm<0>();
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (j + 1 + AHEAD < ns) issue(j + 1 + AHEAD, slot_i);
+        }
+        slot_c = (slot_c + 1 == STAGES) ? 0 : slot_c + 1;
+        slot_i = (slot_i + 1 == STAGES) ? 0 : slot_i + 1;
+    };
+    // The fragment fetch is unconditional (after the last slice it re-reads an idle slot and the
+    // values are dropped) so that the two register sets never merge across a branch.
+    if constexpr (KU == 2) {
+        for (int j = 0; j < ns; ++j) {
+            mma(fr[0]);
+            fetch(slot_c, std::integral_constant<int, 1>{}, fr[1]);
+            interleave();
+            advance(j);
+            mma(fr[1]);
+            fetch(slot_c, std::integral_constant<int, 0>{}, fr[0]);
+            interleave();
+        }
+    } else {
+        int j = 0;
+        for (; j + 2 <= ns; j += 2) {
+            advance(j);
+            mma(fr[0]);
+            fetch(slot_c, std::integral_constant<int, 0>{}, fr[1]);
+            interleave();
+            advance(j + 1);
+            mma(fr[1]);
+            fetch(slot_c, std::integral_constant<int, 0>{}, fr[0]);
+            interleave();
+        }
+        if (j < ns) {
+            advance(j);
+            mma(fr[0]);
+        }
+    }
+
+    // ---- epilogue: Eq. 4 with offset 0 on the product of two quantised operands --------------
+    store_tile_pre<FO, FT>(a, acc, sw, bw, o0 + wo * WO, t0 + wt * WT, li, lg);
+}
+
+template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU>
+bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
+{
+    using G = DmaGeom<N, M, BITS, BT, BO, KU>;
+    constexpr int NW = WAVES_T * WAVES_O;
+    constexpr int PER_WAVE = (G::BLOCKS + NW - 1) / NW;
+    constexpr size_t lds = (size_t)STAGES * PER_WAVE * NW * 1024;
+    static_assert(lds <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
+    if ((a.K / 128) % KU != 0) return false;
+    const int tiles_t = (a.tokens + BT - 1) / BT, tiles_o = (a.O + BO - 1) / BO;
+    const int n_tiles = tiles_t * tiles_o;
+    const int grid = 8 * ((n_tiles + 7) / 8);
+    auto kern = gemm_dma_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O, STAGES, KU>;
+    if (lds > 64 * 1024) {
+        static bool raised = false;             // per instantiation; the attribute is sticky
+        if (!raised) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), lds, st, a, tiles_o, n_tiles);
+    return true;
+}
+
+// Tile choice.  The kernel is bound by what one CU can pull through its L1 (about 50 B/clk), so
+// the tile wants to be as large as the CU count allows: 128 x 96 gives BERT-base's 768-wide
+// layers exactly 256 workgroups at 4096 tokens.  Rings of at most 80 KB let two workgroups share
+// a CU, which overlaps one's epilogue with the other's prologue when there are several rounds.
+template <int N, int M, int BITS>
+bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
+{
+    if (cfg == 0) {
+        const long long n96 = (long long)((a.tokens + 127) / 128) * ((a.O + 95) / 96);
+        const bool k256 = (a.K % 256) == 0;
+        if (a.O % 96 != 0 && a.O % 128 == 0) cfg = 117;          // 128 x 128, no ragged column tile
+        else if (n96 <= 256 && k256) cfg = 113;                  // one round: deepest ring, 256-column stages
+        else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
+        else cfg = 116;                                          // 128 x 96, two workgroups per CU
+    }
+    switch (cfg) {
+        case 101: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 4, 1>(a, st);
+        case 105: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 2>(a, st);
+        case 107: return launch_dma_tile<N, M, BITS, 256, 144, 4, 1, 3, 1>(a, st);
+        case 109: return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 6, 1>(a, st);
+        case 112: return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
+        case 113: return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(a, st);
+        case 115: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
+        case 116: return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
+        case 117: return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
+        case 118: return launch_dma_tile<N, M, BITS, 64, 96, 2, 2, 4, 1>(a, st);
+        case 121: return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
+        default: return false;
+    }
+}
+
+}  // namespace
+
+// Returns true when it launched a kernel for this problem.
+bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg)
+{
+#define NM_CASE(n, m, b) if (a.N == n && a.M == m && a.bits == b) return launch_dma_pattern<n, m, b>(a, st, cfg)
+    NM_CASE(2, 4, 8);
+#undef NM_CASE
+    return false;
+}
+
+}  // namespace nm

@@ -148,10 +148,19 @@ def small_case(N, M, bits, T, K, O, seed, with_bias=True):
 @pytest.mark.parametrize("tile", ["0", "1", "2", "3"])
 @pytest.mark.parametrize("N,M,bits", FAST_SCHEMES)
 def test_gemm_mfma_path_small(N, M, bits, tile):
+    _gemm_small(N, M, bits, tile)
+
+
+@pytest.mark.parametrize("tile", [str(i) for i in range(4, 18)] + ["101", "105", "107", "109", "112", "113", "115", "116", "117", "118", "121"])
+def test_gemm_mfma_path_every_tile_shape(tile):
+    _gemm_small(2, 4, 8, tile)
+
+
+def _gemm_small(N, M, bits, tile):
     say("gemm small", N, M, bits, "tile", tile)
     os.environ["NM_GEMM_TILE"] = tile
     try:
-        for T, K, O in [(200, 256, 136), (129, 128, 260), (16, 384, 64)]:
+        for T, K, O in [(200, 256, 136), (129, 128, 260), (16, 384, 64), (300, 1408, 200)]:
             W, Xq, sx, bias, ref, acc_ref = small_case(N, M, bits, T, K, O, 1)
             packed = gpu_compress(W, N, M, bits)
             assert_packed_equal(packed, ref, "compress")
