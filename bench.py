@@ -31,6 +31,12 @@ def parse():
     ap.add_argument("--out-dtype", choices=["bf16", "f32"], default="bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--workload", choices=["bert_base", "single", "copy"], default="bert_base",
+                    help="bert_base: the four GEMMs of a BERT-base layer at 4096 tokens (the benchmark); "
+                         "single: one 768x768 layer at 128 tokens (the skinny shape, for profiling); "
+                         "copy: a plain 256 MiB device copy (calibrates the HBM traffic counters)")
+    ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
+                    help="graph: the eight launches of a step are captured once in a HIP graph and replayed")
     return ap.parse_args()
 
 
@@ -50,8 +56,25 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.workload == "copy":
+        n = 256 << 20
+        src = torch.ones(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(max(args.steps, 1)):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"workload": "copy", "bytes_read_per_launch": n, "bytes_written_per_launch": n,
+                          "launches": max(args.steps, 1)}))
+        return
     lib = binding.raw()
-    gemms = synth.config2()
+    if args.workload == "single":
+        g1 = synth.config1_tensors()[0]
+        gemms = [synth.Gemm("single", g1.T, g1.K, g1.O, g1.N, g1.M, g1.bits, (1, 0, 0), outliers=False)]
+        workload_name = "single 768x768 linear layer, 128 tokens, 2:4 int8"
+    else:
+        gemms = synth.config2()
+        workload_name = ("BERT-base encoder layer linear set (QKV, attn-out, FFN-up, FFN-down), 2:4 int8, "
+                         "32x128=4096 tokens")
     out_code = NM_OUT_BF16 if args.out_dtype == "bf16" else NM_OUT_F32
     out_torch = torch.bfloat16 if args.out_dtype == "bf16" else torch.float32
 
@@ -90,16 +113,11 @@ def main():
         if rc != 0:
             raise RuntimeError("libnm call failed: %s" % nm.nm_status_string(rc))
 
-    def step(events=None):
+    def step():
         for a in cargs:
             check(lib.nm_compress(*a))
-        for i, a in enumerate(gargs):
-            if events is not None and i == events[0]:
-                events[1].record()
-                check(lib.nm_gemm(*a))
-                events[2].record()
-            else:
-                check(lib.nm_gemm(*a))
+        for a in gargs:
+            check(lib.nm_gemm(*a))
 
     def timed_launches(fn, a, reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -122,18 +140,38 @@ def main():
     dom = int(np.argmax(per_gemm_us))
 
     # ---- timed region -----------------------------------------------------------------------
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    # The step's eight launches are short (4-20 us each), so they are captured once into a HIP
+    # graph and the graph is replayed; the eager mode issues them one by one from Python.
+    graph = None
+    if args.launch == "graph":
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            graph = torch.cuda.CUDAGraph()
+            cap_stream = side.cuda_stream
+            cg = [a[:-1] + (cap_stream,) for a in cargs]
+            gg = [a[:-1] + (cap_stream,) for a in gargs]
+            with torch.cuda.graph(graph, stream=side):
+                for a in cg:
+                    check(lib.nm_compress(*a))
+                for a in gg:
+                    check(lib.nm_gemm(*a))
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(3):
+            graph.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step((dom, pairs[k][0], pairs[k][1]))
+        if graph is not None:
+            graph.replay()
+        else:
+            step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    dom_pair_us = float(np.mean([a.elapsed_time(b) for a, b in pairs])) * 1e3
-    # The pair brackets one launch and carries about 3 us of event cost; the launch duration proper
-    # is taken from a run of back-to-back launches of that same kernel right after the timed steps
-    # (this is the figure a rocprofv3 kernel trace of this command reports for the kernel).
+    # Launch duration of the dominant kernel: HIP events around back-to-back launches of that same
+    # kernel on the same stream, right after the timed steps (this is the figure a rocprofv3
+    # kernel trace of this command reports for the kernel).
     dom_us = timed_launches(lib.nm_gemm, gargs[dom], 200)
     dense_ops = sum(g.dense_ops for g in gemms)
     value = dense_ops / (ms_per_step * 1e-3) / 1e12
@@ -149,9 +187,9 @@ def main():
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": "BERT-base encoder layer linear set (QKV, attn-out, FFN-up, FFN-down), 2:4 int8, "
-                               "32x128=4096 tokens; step = nm_compress x4 + nm_gemm x4 (bias, %s out)" % args.out_dtype,
-                   "tokens": 4096, "hidden": 768, "pattern": "2:4", "weight_bits": 8, "out_dtype": args.out_dtype},
+        "config": {"workload": workload_name + "; step = nm_compress x%d + nm_gemm x%d (bias, %s out), %s launch"
+                               % (len(gemms), len(gemms), args.out_dtype, args.launch),
+                   "tokens": gemms[0].T, "hidden": 768, "pattern": "2:4", "weight_bits": 8, "out_dtype": args.out_dtype},
         "pct_of_int8_dense_peak": round(100.0 * value / INT8_DENSE_PEAK_TOPS, 2),
         "roofline": {
             "bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_DENSE_PEAK_TOPS, "unit": "TFLOP/s",
@@ -160,7 +198,6 @@ def main():
             "note": "int8 multiply-add ops, dense-equivalent (zeros counted), against the dense int8 MFMA peak; "
                     "duration = HIP events around 200 back-to-back launches of this kernel after the timed steps",
             "duration_us": round(dom_us, 2),
-            "duration_us_event_pair_inside_steps": round(dom_pair_us, 2),
         },
         "kernels": {
             "gemm_us_back_to_back": {g.name: round(u, 2) for g, u in zip(gemms, per_gemm_us)},

@@ -13,19 +13,39 @@ namespace nm {
 
 namespace {
 
-__device__ __forceinline__ float wave_max(float v)
+// Lane-crossing moves inside a row of 16 lanes through the DPP path of the vector ALU (no LDS
+// round trip): controls 0xB1 / 0x4E swap neighbours at distance 1 / 2 inside each quad, 0x141
+// mirrors each half-row of 8, 0x140 mirrors the row of 16.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v)
 {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
-    return v;
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
 }
 
-// OR together the `lanes` consecutive lanes of each aligned lane group (lanes is a power of two).
+// max over the 64 lanes, result in every lane
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = fmaxf(v, __uint_as_float(dpp_u32<0xB1>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(dpp_u32<0x4E>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(dpp_u32<0x141>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(dpp_u32<0x140>(__float_as_uint(v))));
+    const int b = (int)__float_as_uint(v);               // every lane now holds its row's maximum
+    const float r0 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane(b, 0));
+    const float r1 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane(b, 16));
+    const float r2 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane(b, 32));
+    const float r3 = __uint_as_float((uint32_t)__builtin_amdgcn_readlane(b, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+// OR together the LANES consecutive lanes of each aligned lane group (LANES = 1, 2, 4, 8 or 16).
 template <int LANES>
 __device__ __forceinline__ uint32_t group_or(uint32_t v)
 {
-#pragma unroll
-    for (int m = 1; m < LANES; m <<= 1) v |= (uint32_t)__shfl_xor((int)v, m, 64);
+    static_assert(LANES == 1 || LANES == 2 || LANES == 4 || LANES == 8 || LANES == 16, "group within a row of 16");
+    if constexpr (LANES >= 2) v |= dpp_u32<0xB1>(v);
+    if constexpr (LANES >= 4) v |= dpp_u32<0x4E>(v);
+    if constexpr (LANES >= 8) v |= dpp_u32<0x141>(v);
+    if constexpr (LANES >= 16) v |= dpp_u32<0x140>(v);
     return v;
 }
 
@@ -62,42 +82,45 @@ __device__ __forceinline__ uint32_t keep_mask(const float (&x)[M])
     return mask;
 }
 
-template <int M>
-__device__ __forceinline__ float pick(const float (&x)[M], int c)
-{
-    float v = x[0];
-#pragma unroll
-    for (int d = 1; d < M; ++d) v = (c == d) ? x[d] : v;
-    return v;
-}
-
-// One group -> its value bits (N codes of BITS bits, ascending columns) and index bits.
+// One group -> its value bits (N codes of BITS bits, ascending columns) and index bits.  Kept
+// column c goes to slot (number of kept columns below c); every register is addressed with a
+// compile-time index so the group never leaves the register file.
 template <int N, int M, int BITS>
 __device__ __forceinline__ void encode_group(const float (&x)[M], float s, uint32_t& vbits, uint32_t& mbits)
 {
     constexpr int IB = (M == 4) ? 2 : 4;
-    uint32_t mask = keep_mask<N, M>(x);
+    const uint32_t mask = keep_mask<N, M>(x);
     vbits = 0;
     mbits = 0;
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-        int c = __builtin_ctz(mask);
-        mask &= mask - 1;
-        int q = quantize<BITS>(pick<M>(x, c), s);
+        float v = 0.0f;
+        uint32_t col = 0;
+#pragma unroll
+        for (int c = j; c <= M - N + j; ++c) {          // slot j can only hold columns j .. M-N+j
+            const bool here = ((mask >> c) & 1u) && (__builtin_popcount(mask & ((1u << c) - 1u)) == j);
+            v = here ? x[c] : v;
+            col = here ? (uint32_t)c : col;
+        }
+        const int q = quantize<BITS>(v, s);
         vbits |= ((uint32_t)q & ((1u << BITS) - 1u)) << (j * BITS);
-        mbits |= (uint32_t)c << (j * IB);
+        mbits |= col << (j * IB);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// One wavefront per row.  Lane l owns group j*64 + l of pass j, so the fp32 row is read with
-// lane-contiguous 16-byte loads, and the per-group value / index bits of neighbouring lanes are
-// OR-combined into whole dwords before they are stored.  Rows of up to 4096 columns stay in
-// registers between the amax pass and the encode pass; longer rows are read a second time.
+// WPR wavefronts per row (1, 2 or 4; four wavefronts per workgroup).  Pass p of a row covers
+// groups 64p .. 64p+63, lane l owning group 64p + l, so the fp32 row is read with lane-contiguous
+// 16-byte loads; wavefront w of the row takes passes w, w+WPR, ...  The per-group value / index
+// bits of neighbouring lanes are OR-combined into whole dwords before they are stored.  A
+// wavefront keeps up to 64 floats per lane in registers between the amax pass and the encode
+// pass (rows up to 4096*WPR columns); longer rows are read a second time.  Long rows are split
+// over several wavefronts because one wavefront walking a 3072-wide row alone is bound by its own
+// serial arithmetic, not by memory.
 // Requires: N*BITS and N*IB in {2,4,8,16,32}, packed row strides that are multiples of 4 bytes,
 // ldw % 4 == 0 and a 16-byte aligned W.
 // ---------------------------------------------------------------------------------------------
-template <int N, int M, int BITS>
+template <int N, int M, int BITS, int WPR>
 __global__ void __launch_bounds__(256)
 compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
                      uint32_t* __restrict__ vals, uint32_t* __restrict__ meta, float* __restrict__ scales,
@@ -109,46 +132,65 @@ compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
     constexpr int VL = 32 / VB;            // lanes per value dword
     constexpr int ML = 32 / MB;            // lanes per index dword
     constexpr int F4 = M / 4;              // 16-byte loads per group
-    constexpr int RES = 16 / F4;           // register-resident passes (64 floats per lane)
+    constexpr int RES = 16 / F4;           // register-resident passes per wavefront (64 floats per lane)
+    constexpr int RPB = 4 / WPR;           // rows per workgroup
     constexpr float QMAX = (float)((1 << (BITS - 1)) - 1);
 
-    const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= rows) return;               // whole wavefront leaves together; no block barrier is used
+    __shared__ float part[4];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row_raw = blockIdx.x * RPB + wave / WPR;
+    const bool live = row_raw < rows;      // rows past the end are computed on the last row and not stored
+    const int row = live ? row_raw : rows - 1;
+    const int w = wave % WPR;
 
     const float4* __restrict__ w4 = reinterpret_cast<const float4*>(W + (size_t)row * ldw);
     const int groups = cols / M;
-    const int passes = (groups + 63) >> 6;
-    const bool resident = passes <= RES;
+    const int passes = (groups + 63) >> 6;                 // of the whole row
+    const int mine = (passes - w + WPR - 1) / WPR;          // passes of this wavefront: w, w+WPR, ...
+    const bool resident = mine <= RES;
 
-    float x[RES][M];
+    float4 x[RES * F4];                     // only ever indexed with compile-time constants: stays in registers
+#pragma unroll
+    for (int i = 0; i < RES * F4; ++i) x[i] = make_float4(0.f, 0.f, 0.f, 0.f);
     float amax = 0.0f;
     if (resident) {
 #pragma unroll
-        for (int j = 0; j < RES; ++j) {
-            if (j < passes) {
-                int g = j * 64 + lane;
+        for (int i = 0; i < RES; ++i) {
+            const int g = (w + i * WPR) * 64 + lane;
+            if (i < mine && g < groups) {
 #pragma unroll
-                for (int f = 0; f < F4; ++f) {
-                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (g < groups) v = w4[(size_t)g * F4 + f];
-                    x[j][4 * f + 0] = v.x; x[j][4 * f + 1] = v.y; x[j][4 * f + 2] = v.z; x[j][4 * f + 3] = v.w;
-                    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-                }
+                for (int f = 0; f < F4; ++f) x[i * F4 + f] = w4[(size_t)g * F4 + f];
             }
         }
-    } else {
-        for (int g = lane; g < groups; g += 64)
 #pragma unroll
-            for (int f = 0; f < F4; ++f) {
-                float4 v = w4[(size_t)g * F4 + f];
-                amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-            }
+        for (int i = 0; i < RES * F4; ++i) {
+            const float4 v = x[i];
+            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+    } else {
+        for (int i = 0; i < mine; ++i) {
+            const int g = (w + i * WPR) * 64 + lane;
+            if (g < groups)
+#pragma unroll
+                for (int f = 0; f < F4; ++f) {
+                    float4 v = w4[(size_t)g * F4 + f];
+                    amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+                }
+        }
     }
     amax = wave_max(amax);
+    if constexpr (WPR > 1) {
+        if (lane == 0) part[wave] = amax;
+        __syncthreads();
+        const int first = (wave / WPR) * WPR;
+        amax = part[first];
+#pragma unroll
+        for (int k = 1; k < WPR; ++k) amax = fmaxf(amax, part[first + k]);
+    }
     // Sec. 3.3.1: largest magnitude over the largest code; an all-zero row keeps scale 1
     const float s = (amax == 0.0f) ? 1.0f : amax / QMAX;
-    if (lane == 0) scales[row] = s;
+    if (live && w == 0 && lane == 0) scales[row] = s;
 
     uint32_t* __restrict__ vrow = vals + (size_t)row * vstride_dw;
     uint32_t* __restrict__ mrow = meta + (size_t)row * mstride_dw;
@@ -158,17 +200,26 @@ compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
         if (g < groups) encode_group<N, M, BITS>(grp, s, vb, mb);
         vb = group_or<VL>(vb << ((lane % VL) * VB));
         mb = group_or<ML>(mb << ((lane % ML) * MB));
-        if (g < groups && lane % VL == 0) vrow[g / VL] = vb;
-        if (g < groups && lane % ML == 0) mrow[g / ML] = mb;
+        if (live && g < groups && lane % VL == 0) vrow[g / VL] = vb;
+        if (live && g < groups && lane % ML == 0) mrow[g / ML] = mb;
     };
 
     if (resident) {
 #pragma unroll
-        for (int j = 0; j < RES; ++j)
-            if (j < passes) emit(x[j], j * 64 + lane);
+        for (int i = 0; i < RES; ++i) {
+            if (i < mine) {
+                float grp[M];
+#pragma unroll
+                for (int f = 0; f < F4; ++f) {
+                    const float4 v = x[i * F4 + f];
+                    grp[4 * f + 0] = v.x; grp[4 * f + 1] = v.y; grp[4 * f + 2] = v.z; grp[4 * f + 3] = v.w;
+                }
+                emit(grp, (w + i * WPR) * 64 + lane);
+            }
+        }
     } else {
-        for (int j = 0; j < passes; ++j) {
-            int g = j * 64 + lane;
+        for (int i = 0; i < mine; ++i) {
+            const int g = (w + i * WPR) * 64 + lane;
             float grp[M];
 #pragma unroll
             for (int f = 0; f < F4; ++f) {
@@ -257,8 +308,19 @@ template <int N, int M, int BITS>
 void launch_wave(const float* W, int rows, int cols, int ldw, void* vals, void* meta, float* scales,
                  int vstride, int mstride, hipStream_t st)
 {
-    hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS>), dim3((rows + 3) / 4), dim3(256), 0, st,
-                       W, rows, cols, ldw, (uint32_t*)vals, (uint32_t*)meta, scales, vstride / 4, mstride / 4);
+    // wavefronts per row: enough that a wavefront walks at most ~4 passes of 64 groups
+    const int passes = (cols / M + 63) / 64;
+    uint32_t* v = (uint32_t*)vals;
+    uint32_t* m = (uint32_t*)meta;
+    if (passes > 8)
+        hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, 4>), dim3(rows), dim3(256), 0, st,
+                           W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4);
+    else if (passes > 4)
+        hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, 2>), dim3((rows + 1) / 2), dim3(256), 0, st,
+                           W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4);
+    else
+        hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, 1>), dim3((rows + 3) / 4), dim3(256), 0, st,
+                           W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4);
 }
 
 }  // namespace

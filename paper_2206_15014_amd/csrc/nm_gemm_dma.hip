@@ -279,7 +279,62 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     }
 
     // ---- epilogue: Eq. 4 with offset 0 on the product of two quantised operands --------------
-    store_tile_pre<FO, FT>(a, acc, sw, bw, o0 + wo * WO, t0 + wt * WT, li, lg);
+    // The MFMA leaves each lane with 4 consecutive outputs of one token, so a direct store writes
+    // 32-byte (bf16) pieces of 16 different rows per instruction.  For the dequantised output the
+    // tile is instead turned round through the (now idle) LDS ring and written as whole rows:
+    // BO outputs of one token are contiguous in memory.  Exact accumulators, when asked for, and
+    // ragged column tiles take the direct route.
+    constexpr int RING = STAGES * STAGE;
+    const bool full_cols = (o0 + BO <= a.O);
+    if (a.acc != nullptr || a.out_dtype == 0 || !full_cols) {
+        store_tile_pre<FO, FT>(a, acc, sw, bw, o0 + wo * WO, t0 + wt * WT, li, lg);
+        return;
+    }
+    const int esize = (a.out_dtype == 1) ? 4 : 2;
+    const int row_b = BO * esize + 16;                    // staged row stride in bytes (pad spreads banks)
+    if (BT * row_b > RING || (a.ldo * esize) % 16 != 0) { // tile does not fit the ring, or rows not 16-byte aligned
+        store_tile_pre<FO, FT>(a, acc, sw, bw, o0 + wo * WO, t0 + wt * WT, li, lg);
+        return;
+    }
+    __builtin_amdgcn_s_barrier();                          // every wavefront is done reading the ring
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int fo = 0; fo < FO; ++fo) {
+        const float sc[4] = {a.act_scale * sw[fo].x, a.act_scale * sw[fo].y, a.act_scale * sw[fo].z, a.act_scale * sw[fo].w};
+        const float bs[4] = {bw[fo].x, bw[fo].y, bw[fo].z, bw[fo].w};
+        const int col = wo * WO + fo * 16 + 4 * lg;
+#pragma unroll
+        for (int ft = 0; ft < FT; ++ft) {
+            const int row = wt * WT + ft * 16 + li;
+            const v4i c = acc[fo][ft];
+            float y[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) y[r] = (float)c[r] * sc[r] + bs[r];
+            uint8_t* dst = smem + row * row_b + col * esize;
+            if (a.out_dtype == 1) {
+                *reinterpret_cast<float4*>(dst) = make_float4(y[0], y[1], y[2], y[3]);
+            } else {
+                uint2 p;
+                p.x = bf16_rne(y[0]) | (bf16_rne(y[1]) << 16);
+                p.y = bf16_rne(y[2]) | (bf16_rne(y[3]) << 16);
+                *reinterpret_cast<uint2*>(dst) = p;
+            }
+        }
+    }
+    __syncthreads();
+    {
+        const int cpr = BO * esize / 16;                   // 16-byte chunks per staged row
+        const int total = BT * cpr;
+        uint8_t* out = reinterpret_cast<uint8_t*>(a.out);
+        for (int c = tid; c < total; c += 64 * NW) {
+            const int row = c / cpr, ch = c - row * cpr;
+            const int t = t0 + row;
+            if (t < a.tokens) {
+                const v4i v = *reinterpret_cast<const v4i*>(smem + row * row_b + ch * 16);
+                *reinterpret_cast<v4i*>(out + ((size_t)t * a.ldo + o0) * esize + ch * 16) = v;
+            }
+        }
+    }
 }
 
 template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU>
@@ -333,6 +388,12 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
         case 117: return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
         case 118: return launch_dma_tile<N, M, BITS, 64, 96, 2, 2, 4, 1>(a, st);
         case 121: return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
+        case 123: return launch_dma_tile<N, M, BITS, 128, 384, 4, 2, 3, 1>(a, st);
+        case 124: return launch_dma_tile<N, M, BITS, 128, 288, 4, 2, 3, 1>(a, st);
+        case 125: return launch_dma_tile<N, M, BITS, 128, 384, 2, 2, 3, 1>(a, st);
+        case 126: return launch_dma_tile<N, M, BITS, 128, 192, 4, 2, 4, 1>(a, st);
+        case 127: return launch_dma_tile<N, M, BITS, 64, 384, 2, 2, 4, 1>(a, st);
+        case 128: return launch_dma_tile<N, M, BITS, 64, 384, 2, 4, 4, 1>(a, st);
         default: return false;
     }
 }
