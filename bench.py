@@ -35,6 +35,9 @@ def parse():
                     help="bert_base: the four GEMMs of a BERT-base layer at 4096 tokens (the benchmark); "
                          "single: one 768x768 layer at 128 tokens (the skinny shape, for profiling); "
                          "copy: a plain 256 MiB device copy (calibrates the HBM traffic counters)")
+    ap.add_argument("--only", default=None,
+                    help="restrict the bert_base workload to one layer (qkv, attn_out, ffn_up, ffn_down): used by "
+                         "the counter passes, which can tell dispatches apart only by kernel name and grid")
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="graph: the eight launches of a step are captured once in a HIP graph and replayed")
     return ap.parse_args()
@@ -73,6 +76,9 @@ def main():
         workload_name = "single 768x768 linear layer, 128 tokens, 2:4 int8"
     else:
         gemms = synth.config2()
+        if args.only is not None:
+            gemms = [g for g in gemms if g.name == args.only]
+            assert gemms, "--only names no layer of the workload"
         workload_name = ("BERT-base encoder layer linear set (QKV, attn-out, FFN-up, FFN-down), 2:4 int8, "
                          "32x128=4096 tokens")
     out_code = NM_OUT_BF16 if args.out_dtype == "bf16" else NM_OUT_F32

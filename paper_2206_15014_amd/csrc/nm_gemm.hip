@@ -230,7 +230,7 @@ gemm_generic_kernel(const GemmArgs a)
     if (a.out_dtype != 0) {
         float y = (float)sum * (a.act_scale * a.scales[o]) + (a.bias ? a.bias[o] : 0.0f);
         if (a.out_dtype == 1) reinterpret_cast<float*>(a.out)[at] = y;
-        else reinterpret_cast<uint16_t*>(a.out)[at] = (uint16_t)bf16_rne(y);
+        else reinterpret_cast<uint16_t*>(a.out)[at] = (uint16_t)pack_bf16x2(y, 0.0f);
     }
 }
 
@@ -319,6 +319,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t st)
         int tile_cfg = env ? atoi(env) : 0;
         // LDS-direct kernel first (tile_cfg 0 = its own choice, >= 100 = forced variant);
         // 1..99 force the register-staged kernel below.
+        if (tile_cfg >= 200 && launch_gemm_stream(a, st, tile_cfg)) return launch_status();
         if ((tile_cfg == 0 || tile_cfg >= 100) && (uintptr_t)a.meta % 16 == 0 && launch_gemm_dma(a, st, tile_cfg))
             return launch_status();
         if (tile_cfg >= 100) tile_cfg = 0;

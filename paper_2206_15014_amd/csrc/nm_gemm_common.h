@@ -88,6 +88,48 @@ struct Unit {
     }
 };
 
+// ---------------------------------------------------------------------------------------------
+// LDS-direct operand staging (global_load_lds_dwordx4): geometry of one ring stage and the load /
+// wait primitives.  A direct load writes 64 lanes x 16 bytes to 1 KB of consecutive LDS in lane
+// order, so every staged array is a sequence of 1 KB blocks and the layout inside a block is
+// chosen by which global chunk each lane fetches.
+// ---------------------------------------------------------------------------------------------
+template <int N, int M, int BITS, int BT, int BO, int KU>
+struct DmaGeom {
+    using U = Unit<N, M, BITS>;
+    static constexpr int RV = 4 * U::VBYTES * KU;            // packed value bytes per row per stage
+    static constexpr int RM = 4 * U::MBYTES * KU;            // packed index bytes per row per stage
+    static_assert(RV % 16 == 0 && RM % 16 == 0, "rows must be whole 16-byte chunks");
+    static constexpr bool V_SWIZZLE = (RV == 128);           // 8 chunks per row: same XOR as the X rows
+    static constexpr int X_SUB = BT * 128;                   // bytes of one 128-column slice of X
+    static constexpr int X_BLOCKS = KU * BT * 128 / 1024;
+    static constexpr int V_BLOCKS = (BO * RV + 1023) / 1024;
+    static constexpr int M_BLOCKS = (BO * RM + 1023) / 1024;
+    static constexpr int X_OFF = 0;
+    static constexpr int V_OFF = X_BLOCKS * 1024;
+    static constexpr int M_OFF = V_OFF + V_BLOCKS * 1024;
+    static constexpr int BLOCKS = X_BLOCKS + V_BLOCKS + M_BLOCKS;
+};
+
+// One direct-to-LDS load: 64 lanes x 16 bytes, lane l from its own pointer to LDS lds_addr + 16*l.
+// (M0 carries the LDS address, which must be the same in every lane; one wait state between
+// writing M0 and the load that reads it.)
+__device__ __forceinline__ void dma16(uint32_t lds_addr, const uint8_t* src)
+{
+    lds_addr = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(src)
+                 : "memory");
+}
+
+template <int CNT>
+__device__ __forceinline__ void wait_vm()
+{
+    static_assert(CNT >= 0 && CNT < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(CNT) : "memory");
+}
+
 // Compile-time counted loop: f(std::integral_constant<int, 0>{}) ... f(std::integral_constant<int, COUNT-1>{}).
 template <int COUNT, class F, int I = 0>
 __device__ __forceinline__ void int_for(F&& f)
@@ -98,13 +140,16 @@ __device__ __forceinline__ void int_for(F&& f)
     }
 }
 
-__device__ __forceinline__ uint32_t bf16_rne(float f)
+// Two fp32 -> two bf16 (round to nearest even) in one dword, `lo` in bits 0..15: gfx950 converts
+// a pair per instruction (v_cvt_pk_bf16_f32), which matters because the epilogue's vector ALU
+// work per output is of the same order as the matrix-pipe work per output at K = 768.
+typedef __bf16 nm_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float nm_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
+    const nm_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, nm_bf16x2));
 }
-
 
 // Epilogue shared by the MFMA kernels: Eq. 4 with offset 0 applied to the product of two quantised
 // operands.  acc[fo][ft] is the 16x16 accumulator fragment of weight rows o_base + fo*16 .. and
@@ -138,8 +183,8 @@ __device__ __forceinline__ void store_tile(const Args& a, const v4i (&acc)[FO][F
                     *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + at) = make_float4(y[0], y[1], y[2], y[3]);
                 } else {
                     uint2 p;
-                    p.x = bf16_rne(y[0]) | (bf16_rne(y[1]) << 16);
-                    p.y = bf16_rne(y[2]) | (bf16_rne(y[3]) << 16);
+                    p.x = pack_bf16x2(y[0], y[1]);
+                    p.y = pack_bf16x2(y[2], y[3]);
                     *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = p;
                 }
             }
@@ -174,8 +219,8 @@ __device__ __forceinline__ void store_tile_pre(const Args& a, const v4i (&acc)[F
                     *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + at) = make_float4(y[0], y[1], y[2], y[3]);
                 } else {
                     uint2 p;
-                    p.x = bf16_rne(y[0]) | (bf16_rne(y[1]) << 16);
-                    p.y = bf16_rne(y[2]) | (bf16_rne(y[3]) << 16);
+                    p.x = pack_bf16x2(y[0], y[1]);
+                    p.y = pack_bf16x2(y[2], y[3]);
                     *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = p;
                 }
             }

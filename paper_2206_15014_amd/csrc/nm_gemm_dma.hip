@@ -31,40 +31,6 @@ namespace nm {
 
 namespace {
 
-template <int N, int M, int BITS, int BT, int BO, int KU>
-struct DmaGeom {
-    using U = Unit<N, M, BITS>;
-    static constexpr int RV = 4 * U::VBYTES * KU;            // packed value bytes per row per stage
-    static constexpr int RM = 4 * U::MBYTES * KU;            // packed index bytes per row per stage
-    static_assert(RV % 16 == 0 && RM % 16 == 0, "rows must be whole 16-byte chunks");
-    static constexpr bool V_SWIZZLE = (RV == 128);           // 8 chunks per row: same XOR as the X rows
-    static constexpr int X_SUB = BT * 128;                   // bytes of one 128-column slice of X
-    static constexpr int X_BLOCKS = KU * BT * 128 / 1024;
-    static constexpr int V_BLOCKS = (BO * RV + 1023) / 1024;
-    static constexpr int M_BLOCKS = (BO * RM + 1023) / 1024;
-    static constexpr int X_OFF = 0;
-    static constexpr int V_OFF = X_BLOCKS * 1024;
-    static constexpr int M_OFF = V_OFF + V_BLOCKS * 1024;
-    static constexpr int BLOCKS = X_BLOCKS + V_BLOCKS + M_BLOCKS;
-};
-
-// One direct-to-LDS load: 64 lanes x 16 bytes, lane l from its own pointer to LDS lds_addr + 16*l.
-// (M0 carries the LDS address; one wait state between writing M0 and the load that reads it.)
-__device__ __forceinline__ void dma16(uint32_t lds_addr, const uint8_t* src)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(lds_addr), "v"(src)
-                 : "memory");
-}
-
-template <int CNT>
-__device__ __forceinline__ void wait_vm()
-{
-    static_assert(CNT >= 0 && CNT < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(CNT) : "memory");
-}
-
 // KU = 128-column slices per stage.  With KU = 2 a stage row of 2:4 int8 codes is one full
 // 128-byte line and the index rows are 32 bytes: the memory system sees a third fewer requests
 // per byte than with single-slice stages, at the price of a coarser ring.
@@ -147,7 +113,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     // integer sums do not care), so that workgroups sharing rows of X do not all miss on the same
     // lines at the same moment.
     const int kstart = (int)(((unsigned)tile * 7u) % (unsigned)ns);
-    auto issue = [&](int j, int stage) {
+    auto issue = [&](int j, int stage) __attribute__((always_inline)) {
         int k = kstart + j;
         if (k >= ns) k -= ns;
 #pragma unroll
@@ -181,7 +147,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         v8i b[FT];
         typename U::Raw w[FO];
     };
-    auto fetch = [&](int stage, auto sub, Frags& f) {
+    auto fetch = [&](int stage, auto sub, Frags& f) __attribute__((always_inline)) {
         constexpr int s = decltype(sub)::value;
         const uint8_t* base = smem + stage * STAGE;
 #pragma unroll
@@ -194,7 +160,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         for (int fo = 0; fo < FO; ++fo)
             f.w[fo] = U::load(base + frag_v[s] + fo * 16 * G::RV, base + frag_m + s * 4 * U::MBYTES + fo * 16 * G::RM, 0);
     };
-    auto mma = [&](const Frags& f) {
+    auto mma = [&](const Frags& f) __attribute__((always_inline)) {
 #pragma unroll
         for (int fo = 0; fo < FO; ++fo) {
             v4i codes; int pos;
@@ -204,7 +170,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
                 acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(codes, f.b[ft], acc[fo][ft], pos, 0, 0);
         }
     };
-    auto interleave = [&]() {
+    auto interleave = [&]() __attribute__((always_inline)) {
         // One MFMA, then one LDS read issued in its shadow.  A wavefront issues in order, so
         // without this the reads of the next slice would all sit behind (or in front of) the
         // MFMAs and the LDS would idle while the matrix pipe runs.
@@ -236,7 +202,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     int slot_c = 0;                             // ring slot of the stage being multiplied
     int slot_i = (AHEAD + 1) % STAGES;          // ring slot the next issue refills
     // Everything needed before the fragments of the first slice of stage j+1 can be read.
-    auto advance = [&](int j) {
+    auto advance = [&](int j) __attribute__((always_inline)) {
         if (j + 1 < ns) {
             // stages j+1 .. min(j+AHEAD, ns-1) are in flight, oldest first
             if (j + AHEAD < ns) wait_vm<(AHEAD - 1) * PER_WAVE>();
@@ -291,50 +257,66 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         return;
     }
     const int esize = (a.out_dtype == 1) ? 4 : 2;
-    const int row_b = BO * esize + 16;                    // staged row stride in bytes (pad spreads banks)
-    if (BT * row_b > RING || (a.ldo * esize) % 16 != 0) { // tile does not fit the ring, or rows not 16-byte aligned
+    if (BT * (BO * esize + 16) > RING || (a.ldo * esize) % 16 != 0) {   // tile does not fit the ring, or rows not 16-byte aligned
         store_tile_pre<FO, FT>(a, acc, sw, bw, o0 + wo * WO, t0 + wt * WT, li, lg);
         return;
     }
     __builtin_amdgcn_s_barrier();                          // every wavefront is done reading the ring
     asm volatile("" ::: "memory");
+    // ES = bytes per output element as a compile-time constant: the chunk arithmetic folds and the
+    // store loop unrolls (all LDS reads first, then all stores).
+    auto staged = [&](auto es) __attribute__((always_inline)) {
+        constexpr int ES = decltype(es)::value;
+        constexpr int ROW_B = BO * ES + 16;                // staged row stride in bytes (pad spreads banks)
 #pragma unroll
-    for (int fo = 0; fo < FO; ++fo) {
-        const float sc[4] = {a.act_scale * sw[fo].x, a.act_scale * sw[fo].y, a.act_scale * sw[fo].z, a.act_scale * sw[fo].w};
-        const float bs[4] = {bw[fo].x, bw[fo].y, bw[fo].z, bw[fo].w};
-        const int col = wo * WO + fo * 16 + 4 * lg;
+        for (int fo = 0; fo < FO; ++fo) {
+            const float sc[4] = {a.act_scale * sw[fo].x, a.act_scale * sw[fo].y, a.act_scale * sw[fo].z, a.act_scale * sw[fo].w};
+            const float bs[4] = {bw[fo].x, bw[fo].y, bw[fo].z, bw[fo].w};
+            const int col = wo * WO + fo * 16 + 4 * lg;
 #pragma unroll
-        for (int ft = 0; ft < FT; ++ft) {
-            const int row = wt * WT + ft * 16 + li;
-            const v4i c = acc[fo][ft];
-            float y[4];
+            for (int ft = 0; ft < FT; ++ft) {
+                const int row = wt * WT + ft * 16 + li;
+                const v4i c = acc[fo][ft];
+                float y[4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r) y[r] = (float)c[r] * sc[r] + bs[r];
-            uint8_t* dst = smem + row * row_b + col * esize;
-            if (a.out_dtype == 1) {
-                *reinterpret_cast<float4*>(dst) = make_float4(y[0], y[1], y[2], y[3]);
-            } else {
-                uint2 p;
-                p.x = bf16_rne(y[0]) | (bf16_rne(y[1]) << 16);
-                p.y = bf16_rne(y[2]) | (bf16_rne(y[3]) << 16);
-                *reinterpret_cast<uint2*>(dst) = p;
+                for (int r = 0; r < 4; ++r) y[r] = (float)c[r] * sc[r] + bs[r];
+                uint8_t* dst = smem + row * ROW_B + col * ES;
+                if constexpr (ES == 4) {
+                    *reinterpret_cast<float4*>(dst) = make_float4(y[0], y[1], y[2], y[3]);
+                } else {
+                    uint2 p;
+                    p.x = pack_bf16x2(y[0], y[1]);
+                    p.y = pack_bf16x2(y[2], y[3]);
+                    *reinterpret_cast<uint2*>(dst) = p;
+                }
             }
         }
-    }
-    __syncthreads();
-    {
-        const int cpr = BO * esize / 16;                   // 16-byte chunks per staged row
-        const int total = BT * cpr;
-        uint8_t* out = reinterpret_cast<uint8_t*>(a.out);
-        for (int c = tid; c < total; c += 64 * NW) {
-            const int row = c / cpr, ch = c - row * cpr;
-            const int t = t0 + row;
-            if (t < a.tokens) {
-                const v4i v = *reinterpret_cast<const v4i*>(smem + row * row_b + ch * 16);
-                *reinterpret_cast<v4i*>(out + ((size_t)t * a.ldo + o0) * esize + ch * 16) = v;
+        __syncthreads();
+        constexpr int CPR = BO * ES / 16;                  // 16-byte chunks per staged row
+        constexpr int CHUNKS = BT * CPR;
+        constexpr int ITER = (CHUNKS + 64 * NW - 1) / (64 * NW);
+        uint8_t* out = reinterpret_cast<uint8_t*>(a.out) + (size_t)o0 * ES;
+        constexpr int BATCH = ITER < 6 ? ITER : 6;         // chunks a lane holds in registers at a time
+#pragma unroll
+        for (int i0 = 0; i0 < ITER; i0 += BATCH) {
+            v4i v[BATCH];
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i) {
+                const int c = min(tid + (i0 + i) * 64 * NW, CHUNKS - 1);
+                const int row = c / CPR, ch = c - row * CPR;
+                v[i] = *reinterpret_cast<const v4i*>(smem + row * ROW_B + ch * 16);
+            }
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i) {
+                const int c = tid + (i0 + i) * 64 * NW;
+                const int row = c / CPR, ch = c - row * CPR;
+                if (i0 + i < ITER && c < CHUNKS && t0 + row < a.tokens)
+                    *reinterpret_cast<v4i*>(out + (size_t)(t0 + row) * a.ldo * ES + ch * 16) = v[i];
             }
         }
-    }
+    };
+    if (a.out_dtype == 1) staged(std::integral_constant<int, 4>{});
+    else staged(std::integral_constant<int, 2>{});
 }
 
 template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU>

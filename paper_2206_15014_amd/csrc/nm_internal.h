@@ -42,7 +42,8 @@ int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, i
 int launch_decompress(const void* vals, const void* meta, int rows, int cols, int N, int M, int bits,
                       int8_t* Wq, hipStream_t st);
 int launch_gemm(const GemmArgs& a, hipStream_t st);
-bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg);   // false: not handled, nothing launched
+bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg);      // false: not handled, nothing launched
+bool launch_gemm_stream(const GemmArgs& a, hipStream_t st, int cfg);   // same
 
 }  // namespace nm
 

@@ -13,7 +13,7 @@ def main():
     d = sys.argv[1]
     agg = collections.defaultdict(lambda: collections.defaultdict(list))
     for f in sorted(glob.glob(os.path.join(d, "*_counter_collection.csv"))):
-        tag = os.path.basename(f).replace("_counter_collection.csv", "").split("_")[0]
+        tag = os.path.basename(f).replace("_counter_collection.csv", "").split(".")[0]
         for r in csv.DictReader(open(f)):
             name = re.sub(r"void nm::\(anonymous namespace\)::|\(nm::GemmArgs.*|\(float const\*.*|void at::native::", "", r["Kernel_Name"])[:64]
             key = (tag, name, int(r["Grid_Size"]) // max(int(r["Workgroup_Size"]), 1))

@@ -64,8 +64,15 @@ def check_outputs(acc_ref, sx, scales_ref, bias, acc_gpu=None, f32_gpu=None, bf1
         assert np.all(err <= 1e-5 * mag + 1e-37), "%s: fp32 output off, worst ratio %g" % (
             what, np.max(err / (mag + 1e-37)))
     if bf16_gpu is not None:
+        # One bf16 step from the rounded reference.  Where the bias cancels the product (|y| far
+        # below |acc|*s_act*s_w + |bias|) a step of bf16 is smaller than the fp32 tolerance the
+        # value was computed to, so there the fp32 band, widened by one bf16 step, decides.
         d = np.abs(bf16_order(bf16_gpu) - bf16_order(ref_b16))
-        assert d.max() <= 1, "%s: bf16 output more than one step off (max %d)" % (what, d.max())
+        val = (bf16_gpu.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        band = 1e-5 * mag + np.abs(ref_f32.astype(np.float64)) * 2.0 ** -7 + 1e-37
+        ok = (d <= 1) | (np.abs(val - ref_f32.astype(np.float64)) <= band)
+        assert np.all(ok), "%s: bf16 output more than one step off at %d places (max %d steps)" % (
+            what, np.count_nonzero(~ok), d[~ok].max())
 
 
 def run_gemm(Xq, sx, packed, O, N, M, bits, bias=None, want=("acc", "f32"), ldo=None):
@@ -151,7 +158,7 @@ def test_gemm_mfma_path_small(N, M, bits, tile):
     _gemm_small(N, M, bits, tile)
 
 
-@pytest.mark.parametrize("tile", [str(i) for i in range(4, 18)] + ["101", "105", "107", "109", "112", "113", "115", "116", "117", "118", "121", "123", "124", "125", "126", "127", "128"])
+@pytest.mark.parametrize("tile", [str(i) for i in range(4, 18)] + ["101", "105", "107", "109", "112", "113", "115", "116", "117", "118", "121", "201", "202", "203", "204", "205", "206", "123", "124", "125", "126", "127", "128"])
 def test_gemm_mfma_path_every_tile_shape(tile):
     _gemm_small(2, 4, 8, tile)
 
@@ -166,6 +173,31 @@ def _gemm_small(N, M, bits, tile):
             assert_packed_equal(packed, ref, "compress")
             res = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("acc", "f32", "bf16"))
             check_outputs(acc_ref, sx, ref[2], bias, res["acc"], res["f32"], res["bf16"], what="T%d K%d O%d" % (T, K, O))
+    finally:
+        os.environ.pop("NM_GEMM_TILE", None)
+
+
+STREAM_TILES = ["201", "202", "203", "204", "205", "206"]
+
+
+@pytest.mark.parametrize("tile", STREAM_TILES)
+def test_gemm_persistent_kernel_several_tiles_per_workgroup(tile):
+    """Shapes the persistent kernel takes (whole column tiles, dequantised output only): more tiles
+    than CUs so that workgroups run on from one tile into the next, one K step per tile, an odd
+    number of K steps, a ragged last token tile, and a problem of a single tile."""
+    say("gemm persistent tile", tile)
+    os.environ["NM_GEMM_TILE"] = tile
+    try:
+        for T, K, O, with_bias in [(4400, 384, 1536, True), (4400, 128, 1536, False), (100, 256, 384, True), (1, 640, 384, True)]:
+            W, Xq, sx, bias, ref, acc_ref = small_case(2, 4, 8, T, K, O, 7, with_bias=with_bias)
+            packed = gpu_compress(W, 2, 4, 8)
+            f32 = run_gemm(Xq, sx, packed, O, 2, 4, 8, bias, want=("f32",))["f32"]
+            b16 = run_gemm(Xq, sx, packed, O, 2, 4, 8, bias, want=("bf16",))["bf16"]
+            check_outputs(acc_ref, sx, ref[2], bias, None, f32, b16, what="T%d K%d O%d" % (T, K, O))
+            if T == 100:     # padded output rows stay untouched
+                f32p = run_gemm(Xq, sx, packed, O, 2, 4, 8, bias, want=("f32",), ldo=O + 32)["f32"]
+                assert np.all(f32p[:, O:] == -7.0)
+                check_outputs(acc_ref, sx, ref[2], bias, None, f32p[:, :O], None, what="padded T%d" % T)
     finally:
         os.environ.pop("NM_GEMM_TILE", None)
 
