@@ -18,6 +18,14 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 // Weight units.  A unit is the slice of one packed weight row that covers 32 consecutive input
 // columns: what one lane feeds to one sparse MFMA.
 // ---------------------------------------------------------------------------------------------
+// Four 4-bit two's-complement values, one in the low nibble of each byte (high nibbles zero), sign-
+// extended to bytes: per byte (b ^ 8) - 8, done on the whole dword with the top bit of each byte
+// set during the subtraction so that no borrow crosses a byte.
+__device__ __forceinline__ uint32_t sext4x4(uint32_t nib)
+{
+    return ((nib ^ 0x88888888u) - 0x08080808u) ^ 0x80808080u;
+}
+
 template <int N, int M, int BITS>
 struct Unit {
     static constexpr int IB = (M == 4) ? 2 : 4;
@@ -58,6 +66,82 @@ struct Unit {
         if constexpr (IDENTITY) {
             codes = v4i{(int)r.v[0], (int)r.v[1], (int)r.v[2], (int)r.v[3]};
             pos = (int)r.m;
+        } else if constexpr (M == 4) {
+            // Whole dwords at a time (the per-entry form below costs ~6 vector-ALU operations per
+            // kept entry, several times the MFMA time of the fragment).  Operand byte 2g+j is slot
+            // j of group g; a pattern that keeps one entry per group fills slot 0 and leaves slot 1
+            // zero, whose position bits may then be anything.
+            uint32_t w[EPU / 4];                               // the codes as bytes, in entry order
+            if constexpr (BITS == 8) {
+#pragma unroll
+                for (int d = 0; d < EPU / 4; ++d) w[d] = r.v[d];
+            } else {
+#pragma unroll
+                for (int d = 0; d < EPU / 8; ++d) {
+                    const uint32_t x = r.v[d];
+                    const uint32_t lo = sext4x4(x & 0x0F0F0F0Fu);          // entries 0, 2, 4, 6 of this dword
+                    const uint32_t hi = sext4x4((x >> 4) & 0x0F0F0F0Fu);   // entries 1, 3, 5, 7
+                    w[2 * d] = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+                    w[2 * d + 1] = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+                }
+            }
+            if constexpr (N == 2) {
+                codes = v4i{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+                pos = (int)r.m;
+            } else {
+                // entry i -> byte 2i, zero in byte 2i+1; its 2 position bits -> bits 4i, 4i+1
+                codes = v4i{(int)__builtin_amdgcn_perm(0u, w[0], 0x0c010c00u), (int)__builtin_amdgcn_perm(0u, w[0], 0x0c030c02u),
+                            (int)__builtin_amdgcn_perm(0u, w[1], 0x0c010c00u), (int)__builtin_amdgcn_perm(0u, w[1], 0x0c030c02u)};
+                uint32_t x = r.m & 0xFFFFu;
+                x = (x | (x << 8)) & 0x00FF00FFu;
+                x = (x | (x << 4)) & 0x0F0F0F0Fu;
+                x = (x | (x << 2)) & 0x33333333u;
+                pos = (int)x;
+            }
+        } else if constexpr (M == 8 && N <= 2) {
+            // A group of 8 columns is two operand groups of 4 ("halves").  Kept entry j of a group
+            // goes to slot j of the half its column lies in (bit 2 of its offset); the other slots
+            // hold zero.  All four groups of the unit are handled at once, one byte lane per group.
+            uint32_t w[2];                                     // the codes as bytes, in entry order
+            if constexpr (BITS == 8) {
+                w[0] = r.v[0];
+                if constexpr (N == 2) w[1] = r.v[1];
+                else w[1] = 0u;
+            } else {
+                const uint32_t x = r.v[0];
+                const uint32_t lo = sext4x4(x & 0x0F0F0F0Fu);
+                const uint32_t hi = sext4x4((x >> 4) & 0x0F0F0F0Fu);
+                w[0] = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+                w[1] = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+            }
+            if constexpr (N == 2) {
+                const uint32_t m = r.m;                        // byte g = offset a | offset b << 4 of group g
+                const uint32_t ma = ((m >> 2) & 0x01010101u) * 255u;   // 0xFF where a lies in the upper half
+                const uint32_t mb = ((m >> 6) & 0x01010101u) * 255u;
+                const uint32_t a3 = m & 0x03030303u, b3 = (m >> 4) & 0x03030303u;
+                pos = (int)((((a3 << 4) & ma) | (a3 & ~ma)) | (((b3 << 6) & mb) | ((b3 << 2) & ~mb)));
+                // group g: (qa, qb, qa, qb) masked with (~ma, ~mb, ma, mb) of that group
+                const uint32_t k0 = __builtin_amdgcn_perm(mb, ma, 0x04000400u) ^ 0x0000FFFFu;
+                const uint32_t k1 = __builtin_amdgcn_perm(mb, ma, 0x05010501u) ^ 0x0000FFFFu;
+                const uint32_t k2 = __builtin_amdgcn_perm(mb, ma, 0x06020602u) ^ 0x0000FFFFu;
+                const uint32_t k3 = __builtin_amdgcn_perm(mb, ma, 0x07030703u) ^ 0x0000FFFFu;
+                codes = v4i{(int)(__builtin_amdgcn_perm(0u, w[0], 0x01000100u) & k0),
+                            (int)(__builtin_amdgcn_perm(0u, w[0], 0x03020302u) & k1),
+                            (int)(__builtin_amdgcn_perm(0u, w[1], 0x01000100u) & k2),
+                            (int)(__builtin_amdgcn_perm(0u, w[1], 0x03020302u) & k3)};
+            } else {
+                uint32_t y = r.m & 0xFFFFu;                    // four 4-bit offsets -> one per byte
+                y = (y | (y << 8)) & 0x00FF00FFu;
+                y = (y | (y << 4)) & 0x0F0F0F0Fu;
+                const uint32_t ma = ((y >> 2) & 0x01010101u) * 255u;
+                const uint32_t a3 = y & 0x03030303u;
+                pos = (int)(((a3 << 4) & ma) | (a3 & ~ma));
+                // group g: (q, 0, q, 0) masked with (~ma, 0, ma, 0) of that group
+                codes = v4i{(int)(__builtin_amdgcn_perm(0u, w[0], 0x0c000c00u) & (__builtin_amdgcn_perm(0u, ma, 0x0c000c00u) ^ 0x000000FFu)),
+                            (int)(__builtin_amdgcn_perm(0u, w[0], 0x0c010c01u) & (__builtin_amdgcn_perm(0u, ma, 0x0c010c01u) ^ 0x000000FFu)),
+                            (int)(__builtin_amdgcn_perm(0u, w[0], 0x0c020c02u) & (__builtin_amdgcn_perm(0u, ma, 0x0c020c02u) ^ 0x000000FFu)),
+                            (int)(__builtin_amdgcn_perm(0u, w[0], 0x0c030c03u) & (__builtin_amdgcn_perm(0u, ma, 0x0c030c03u) ^ 0x000000FFu))};
+            }
         } else {
             uint32_t hv[4] = {0u, 0u, 0u, 0u};
             uint32_t hp = 0u;

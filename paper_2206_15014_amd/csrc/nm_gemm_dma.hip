@@ -347,37 +347,40 @@ bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
 // the tile wants to be as large as the CU count allows: 128 x 96 gives BERT-base's 768-wide
 // layers exactly 256 workgroups at 4096 tokens.  Rings of at most 80 KB let two workgroups share
 // a CU, which overlaps one's epilogue with the other's prologue when there are several rounds.
+// Stage rows must be whole 16-byte pieces, which decides whether a pattern can use
+// single-slice stages (KU = 1) or needs 256-column stages (KU = 2).
 template <int N, int M, int BITS>
 bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 {
+    using U = Unit<N, M, BITS>;
+    constexpr bool KU1 = (4 * U::VBYTES) % 16 == 0 && (4 * U::MBYTES) % 16 == 0;
+    const bool k256 = (a.K % 256) == 0;
     if (cfg == 0) {
         const long long n96 = (long long)((a.tokens + 127) / 128) * ((a.O + 95) / 96);
-        const bool k256 = (a.K % 256) == 0;
-        if (a.O % 96 != 0 && a.O % 128 == 0) cfg = 117;          // 128 x 128, no ragged column tile
+        if (!KU1) cfg = (n96 <= 256) ? 113 : 119;               // 256-column stages only: 128 x 96, or 64 x 96 twice per CU
+        else if (!U::IDENTITY) cfg = 116;                        // decode work favours the smaller ring
         else if (n96 <= 256 && k256) cfg = 113;                  // one round: deepest ring, 256-column stages
         else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
         else cfg = 116;                                          // 128 x 96, two workgroups per CU
     }
-    switch (cfg) {
-        case 101: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 4, 1>(a, st);
-        case 105: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 2>(a, st);
-        case 107: return launch_dma_tile<N, M, BITS, 256, 144, 4, 1, 3, 1>(a, st);
-        case 109: return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 6, 1>(a, st);
-        case 112: return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
-        case 113: return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(a, st);
-        case 115: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
-        case 116: return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
-        case 117: return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
-        case 118: return launch_dma_tile<N, M, BITS, 64, 96, 2, 2, 4, 1>(a, st);
-        case 121: return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
-        case 123: return launch_dma_tile<N, M, BITS, 128, 384, 4, 2, 3, 1>(a, st);
-        case 124: return launch_dma_tile<N, M, BITS, 128, 288, 4, 2, 3, 1>(a, st);
-        case 125: return launch_dma_tile<N, M, BITS, 128, 384, 2, 2, 3, 1>(a, st);
-        case 126: return launch_dma_tile<N, M, BITS, 128, 192, 4, 2, 4, 1>(a, st);
-        case 127: return launch_dma_tile<N, M, BITS, 64, 384, 2, 2, 4, 1>(a, st);
-        case 128: return launch_dma_tile<N, M, BITS, 64, 384, 2, 4, 4, 1>(a, st);
-        default: return false;
+    if (cfg == 113) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(a, st);
+    if (cfg == 105) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 2>(a, st);
+    if (cfg == 119) return launch_dma_tile<N, M, BITS, 64, 96, 2, 2, 3, 2>(a, st);
+    if constexpr (KU1) {
+        if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
+        if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
     }
+    if constexpr (U::IDENTITY) {                                 // further shapes, kept selectable for tuning
+        switch (cfg) {
+            case 101: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 4, 1>(a, st);
+            case 109: return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 6, 1>(a, st);
+            case 115: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
+            case 117: return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
+            case 121: return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
+            default: break;
+        }
+    }
+    return false;
 }
 
 }  // namespace
@@ -386,7 +389,8 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg)
 {
 #define NM_CASE(n, m, b) if (a.N == n && a.M == m && a.bits == b) return launch_dma_pattern<n, m, b>(a, st, cfg)
-    NM_CASE(2, 4, 8);
+    NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4);
+    NM_CASE(1, 8, 8); NM_CASE(2, 8, 8); NM_CASE(1, 8, 4); NM_CASE(2, 8, 4);
 #undef NM_CASE
     return false;
 }
