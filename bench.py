@@ -21,6 +21,10 @@ if ROOT not in sys.path:
 
 INT8_DENSE_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA peak (sparsity not counted)
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per nm_gemm launch (bf16 output) of the benchmark's four layers, from rocprofv3 FETCH_SIZE and
+# WRITE_SIZE passes scaled by what the same counters read on a plain 256 MiB copy (read counter x2.000, write
+# counter x1.000): profiles/bert_base_2of4_int8_counters.txt.  Not measurable from inside this process.
+MEASURED_HBM_BYTES_BF16 = {"qkv": 31.13e6, "attn_out": 12.54e6, "ffn_up": 40.44e6, "ffn_down": 30.82e6}
 
 
 def parse():
@@ -125,24 +129,52 @@ def main():
         for a in gargs:
             check(lib.nm_gemm(*a))
 
+    side = torch.cuda.Stream()
+
     def timed_launches(fn, a, reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        for _ in range(5):
-            check(fn(*a))
+        """Microseconds per launch: `reps` launches captured into one HIP graph on a side stream and replayed
+        back to back, HIP events around the replays.  (Issued one by one from Python, launches this short
+        would be bound by the host, more so under a profiler.)  With --launch eager no graph is built
+        anywhere in the run and the launches are issued one by one."""
+        if args.launch == "eager":
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for _ in range(3):
+                check(fn(*a))
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                check(fn(*a))
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+        g = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            b = a[:-1] + (side.cuda_stream,)
+            for _ in range(3):
+                check(fn(*b))
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(reps):
+                    check(fn(*b))
+        torch.cuda.current_stream().wait_stream(side)
+        g.replay()
         torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = 5
         e0.record()
-        for _ in range(reps):
-            check(fn(*a))
+        for _ in range(n):
+            g.replay()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / reps          # microseconds per launch
+        return e0.elapsed_time(e1) * 1e3 / (n * reps)
 
     # ---- warm-up, and which kernel dominates the step ---------------------------------------
     for _ in range(max(args.warmup, 1)):
         step()
     torch.cuda.synchronize()
-    per_gemm_us = [timed_launches(lib.nm_gemm, a, 50) for a in gargs]
-    per_comp_us = [timed_launches(lib.nm_compress, a, 50) for a in cargs]
+    per_gemm_us = [timed_launches(lib.nm_gemm, a, 40) for a in gargs]
+    per_comp_us = [timed_launches(lib.nm_compress, a, 40) for a in cargs]
     dom = int(np.argmax(per_gemm_us))
 
     # ---- timed region -----------------------------------------------------------------------
@@ -150,7 +182,6 @@ def main():
     # graph and the graph is replayed; the eager mode issues them one by one from Python.
     graph = None
     if args.launch == "graph":
-        side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             graph = torch.cuda.CUDAGraph()
@@ -175,10 +206,10 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    # Launch duration of the dominant kernel: HIP events around back-to-back launches of that same
-    # kernel on the same stream, right after the timed steps (this is the figure a rocprofv3
-    # kernel trace of this command reports for the kernel).
-    dom_us = timed_launches(lib.nm_gemm, gargs[dom], 200)
+    # Launch duration of the dominant kernel: HIP events around back-to-back (graph-replayed) launches
+    # of that same kernel, right after the timed steps; a rocprofv3 kernel trace of this command
+    # reports the same kernel about a microsecond shorter (the gap between two launches).
+    dom_us = timed_launches(lib.nm_gemm, gargs[dom], 40)
     dense_ops = sum(g.dense_ops for g in gemms)
     value = dense_ops / (ms_per_step * 1e-3) / 1e12
 
@@ -199,10 +230,14 @@ def main():
         "pct_of_int8_dense_peak": round(100.0 * value / INT8_DENSE_PEAK_TOPS, 2),
         "roofline": {
             "bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_DENSE_PEAK_TOPS, "unit": "TFLOP/s",
-            "frac": round(achieved / INT8_DENSE_PEAK_TOPS, 4), "traffic": None,
+            "frac": round(achieved / INT8_DENSE_PEAK_TOPS, 4),
+            "traffic": MEASURED_HBM_BYTES_BF16.get(gd.name) if (args.workload == "bert_base" and args.out_dtype == "bf16") else None,
+            "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated on a copy; a stored figure)",
+            "algorithmic_bytes": gd.T * gd.K + gd.O * (gd.K // gd.M * gd.N) * (gd.bits + 2) // 8 + 8 * gd.O
+                                 + gd.T * gd.O * (2 if args.out_dtype == "bf16" else 4),
             "kernel": "nm_gemm %s %dx%d->%d" % (gd.name, gd.T, gd.K, gd.O),
             "note": "int8 multiply-add ops, dense-equivalent (zeros counted), against the dense int8 MFMA peak; "
-                    "duration = HIP events around 200 back-to-back launches of this kernel after the timed steps",
+                    "duration = HIP events around 200 back-to-back launches of this kernel (5 replays of a 40-launch graph) after the timed steps",
             "duration_us": round(dom_us, 2),
         },
         "kernels": {
