@@ -120,7 +120,7 @@ __device__ __forceinline__ void encode_group(const float (&x)[M], float s, uint3
 // Requires: N*BITS and N*IB in {2,4,8,16,32}, packed row strides that are multiples of 4 bytes,
 // ldw % 4 == 0 and a 16-byte aligned W.
 // ---------------------------------------------------------------------------------------------
-template <int N, int M, int BITS, int WPR>
+template <int N, int M, int BITS, int WPR, int RES>
 __global__ void __launch_bounds__(256)
 compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
                      uint32_t* __restrict__ vals, uint32_t* __restrict__ meta, float* __restrict__ scales,
@@ -132,7 +132,7 @@ compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
     constexpr int VL = 32 / VB;            // lanes per value dword
     constexpr int ML = 32 / MB;            // lanes per index dword
     constexpr int F4 = M / 4;              // 16-byte loads per group
-    constexpr int RES = 16 / F4;           // register-resident passes per wavefront (64 floats per lane)
+    static_assert(RES * F4 <= 16, "at most 64 floats per lane stay in registers");
     constexpr int RPB = 4 / WPR;           // rows per workgroup
     constexpr float QMAX = (float)((1 << (BITS - 1)) - 1);
 
@@ -304,23 +304,43 @@ decompress_kernel(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ 
     for (int c = 0; c < M; ++c) dst[c] = out[c];
 }
 
+template <int N, int M, int BITS, int WPR, int RES>
+void launch_wave_res(const float* W, int rows, int cols, int ldw, uint32_t* v, uint32_t* m, float* scales,
+                     int vstride, int mstride, hipStream_t st)
+{
+    constexpr int RPB = 4 / WPR;
+    hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, WPR, RES>), dim3((rows + RPB - 1) / RPB), dim3(256), 0, st,
+                       W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4);
+}
+
+// WPR = wavefronts per row: enough that a wavefront walks at most ~4 passes of 64 groups.  RES =
+// passes a wavefront keeps in registers: the smallest compiled size that holds its share of the
+// row (the loops over passes unroll completely, so an oversized RES costs instructions for
+// nothing); rows too long for the largest size are read twice.
+template <int N, int M, int BITS, int WPR>
+void launch_wave_wpr(const float* W, int rows, int cols, int ldw, uint32_t* v, uint32_t* m, float* scales,
+                     int vstride, int mstride, hipStream_t st)
+{
+    constexpr int MAXRES = 16 / (M / 4);
+    const int passes = (cols / M + 63) / 64;
+    const int mine = (passes + WPR - 1) / WPR;                 // of wavefront 0, the longest share
+    if (mine <= 1) launch_wave_res<N, M, BITS, WPR, 1>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
+    else if (mine <= 2) launch_wave_res<N, M, BITS, WPR, 2>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
+    else if (mine <= 3) launch_wave_res<N, M, BITS, WPR, 3>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
+    else if (mine <= 4) launch_wave_res<N, M, BITS, WPR, 4>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
+    else launch_wave_res<N, M, BITS, WPR, MAXRES>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
+}
+
 template <int N, int M, int BITS>
 void launch_wave(const float* W, int rows, int cols, int ldw, void* vals, void* meta, float* scales,
                  int vstride, int mstride, hipStream_t st)
 {
-    // wavefronts per row: enough that a wavefront walks at most ~4 passes of 64 groups
     const int passes = (cols / M + 63) / 64;
     uint32_t* v = (uint32_t*)vals;
     uint32_t* m = (uint32_t*)meta;
-    if (passes > 8)
-        hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, 4>), dim3(rows), dim3(256), 0, st,
-                           W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4);
-    else if (passes > 4)
-        hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, 2>), dim3((rows + 1) / 2), dim3(256), 0, st,
-                           W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4);
-    else
-        hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, 1>), dim3((rows + 3) / 4), dim3(256), 0, st,
-                           W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4);
+    if (passes > 8) launch_wave_wpr<N, M, BITS, 4>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
+    else if (passes > 4) launch_wave_wpr<N, M, BITS, 2>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
+    else launch_wave_wpr<N, M, BITS, 1>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
 }
 
 }  // namespace
