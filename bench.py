@@ -249,6 +249,23 @@ def main():
         },
     }
 
+    # ---- the skinny shape (one 768x768 layer, 128 tokens): latency-bound, reported as HBM GB/s ------
+    if args.workload == "bert_base" and args.only is None:
+        gs, Ws, Xs, sxs = synth.config1_tensors()
+        js = dict(g=gs, sx=float(sxs), W=torch.from_numpy(Ws).to(dev), X=torch.from_numpy(Xs).to(dev),
+                  bias=torch.zeros(gs.O, dtype=torch.float32, device=dev))
+        vb, mb, _ = nm.nm_packed_sizes(gs.O, gs.K, gs.N, gs.M, gs.bits)
+        js.update(vals=torch.empty(vb, dtype=torch.uint8, device=dev), meta=torch.empty(mb, dtype=torch.uint8, device=dev),
+                  scales=torch.empty(gs.O, dtype=torch.float32, device=dev),
+                  out=torch.empty((gs.T, gs.O), dtype=out_torch, device=dev))
+        check(lib.nm_compress(*compress_args(js)))
+        us = timed_launches(lib.nm_gemm, gemm_args(js), 40)
+        esz = 2 if args.out_dtype == "bf16" else 4
+        nbytes = gs.T * gs.K + vb + mb + 8 * gs.O + gs.T * gs.O * esz
+        result["kernels"]["skinny_gemm_128x768x768"] = {
+            "us_back_to_back": round(us, 2), "algorithmic_bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1),
+            "dense_equiv_tops": round(gs.dense_ops / us / 1e6, 1)}
+
     # ---- CPU oracle on a bounded sample of the same workload --------------------------------
     if not args.no_cpu_baseline:
         import oracle
