@@ -207,6 +207,20 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, const uint8_t* src)
                  : "memory");
 }
 
+// The same with the address split into a scalar base and a 32-bit per-lane byte offset (no 64-bit
+// vector arithmetic to form it).  `base` must be the same in every lane.
+__device__ __forceinline__ void dma16s(uint32_t lds_addr, uint32_t offset, const uint8_t* base)
+{
+    lds_addr = (uint32_t)__builtin_amdgcn_readfirstlane((int)lds_addr);
+    const uint64_t b = (uint64_t)(uintptr_t)base;
+    const uint64_t sb = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(b >> 32)) << 32) |
+                        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)b);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(offset), "s"(sb)
+                 : "memory");
+}
+
 template <int CNT>
 __device__ __forceinline__ void wait_vm()
 {

@@ -75,12 +75,20 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     }
     // (Issued before every direct load: the in-order counter then never has to account for them.)
 
-    // ---- per-lane source pointers of this wavefront's PER_WAVE loads --------------------------
+    // ---- sources of this wavefront's PER_WAVE loads per stage ---------------------------------
     // Load p of wave w fills block b = p * NW + w of the stage; blocks past the last real one are
-    // padding and refetch it.
+    // padding and refetch it.  Which array a block belongs to depends on the wavefront only, so
+    // its base address and its step along K are scalars; each lane keeps a 32-bit byte offset
+    // that is advanced in place after every issue.  (The inner loop is bound by the number of
+    // instructions a wavefront has to issue - one per four cycles - so every one saved counts.)
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const uint8_t* src[PER_WAVE];
-    uint32_t step[PER_WAVE];                   // bytes per stage along the source row
+    uint32_t voff[PER_WAVE];                   // this lane's byte offset from sbase[p], at the next stage to issue
+    const uint8_t* sbase[PER_WAVE];
+    uint32_t stepb[PER_WAVE];                  // bytes per stage along the source row
+    // Workgroups walk K in rotated order (stage j of this workgroup is K block (kstart + j) mod ns;
+    // integer sums do not care), so that workgroups sharing rows of X do not all miss on the same
+    // lines at the same moment.
+    const int kstart = (int)(((unsigned)tile * 7u) % (unsigned)ns);
 #pragma unroll
     for (int p = 0; p < PER_WAVE; ++p) {
         const int b = min(p * NW + wave_u, G::BLOCKS - 1);
@@ -89,36 +97,43 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
             const int row = (b % (BT / 8)) * 8 + (lane >> 3);
             const int chunk = (lane & 7) ^ ((row >> 1) & 7);
             const int trow = min(t0 + row, a.tokens - 1);
-            src[p] = reinterpret_cast<const uint8_t*>(a.X) + (size_t)trow * a.ldx + sub * 128 + chunk * 16;
-            step[p] = 128 * KU;
+            sbase[p] = reinterpret_cast<const uint8_t*>(a.X);
+            stepb[p] = 128 * KU;
+            voff[p] = (uint32_t)trow * (uint32_t)a.ldx + sub * 128 + chunk * 16;
         } else if (b < G::X_BLOCKS + G::V_BLOCKS) {
             const int q = (b - G::X_BLOCKS) * 64 + lane;       // 16-byte slot index in the codes array
             const int row = min(q / (G::RV / 16), BO - 1);
             const int slot = q % (G::RV / 16);
             const int chunk = G::V_SWIZZLE ? (slot ^ ((row >> 1) & 7)) : slot;
             const int orow = min(o0 + row, a.O - 1);
-            src[p] = a.vals + (size_t)orow * a.vstride + chunk * 16;
-            step[p] = G::RV;
+            sbase[p] = a.vals;
+            stepb[p] = G::RV;
+            voff[p] = (uint32_t)orow * (uint32_t)a.vstride + chunk * 16;
         } else {
             const int q = (b - G::X_BLOCKS - G::V_BLOCKS) * 64 + lane;
             const int row = min(q / (G::RM / 16), BO - 1);
             const int orow = min(o0 + row, a.O - 1);
-            src[p] = a.meta + (size_t)orow * a.mstride + (q % (G::RM / 16)) * 16;
-            step[p] = G::RM;
+            sbase[p] = a.meta;
+            stepb[p] = G::RM;
+            voff[p] = (uint32_t)orow * (uint32_t)a.mstride + (q % (G::RM / 16)) * 16;
         }
+        voff[p] += (uint32_t)kstart * stepb[p];
     }
-    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
-
-    // Workgroups walk K in rotated order (stage j of this workgroup is K block (kstart + j) mod ns;
-    // integer sums do not care), so that workgroups sharing rows of X do not all miss on the same
-    // lines at the same moment.
-    const int kstart = (int)(((unsigned)tile * 7u) % (unsigned)ns);
-    auto issue = [&](int j, int stage) __attribute__((always_inline)) {
-        int k = kstart + j;
-        if (k >= ns) k -= ns;
+    const uint32_t lds_mine = (uint32_t)(uintptr_t)smem + (uint32_t)wave_u * 1024u;
+    int k_issue = kstart;                      // K block of the next stage to issue
+    // Issues the next stage of the stream into ring slot SLOT (a compile-time value).
+    auto issue = [&](auto slot) __attribute__((always_inline)) {
+        constexpr int SLOT = decltype(slot)::value;
 #pragma unroll
-        for (int p = 0; p < PER_WAVE; ++p)
-            dma16(lds0 + stage * STAGE + (p * NW + wave_u) * 1024, src[p] + (uint32_t)k * step[p]);
+        for (int p = 0; p < PER_WAVE; ++p) {
+            dma16s(lds_mine + (SLOT * STAGE + p * NW * 1024), voff[p], sbase[p]);
+            voff[p] += stepb[p];
+        }
+        if (++k_issue == ns) {                 // wrapped: back to K block 0
+            k_issue = 0;
+#pragma unroll
+            for (int p = 0; p < PER_WAVE; ++p) voff[p] -= (uint32_t)ns * stepb[p];
+        }
     };
 
     v4i acc[FO][FT];
@@ -147,9 +162,9 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         v8i b[FT];
         typename U::Raw w[FO];
     };
-    auto fetch = [&](int stage, auto sub, Frags& f) __attribute__((always_inline)) {
+    auto fetch = [&](auto slot, auto sub, Frags& f) __attribute__((always_inline)) {
         constexpr int s = decltype(sub)::value;
-        const uint8_t* base = smem + stage * STAGE;
+        const uint8_t* base = smem + decltype(slot)::value * STAGE;
 #pragma unroll
         for (int ft = 0; ft < FT; ++ft) {
             const v4i lo = *reinterpret_cast<const v4i*>(base + s * G::X_SUB + frag_x_lo + ft * 16 * 128);
@@ -181,67 +196,127 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         }
     };
 
+    // Large wave tiles (four or more token fragments per wavefront, single-slice stages): two full
+    // fragment sets would not fit the register file, so the token fragments are single-buffered in
+    // two halves instead - while the MFMAs of one half run, the other half (of this slice, then of
+    // the next) is read - and only the weight fragments are double-buffered.
+    constexpr bool SPLIT = (KU == 1 && FT >= 4 && FT % 2 == 0);
+    constexpr int HT = FT / 2;
+    v8i bq[SPLIT ? FT : 1];
+    typename U::Raw wq[2][SPLIT ? FO : 1];
+    auto fetch_b = [&](auto slot, auto half) __attribute__((always_inline)) {
+        const uint8_t* base = smem + decltype(slot)::value * STAGE;
+#pragma unroll
+        for (int i = 0; i < HT; ++i) {
+            const int ft = decltype(half)::value * HT + i;
+            const v4i lo = *reinterpret_cast<const v4i*>(base + frag_x_lo + ft * 16 * 128);
+            const v4i hi = *reinterpret_cast<const v4i*>(base + frag_x_hi + ft * 16 * 128);
+            bq[ft] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
+    };
+    auto fetch_w = [&](auto slot, auto set) __attribute__((always_inline)) {
+        const uint8_t* base = smem + decltype(slot)::value * STAGE;
+#pragma unroll
+        for (int fo = 0; fo < FO; ++fo)
+            wq[decltype(set)::value][fo] = U::load(base + frag_v[0] + fo * 16 * G::RV, base + frag_m + fo * 16 * G::RM, 0);
+    };
+    auto mma_half = [&](auto set, auto half) __attribute__((always_inline)) {
+#pragma unroll
+        for (int fo = 0; fo < FO; ++fo) {
+            v4i codes; int pos;
+            U::decode(wq[decltype(set)::value][fo], codes, pos);
+#pragma unroll
+            for (int i = 0; i < HT; ++i) {
+                const int ft = decltype(half)::value * HT + i;
+                acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(codes, bq[ft], acc[fo][ft], pos, 0, 0);
+            }
+        }
+    };
+    // READS LDS reads against FO * HT MFMAs: the surplus first, then one for one.
+    auto interleave_half = [&](auto reads) __attribute__((always_inline)) {
+        constexpr int READS = decltype(reads)::value, MMAS = FO * HT;
+        if constexpr (READS > MMAS) __builtin_amdgcn_sched_group_barrier(0x100, READS - MMAS, 0);
+#pragma unroll
+        for (int i = 0; i < MMAS; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
+        }
+    };
+
     // ---- pipeline -----------------------------------------------------------------------------
     // Ring of STAGES stages, stream stage j in ring slot j % STAGES.  While stage j is being
     // multiplied, stages j+1 .. j+AHEAD are in flight or landed, and the slot of stage j-1 (whose
-    // reads every wavefront has consumed before the barrier) is refilled.
+    // reads every wavefront has consumed before the barrier) is refilled.  The loop body covers
+    // UNROLL consecutive stages so that ring slots and fragment sets are compile-time values:
+    // no slot arithmetic, LDS addresses fold into instruction offsets.
     constexpr int AHEAD = STAGES - 2;
     static_assert(AHEAD >= 1, "at least three stages");
     static_assert(AHEAD * PER_WAVE < 64, "loads in flight must fit the counter");
-#pragma unroll
-    for (int j = 0; j <= AHEAD; ++j)
-        if (j < ns) issue(j, j % STAGES);
+    int_for<AHEAD + 1>([&](auto jj) __attribute__((always_inline)) {
+        if (decltype(jj)::value < ns) issue(std::integral_constant<int, decltype(jj)::value % STAGES>{});
+    });
 
     Frags fr[2];
     if (ns > AHEAD) wait_vm<AHEAD * PER_WAVE>();             // stage 0 landed; the AHEAD behind it may still fly
     else wait_vm<0>();
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    fetch(0, std::integral_constant<int, 0>{}, fr[0]);
+    if constexpr (SPLIT) {
+        fetch_w(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        fetch_b(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    } else {
+        fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, fr[0]);
+    }
 
-    int slot_c = 0;                             // ring slot of the stage being multiplied
-    int slot_i = (AHEAD + 1) % STAGES;          // ring slot the next issue refills
-    // Everything needed before the fragments of the first slice of stage j+1 can be read.
-    auto advance = [&](int j) __attribute__((always_inline)) {
+    // Everything needed before the fragments of the first slice of stage j+1 can be read; SLOT is
+    // the ring slot of stage j.
+    auto advance = [&](int j, auto slot) __attribute__((always_inline)) {
+        constexpr int SLOT = decltype(slot)::value;
         if (j + 1 < ns) {
             // stages j+1 .. min(j+AHEAD, ns-1) are in flight, oldest first
             if (j + AHEAD < ns) wait_vm<(AHEAD - 1) * PER_WAVE>();
             else wait_vm<0>();
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            if (j + 1 + AHEAD < ns) issue(j + 1 + AHEAD, slot_i);
+            if (j + 1 + AHEAD < ns) issue(std::integral_constant<int, (SLOT + AHEAD + 1) % STAGES>{});
         }
-        slot_c = (slot_c + 1 == STAGES) ? 0 : slot_c + 1;
-        slot_i = (slot_i + 1 == STAGES) ? 0 : slot_i + 1;
     };
     // The fragment fetch is unconditional (after the last slice it re-reads an idle slot and the
     // values are dropped) so that the two register sets never merge across a branch.
-    if constexpr (KU == 2) {
-        for (int j = 0; j < ns; ++j) {
-            mma(fr[0]);
-            fetch(slot_c, std::integral_constant<int, 1>{}, fr[1]);
-            interleave();
-            advance(j);
-            mma(fr[1]);
-            fetch(slot_c, std::integral_constant<int, 0>{}, fr[0]);
-            interleave();
-        }
-    } else {
-        int j = 0;
-        for (; j + 2 <= ns; j += 2) {
-            advance(j);
-            mma(fr[0]);
-            fetch(slot_c, std::integral_constant<int, 0>{}, fr[1]);
-            interleave();
-            advance(j + 1);
-            mma(fr[1]);
-            fetch(slot_c, std::integral_constant<int, 0>{}, fr[0]);
-            interleave();
-        }
-        if (j < ns) {
-            advance(j);
-            mma(fr[0]);
-        }
+    constexpr int UNROLL = (KU == 2 || STAGES % 2 == 0) ? STAGES : 2 * STAGES;
+    for (int j0 = 0; j0 < ns; j0 += UNROLL) {
+        int_for<UNROLL>([&](auto ss) __attribute__((always_inline)) {
+            constexpr int S = decltype(ss)::value;
+            constexpr int SLOT = S % STAGES, NEXT = (S + 1) % STAGES;
+            const int j = j0 + S;
+            if (j < ns) {
+                if constexpr (KU == 2) {
+                    mma(fr[0]);
+                    fetch(std::integral_constant<int, SLOT>{}, std::integral_constant<int, 1>{}, fr[1]);
+                    interleave();
+                    advance(j, std::integral_constant<int, SLOT>{});
+                    mma(fr[1]);
+                    fetch(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 0>{}, fr[0]);
+                    interleave();
+                } else if constexpr (SPLIT) {
+                    // first half of the token fragments, while the second half is read
+                    fetch_b(std::integral_constant<int, SLOT>{}, std::integral_constant<int, 1>{});
+                    mma_half(std::integral_constant<int, S % 2>{}, std::integral_constant<int, 0>{});
+                    interleave_half(std::integral_constant<int, 2 * HT>{});
+                    advance(j, std::integral_constant<int, SLOT>{});
+                    // second half, while the next slice's weights and first half are read
+                    fetch_w(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 1 - S % 2>{});
+                    fetch_b(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 0>{});
+                    mma_half(std::integral_constant<int, S % 2>{}, std::integral_constant<int, 1>{});
+                    interleave_half(std::integral_constant<int, 2 * HT + 2 * FO>{});
+                } else {
+                    advance(j, std::integral_constant<int, SLOT>{});
+                    mma(fr[S % 2]);
+                    fetch(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 0>{}, fr[1 - S % 2]);
+                    interleave();
+                }
+            }
+        });
     }
 
     // ---- epilogue: Eq. 4 with offset 0 on the product of two quantised operands --------------
@@ -328,6 +403,8 @@ bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
     constexpr size_t lds = (size_t)STAGES * PER_WAVE * NW * 1024;
     static_assert(lds <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
     if ((a.K / 128) % KU != 0) return false;
+    // per-lane source offsets are 32-bit
+    if ((unsigned long long)a.tokens * a.ldx >= (1ull << 32) || (unsigned long long)a.O * a.vstride >= (1ull << 32)) return false;
     const int tiles_t = (a.tokens + BT - 1) / BT, tiles_o = (a.O + BO - 1) / BO;
     const int n_tiles = tiles_t * tiles_o;
     const int grid = 8 * ((n_tiles + 7) / 8);
@@ -343,9 +420,10 @@ bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
     return true;
 }
 
-// Tile choice.  The kernel is bound by what one CU can pull through its L1 (about 50 B/clk), so
-// the tile wants to be as large as the CU count allows: 128 x 96 gives BERT-base's 768-wide
-// layers exactly 256 workgroups at 4096 tokens.  Rings of at most 80 KB let two workgroups share
+// Tile choice.  The kernel is bound by the LDS (direct-load writes at the L1 fill rate of 64 B/clk
+// plus fragment reads), so the tile wants to be as large as the CU count allows: 256 x 192 where
+// that still gives every CU a tile, else 128 x 96 (exactly 256 workgroups for BERT-base's 768-wide
+// layers at 4096 tokens).  Rings of at most 80 KB let two workgroups share
 // a CU, which overlaps one's epilogue with the other's prologue when there are several rounds.
 // Stage rows must be whole 16-byte pieces, which decides whether a pattern can use
 // single-slice stages (KU = 1) or needs 256-column stages (KU = 2).
@@ -357,8 +435,10 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
     const bool k256 = (a.K % 256) == 0;
     if (cfg == 0) {
         const long long n96 = (long long)((a.tokens + 127) / 128) * ((a.O + 95) / 96);
+        const long long n192 = (long long)((a.tokens + 255) / 256) * (a.O / 192);
         if (!KU1) cfg = (n96 <= 256) ? 113 : 119;               // 256-column stages only: 128 x 96, or 64 x 96 twice per CU
         else if (!U::IDENTITY) cfg = 116;                        // decode work favours the smaller ring
+        else if (a.O % 192 == 0 && n192 >= 176) cfg = 122;       // wide layers: 256 x 192, a quarter of the LDS fill per MAC
         else if (n96 <= 256 && k256) cfg = 113;                  // one round: deepest ring, 256-column stages
         else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
         else cfg = 116;                                          // 128 x 96, two workgroups per CU
@@ -377,6 +457,7 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
             case 115: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
             case 117: return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
             case 121: return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
+            case 122: return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
             default: break;
         }
     }
