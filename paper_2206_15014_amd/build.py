@@ -19,22 +19,40 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc, *HIPCC_FLAGS, "-o", tmp, *[os.path.join(CSRC, s) for s in SOURCES]]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     noise = ("packed-fp32-ops", "1 warning generated", "warnings generated")
     out = "\n".join(l for l in res.stdout.splitlines() if not any(n in l for n in noise))
     if res.returncode != 0:
-        if os.path.exists(tmp):
-            os.unlink(tmp)
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    os.replace(tmp, LIB)
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every source to an object (in parallel, one hipcc each) and link them into libnm.so.
+    Objects live in a temporary directory, so the tree only ever holds sources and the library."""
+    import concurrent.futures
+    import shutil
+    import tempfile
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    tmpdir = tempfile.mkdtemp(prefix="libnm_build_")
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    try:
+        objs = [os.path.join(tmpdir, s.replace(".hip", ".o")) for s in SOURCES]
+        jobs = [[hipcc, *compile_flags, "-c", "-o", o, os.path.join(CSRC, s)] for s, o in zip(SOURCES, objs)]
+        workers = max(1, min(len(jobs), (os.cpu_count() or 2), 8))
+        with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as pool:
+            list(pool.map(lambda c: _run(c, verbose), jobs))
+        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs], verbose)
+        os.replace(tmp, LIB)
+    finally:
+        shutil.rmtree(tmpdir, ignore_errors=True)
+        if os.path.exists(tmp):
+            os.unlink(tmp)
     return LIB
 
 

@@ -404,11 +404,6 @@ bool launch_xstat_pattern(const GemmArgs& a, hipStream_t st, int cfg)
             case 301:                                            // 128 x 96, 8 wavefronts, 4 weight stages
                 return f32 ? launch_xstat_es<N, M, BITS, 128, 96, 4, 2, 4, 6, 2, 4>(a, st)
                            : launch_xstat_es<N, M, BITS, 128, 96, 4, 2, 4, 6, 1, 2>(a, st);
-            // experiments: K <= 512, ring depth 3 / 4 / 6 / 8
-            case 303: return f32 ? false : launch_xstat_es<N, M, BITS, 128, 96, 4, 2, 3, 4, 1, 2>(a, st);
-            case 304: return f32 ? false : launch_xstat_es<N, M, BITS, 128, 96, 4, 2, 4, 4, 1, 2>(a, st);
-            case 306: return f32 ? false : launch_xstat_es<N, M, BITS, 128, 96, 4, 2, 6, 4, 1, 2>(a, st);
-            case 308: return f32 ? false : launch_xstat_es<N, M, BITS, 128, 96, 4, 2, 8, 4, 2, 2>(a, st);
             default: return false;
         }
     }
