@@ -437,8 +437,8 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
         const long long n96 = (long long)((a.tokens + 127) / 128) * ((a.O + 95) / 96);
         const long long n192 = (long long)((a.tokens + 255) / 256) * (a.O / 192);
         if (!KU1) cfg = (n96 <= 256) ? 113 : 119;               // 256-column stages only: 128 x 96, or 64 x 96 twice per CU
-        else if (!U::IDENTITY) cfg = 116;                        // decode work favours the smaller ring
         else if (a.O % 192 == 0 && n192 >= 176) cfg = 122;       // wide layers: 256 x 192, a quarter of the LDS fill per MAC
+        else if (!U::IDENTITY) cfg = 116;                        // decode work favours the smaller ring
         else if (n96 <= 256 && k256) cfg = 113;                  // one round: deepest ring, 256-column stages
         else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
         else cfg = 116;                                          // 128 x 96, two workgroups per CU
@@ -449,6 +449,7 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
     if constexpr (KU1) {
         if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
         if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
+        if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
     }
     if constexpr (U::IDENTITY) {                                 // further shapes, kept selectable for tuning
         switch (cfg) {
@@ -457,7 +458,6 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
             case 115: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
             case 117: return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
             case 121: return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
-            case 122: return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
             default: break;
         }
     }
