@@ -181,8 +181,14 @@ struct Unit {
 template <int N, int M, int BITS, int BT, int BO, int KU>
 struct DmaGeom {
     using U = Unit<N, M, BITS>;
-    static constexpr int RV = 4 * U::VBYTES * KU;            // packed value bytes per row per stage
-    static constexpr int RM = 4 * U::MBYTES * KU;            // packed index bytes per row per stage
+    static constexpr int RVS = 4 * U::VBYTES * KU;           // packed value bytes per row per stage, in memory
+    static constexpr int RMS = 4 * U::MBYTES * KU;           // packed index bytes per row per stage, in memory
+    // A direct load moves 16-byte pieces.  An array with only 8 bytes per row and stage is staged
+    // as the 16-byte piece that holds two consecutive stages ("pair"): every stage loads the piece
+    // its K block lies in and reads its own half.
+    static constexpr bool PAIR_V = (RVS == 8), PAIR_M = (RMS == 8);
+    static constexpr int RV = PAIR_V ? 16 : RVS;             // bytes per row in the LDS stage
+    static constexpr int RM = PAIR_M ? 16 : RMS;
     static_assert(RV % 16 == 0 && RM % 16 == 0, "rows must be whole 16-byte chunks");
     static constexpr bool V_SWIZZLE = (RV == 128);           // 8 chunks per row: same XOR as the X rows
     static constexpr int X_SUB = BT * 128;                   // bytes of one 128-column slice of X

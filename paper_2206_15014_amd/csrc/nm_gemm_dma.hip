@@ -88,9 +88,12 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     // Workgroups walk K in rotated order (stage j of this workgroup is K block (kstart + j) mod ns;
     // integer sums do not care), so that workgroups sharing rows of X do not all miss on the same
     // lines at the same moment.
-    const int kstart = (int)(((unsigned)tile * 7u) % (unsigned)ns);
+    constexpr bool PAIR = G::PAIR_V || G::PAIR_M;        // then stage parity must equal K block parity: even start, even ns
+    const int kstart = (int)(((unsigned)tile * 7u) % (unsigned)ns) & (PAIR ? ~1 : ~0);
+    uint32_t amask[PER_WAVE];                  // pair arrays: the load address is rounded down to the 16-byte piece
 #pragma unroll
     for (int p = 0; p < PER_WAVE; ++p) {
+        amask[p] = ~0u;
         const int b = min(p * NW + wave_u, G::BLOCKS - 1);
         if (b < G::X_BLOCKS) {
             const int sub = b / (BT / 8);
@@ -107,14 +110,16 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
             const int chunk = G::V_SWIZZLE ? (slot ^ ((row >> 1) & 7)) : slot;
             const int orow = min(o0 + row, a.O - 1);
             sbase[p] = a.vals;
-            stepb[p] = G::RV;
+            stepb[p] = G::RVS;
+            if (G::PAIR_V) amask[p] = ~15u;
             voff[p] = (uint32_t)orow * (uint32_t)a.vstride + chunk * 16;
         } else {
             const int q = (b - G::X_BLOCKS - G::V_BLOCKS) * 64 + lane;
             const int row = min(q / (G::RM / 16), BO - 1);
             const int orow = min(o0 + row, a.O - 1);
             sbase[p] = a.meta;
-            stepb[p] = G::RM;
+            stepb[p] = G::RMS;
+            if (G::PAIR_M) amask[p] = ~15u;
             voff[p] = (uint32_t)orow * (uint32_t)a.mstride + (q % (G::RM / 16)) * 16;
         }
         voff[p] += (uint32_t)kstart * stepb[p];
@@ -126,7 +131,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         constexpr int SLOT = decltype(slot)::value;
 #pragma unroll
         for (int p = 0; p < PER_WAVE; ++p) {
-            dma16s(lds_mine + (SLOT * STAGE + p * NW * 1024), voff[p], sbase[p]);
+            dma16s(lds_mine + (SLOT * STAGE + p * NW * 1024), PAIR ? (voff[p] & amask[p]) : voff[p], sbase[p]);
             voff[p] += stepb[p];
         }
         if (++k_issue == ns) {                 // wrapped: back to K block 0
@@ -162,8 +167,10 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         v8i b[FT];
         typename U::Raw w[FO];
     };
-    auto fetch = [&](auto slot, auto sub, Frags& f) __attribute__((always_inline)) {
+    // `par` = parity of the stage (selects the half of a pair row)
+    auto fetch = [&](auto slot, auto sub, Frags& f, auto par) __attribute__((always_inline)) {
         constexpr int s = decltype(sub)::value;
+        constexpr int PV = G::PAIR_V ? 8 * decltype(par)::value : 0, PM = G::PAIR_M ? 8 * decltype(par)::value : 0;
         const uint8_t* base = smem + decltype(slot)::value * STAGE;
 #pragma unroll
         for (int ft = 0; ft < FT; ++ft) {
@@ -173,7 +180,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         }
 #pragma unroll
         for (int fo = 0; fo < FO; ++fo)
-            f.w[fo] = U::load(base + frag_v[s] + fo * 16 * G::RV, base + frag_m + s * 4 * U::MBYTES + fo * 16 * G::RM, 0);
+            f.w[fo] = U::load(base + frag_v[s] + PV + fo * 16 * G::RV, base + frag_m + PM + s * 4 * U::MBYTES + fo * 16 * G::RM, 0);
     };
     auto mma = [&](const Frags& f) __attribute__((always_inline)) {
 #pragma unroll
@@ -214,11 +221,12 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
             bq[ft] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         }
     };
-    auto fetch_w = [&](auto slot, auto set) __attribute__((always_inline)) {
+    auto fetch_w = [&](auto slot, auto set, auto par) __attribute__((always_inline)) {
+        constexpr int PV = G::PAIR_V ? 8 * decltype(par)::value : 0, PM = G::PAIR_M ? 8 * decltype(par)::value : 0;
         const uint8_t* base = smem + decltype(slot)::value * STAGE;
 #pragma unroll
         for (int fo = 0; fo < FO; ++fo)
-            wq[decltype(set)::value][fo] = U::load(base + frag_v[0] + fo * 16 * G::RV, base + frag_m + fo * 16 * G::RM, 0);
+            wq[decltype(set)::value][fo] = U::load(base + frag_v[0] + PV + fo * 16 * G::RV, base + frag_m + PM + fo * 16 * G::RM, 0);
     };
     auto mma_half = [&](auto set, auto half) __attribute__((always_inline)) {
 #pragma unroll
@@ -262,10 +270,10 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if constexpr (SPLIT) {
-        fetch_w(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        fetch_w(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
         fetch_b(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     } else {
-        fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, fr[0]);
+        fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, fr[0], std::integral_constant<int, 0>{});
     }
 
     // Everything needed before the fragments of the first slice of stage j+1 can be read; SLOT is
@@ -292,11 +300,11 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
             if (j < ns) {
                 if constexpr (KU == 2) {
                     mma(fr[0]);
-                    fetch(std::integral_constant<int, SLOT>{}, std::integral_constant<int, 1>{}, fr[1]);
+                    fetch(std::integral_constant<int, SLOT>{}, std::integral_constant<int, 1>{}, fr[1], std::integral_constant<int, 0>{});
                     interleave();
                     advance(j, std::integral_constant<int, SLOT>{});
                     mma(fr[1]);
-                    fetch(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 0>{}, fr[0]);
+                    fetch(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 0>{}, fr[0], std::integral_constant<int, 0>{});
                     interleave();
                 } else if constexpr (SPLIT) {
                     // first half of the token fragments, while the second half is read
@@ -305,14 +313,14 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
                     interleave_half(std::integral_constant<int, 2 * HT>{});
                     advance(j, std::integral_constant<int, SLOT>{});
                     // second half, while the next slice's weights and first half are read
-                    fetch_w(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 1 - S % 2>{});
+                    fetch_w(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 1 - S % 2>{}, std::integral_constant<int, (S + 1) % 2>{});
                     fetch_b(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 0>{});
                     mma_half(std::integral_constant<int, S % 2>{}, std::integral_constant<int, 1>{});
                     interleave_half(std::integral_constant<int, 2 * HT + 2 * FO>{});
                 } else {
                     advance(j, std::integral_constant<int, SLOT>{});
                     mma(fr[S % 2]);
-                    fetch(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 0>{}, fr[1 - S % 2]);
+                    fetch(std::integral_constant<int, NEXT>{}, std::integral_constant<int, 0>{}, fr[1 - S % 2], std::integral_constant<int, (S + 1) % 2>{});
                     interleave();
                 }
             }
@@ -431,14 +439,16 @@ template <int N, int M, int BITS>
 bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 {
     using U = Unit<N, M, BITS>;
-    constexpr bool KU1 = (4 * U::VBYTES) % 16 == 0 && (4 * U::MBYTES) % 16 == 0;
     const bool k256 = (a.K % 256) == 0;
+    // patterns with 8 bytes of codes or index bits per row and 128 columns stage them in pairs of
+    // K blocks, which needs an even number of blocks
+    constexpr bool PAIR = (4 * U::VBYTES) == 8 || (4 * U::MBYTES) == 8;
+    if (PAIR && !k256) return false;
     if (cfg == 0) {
         const long long n96 = (long long)((a.tokens + 127) / 128) * ((a.O + 95) / 96);
         const long long n192 = (long long)((a.tokens + 255) / 256) * (a.O / 192);
-        if (!KU1) cfg = (n96 <= 256) ? 113 : 119;               // 256-column stages only: 128 x 96, or 64 x 96 twice per CU
-        else if (a.O % 192 == 0 && n192 >= 176) cfg = 122;       // wide layers: 256 x 192, a quarter of the LDS fill per MAC
-        else if (!U::IDENTITY) cfg = 116;                        // decode work favours the smaller ring
+        if (a.O % 192 == 0 && n192 >= 176) cfg = 122;            // wide layers: 256 x 192, a quarter of the LDS fill per MAC
+        else if (!U::IDENTITY) cfg = 116;                        // decode work favours single-slice stages
         else if (n96 <= 256 && k256) cfg = 113;                  // one round: deepest ring, 256-column stages
         else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
         else cfg = 116;                                          // 128 x 96, two workgroups per CU
@@ -446,11 +456,9 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
     if (cfg == 113) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(a, st);
     if (cfg == 105) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 2>(a, st);
     if (cfg == 119) return launch_dma_tile<N, M, BITS, 64, 96, 2, 2, 3, 2>(a, st);
-    if constexpr (KU1) {
-        if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
-        if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
-        if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
-    }
+    if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
+    if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
+    if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
     if constexpr (U::IDENTITY) {                                 // further shapes, kept selectable for tuning
         switch (cfg) {
             case 101: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 4, 1>(a, st);

@@ -44,6 +44,7 @@ struct StreamGeom {
     static constexpr int SROW_B = BO * ES + 16;                         // staged row stride (the pad spreads banks)
     static constexpr int LDS = ST_OFF + SROWS * SROW_B;
     static_assert(NW % 2 == 0, "half of the wavefronts load, half store");
+    static_assert(!G::PAIR_V && !G::PAIR_M, "whole 16-byte rows per stage only");
     static_assert(LDS <= 160 * 1024, "exceeds the 160 KB of LDS of a CU");
 };
 
