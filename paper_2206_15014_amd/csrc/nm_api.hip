@@ -85,6 +85,7 @@ int nm_gemm(const int8_t* X_dev, int tokens, int K, int ldx, float act_scale,
     const size_t kc = (size_t)K / M * N;
     a.vstride = (int)row_bytes(kc, bits);
     a.mstride = (int)row_bytes(kc, M == 4 ? 2 : 4);
+    a.store_through = 0;
     return nm::launch_gemm(a, static_cast<hipStream_t>(hip_stream));
 }
 

@@ -23,6 +23,7 @@ struct GemmArgs {
     int out_dtype;         // nm_out_dtype
     int ldo;
     int vstride, mstride;  // packed row strides in bytes
+    int store_through;     // set by a launcher: output stores bypass the L2's write-back (large outputs)
 };
 
 // Launch-error bracket: begin_launch() drops any stale error left in this thread by earlier HIP
