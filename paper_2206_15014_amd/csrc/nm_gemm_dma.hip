@@ -311,21 +311,31 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     };
 
     // ---- pipeline -----------------------------------------------------------------------------
-    // Ring of STAGES stages, stream stage j in ring slot j % STAGES.  While stage j is being
-    // multiplied, stages j+1 .. j+AHEAD are in flight or landed, and the slot of stage j-1 (whose
-    // reads every wavefront has consumed before the barrier) is refilled.  The loop body covers
+    // Ring of STAGES stages, stream stage j in ring slot j % STAGES.  Fragments are read into
+    // registers one slice ahead of their MFMAs, so by the barrier of step j every wavefront has
+    // taken the last of stage j out of the LDS (it waits for its own reads first), and the slot
+    // of stage j itself is refilled with stage j+STAGES: all other slots hold stages in flight
+    // or landed, AHEAD = STAGES-1 steps of latency cover for STAGES slots.  The loop body covers
     // UNROLL consecutive stages so that ring slots and fragment sets are compile-time values:
     // no slot arithmetic, LDS addresses fold into instruction offsets.
-    constexpr int AHEAD = STAGES - 2;
-    static_assert(AHEAD >= 1, "at least three stages");
+    constexpr int AHEAD = STAGES - 1;
+    static_assert(AHEAD >= 1, "at least two stages");
     static_assert(AHEAD * PER_WAVE < 64, "loads in flight must fit the counter");
     int_for<AHEAD + 1>([&](auto jj) __attribute__((always_inline)) {
         if (decltype(jj)::value < ns) issue(std::integral_constant<int, decltype(jj)::value % STAGES>{});
     });
 
     Frags fr[2];
-    if (ns > AHEAD) wait_vm<AHEAD * PER_WAVE>();             // stage 0 landed; the AHEAD behind it may still fly
-    else wait_vm<0>();
+    {   // stage 0 landed; the min(ns, STAGES) - 1 stages behind it may still fly
+        bool waited = false;
+        int_for<AHEAD + 1>([&](auto c) __attribute__((always_inline)) {
+            constexpr int BEHIND = AHEAD - decltype(c)::value;
+            if (!waited && ns > BEHIND) {
+                wait_vm<BEHIND * PER_WAVE>();
+                waited = true;
+            }
+        });
+    }
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if constexpr (SPLIT) {
@@ -342,6 +352,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
             // stages j+1 .. min(j+AHEAD, ns-1) are in flight, oldest first
             if (j + AHEAD < ns) wait_vm<(AHEAD - 1) * PER_WAVE>();
             else wait_vm<0>();
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own reads of stage j done: its slot may be refilled
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
         }
