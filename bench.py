@@ -2,8 +2,8 @@
 """Benchmark of the hot path on one MI355X: compress + sparse integer GEMMs of one BERT-base
 encoder layer (QKV, attention output, FFN up, FFN down; 2:4 sparsity, int8 weights, 4096 tokens).
 
-One step = nm_compress of the four fp32 weight matrices followed by nm_gemm of the four layers
-(bias + bf16 output), all on one stream with inputs resident in HBM.  Prints one JSON line:
+One step = for each of the four layers in turn, nm_compress of its fp32 weight matrix and then
+nm_gemm against it (bias + bf16 output), all on one stream with inputs resident in HBM.  Prints one JSON line:
 dense-equivalent int8 TOPS of the whole step, the roofline position of the dominant kernel, and
 the CPU oracle timed on a bounded sample of the same workload.
 """
@@ -124,10 +124,9 @@ def main():
             raise RuntimeError("libnm call failed: %s" % nm.nm_status_string(rc))
 
     def step():
-        for a in cargs:
-            check(lib.nm_compress(*a))
-        for a in gargs:
-            check(lib.nm_gemm(*a))
+        for ca, ga in zip(cargs, gargs):
+            check(lib.nm_compress(*ca))
+            check(lib.nm_gemm(*ga))
 
     side = torch.cuda.Stream()
 
@@ -193,10 +192,9 @@ def main():
             gg = [a[:-1] + (cap_stream,) for a in gargs]
             with torch.cuda.graph(graph, stream=side):
                 for _ in range(steps_per_graph):
-                    for a in cg:
-                        check(lib.nm_compress(*a))
-                    for a in gg:
-                        check(lib.nm_gemm(*a))
+                    for ca, ga in zip(cg, gg):
+                        check(lib.nm_compress(*ca))
+                        check(lib.nm_gemm(*ga))
         torch.cuda.current_stream().wait_stream(side)
         for _ in range(3):
             graph.replay()
@@ -229,8 +227,8 @@ def main():
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": workload_name + "; step = nm_compress x%d + nm_gemm x%d (bias, %s out), %s launch%s"
-                               % (len(gemms), len(gemms), args.out_dtype, args.launch,
+        "config": {"workload": workload_name + "; step = %d x (nm_compress, nm_gemm) layer by layer (bias, %s out), %s launch%s"
+                               % (len(gemms), args.out_dtype, args.launch,
                                   " (%d steps per graph)" % steps_per_graph if graph is not None else ""),
                    "tokens": gemms[0].T, "hidden": 768, "pattern": "2:4", "weight_bits": 8, "out_dtype": args.out_dtype},
         "pct_of_int8_dense_peak": round(100.0 * value / INT8_DENSE_PEAK_TOPS, 2),

@@ -191,6 +191,13 @@ struct DmaGeom {
     static constexpr int RM = PAIR_M ? 16 : RMS;
     static_assert(RV % 16 == 0 && RM % 16 == 0, "rows must be whole 16-byte chunks");
     static constexpr bool V_SWIZZLE = (RV == 128);           // 8 chunks per row: same XOR as the X rows
+    // XOR term for the 16-byte chunk index of a codes row, so that the 16 rows one fragment read
+    // touches spread over all banks: rows 256 bytes apart would otherwise meet in the same banks
+    // (every 2nd row of 128 bytes, every 4th of 64, every 8th of 32).
+    __host__ __device__ static constexpr int v_xor(int row)
+    {
+        return RV == 128 ? ((row >> 1) & 7) : RV == 64 ? ((row >> 2) & 3) : RV == 32 ? ((row >> 3) & 1) : 0;
+    }
     static constexpr int X_SUB = BT * 128;                   // bytes of one 128-column slice of X
     static constexpr int X_BLOCKS = KU * BT * 128 / 1024;
     static constexpr int V_BLOCKS = (BO * RV + 1023) / 1024;

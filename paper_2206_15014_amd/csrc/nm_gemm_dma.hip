@@ -119,7 +119,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
             const int q = (b - G::X_BLOCKS) * 64 + lane;       // 16-byte slot index in the codes array
             const int row = min(q / (G::RV / 16), BO - 1);
             const int slot = q % (G::RV / 16);
-            const int chunk = G::V_SWIZZLE ? (slot ^ ((row >> 1) & 7)) : slot;
+            const int chunk = slot ^ G::v_xor(row);
             const int orow = min(o0 + row, a.O - 1);
             sbase[p] = a.vals;
             stepb[p] = G::RVS;
@@ -188,7 +188,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
 #pragma unroll
     for (int s = 0; s < KU; ++s) {
         const int off = (4 * s + lg) * U::VBYTES;              // byte offset of this lane's unit in the row
-        const int chunk = G::V_SWIZZLE ? ((off >> 4) ^ xsw) : (off >> 4);
+        const int chunk = (off >> 4) ^ G::v_xor(li);
         frag_v[s] = G::V_OFF + (wo * WO + li) * G::RV + chunk * 16 + (off & 15);
     }
     const int frag_m = G::M_OFF + (wo * WO + li) * G::RM + lg * U::MBYTES;
