@@ -1,18 +1,19 @@
-// nm_gemm, X-stationary LDS-direct variant for gfx950: layers with a short reduction dimension
-// (K <= 768, i.e. every BERT-base layer but FFN-down) and several column tiles per token tile.
+// nm_gemm, X-resident LDS-direct variant for gfx950: wide layers with a short reduction dimension
+// (K <= 768: QKV and FFN-up of BERT-base).
 //
-// The ordinary kernels stream, per 128 x 96 output tile and 128-column K step, 16 KB of
-// activations and 7.5 KB of packed weights from L2 into LDS, and that fill - not the MFMA - is
-// what bounds them.  Here a workgroup keeps its whole token tile (128 tokens x K bytes, at most
-// 96 KB) in LDS, loaded once, and walks several column tiles against it: only the packed weights
-// (46 KB per column tile at K = 768) are streamed, through a small ring that never drains between
-// column tiles.  Per output tile two thirds of the fill disappear.
+// The ordinary kernel gives every workgroup one 256 x 192 output tile; at 4096 tokens that is one
+// tile per CU, so a CU loads, multiplies and stores strictly one after the other and the output
+// (the larger part of the layer's memory traffic) leaves while nothing else happens.  Here a
+// workgroup keeps a 128-token tile of X whole in LDS (128 x K bytes, at most 96 KB, each slice
+// loaded once, together with the first weight stages) and walks CT = 2 column tiles of 192
+// against it.  Only packed weights are streamed for the second column tile (15 KB per 128-column
+// slice instead of 31 KB), and the stores of the first column tile drain while the second one is
+// multiplied.
 //
-// As in the persistent kernel, memory instructions are split by wavefront: the lower half of the
-// wavefronts issues every load (all direct-to-LDS, including each column tile's scales and
-// biases), the upper half every store, because a wavefront's memory counter is in-order over
-// loads and stores alike.  Handles dequantised output only (no exact accumulators), whole column
-// tiles and 16-byte aligned output rows; everything else goes to the other kernels.
+// One in-order counter covers a wavefront's loads and stores alike, and the waits below are counted
+// by hand, so the launcher only admits shapes for which every wavefront issues exactly the same
+// memory instructions: whole token tiles, whole column tiles, 16-byte aligned output rows, and a
+// kernel that keeps nothing in scratch.  Everything else goes to the other kernels.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -23,361 +24,327 @@ namespace nm {
 
 namespace {
 
-// KS = 128-column slices of X the LDS area is sized for; EP = passes in which a tile goes through
-// the staging area (BT / EP rows at a time); ES = bytes per output element (4: fp32, 2: bf16).
-template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KS, int EP, int ES>
-struct XstatGeom {
+// KS = most 128-column slices of X the LDS area holds; CT = column tiles per workgroup.
+template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int KS>
+struct XresGeom {
     using G = DmaGeom<N, M, BITS, BT, BO, 1>;
     static constexpr int NW = WAVES_T * WAVES_O;
-    static constexpr int LW = NW / 2;                                   // loading wavefronts 0 .. LW-1
-    static constexpr int SW = NW - LW;                                  // storing wavefronts LW .. NW-1
+    static constexpr int STAGES = 3;                                    // weight ring
+    static constexpr int CT = 2;
     static constexpr int X_SLICE = BT * 128;                            // one 128-column slice of the token tile
-    static constexpr int X_BYTES = KS * X_SLICE;
-    static constexpr int XB_PER_SLICE = BT / 8;                         // 1 KB blocks (8 rows x 128 B) per slice
-    static constexpr int W_BLOCKS = G::V_BLOCKS + G::M_BLOCKS;          // one ring stage: codes then index rows
-    static constexpr int PER_LW = (W_BLOCKS + LW - 1) / LW;             // direct loads per loading wavefront per stage
-    static constexpr int STAGE = PER_LW * LW * 1024;
+    static constexpr int XB = BT / 8;                                   // its 1 KB blocks (8 rows x 128 B)
+    static constexpr int PX = XB / NW;                                  // X loads per wavefront and slice
+    static constexpr int W_BLOCKS = G::V_BLOCKS + G::M_BLOCKS;          // one ring stage: codes, then index rows
+    static constexpr int PW = (W_BLOCKS + NW - 1) / NW;                 // W loads per wavefront and stage
+    static constexpr int STAGE = PW * NW * 1024;
     static constexpr int V_OFF = 0, M_OFF = G::V_BLOCKS * 1024;         // inside a stage
-    static constexpr int RING_OFF = X_BYTES;
-    static constexpr int SB_BLOCKS = (2 * BO * 4 + 1023) / 1024;        // scales then biases of a column tile
-    static constexpr int SB_BYTES = SB_BLOCKS * 1024;
-    static constexpr int SB_OFF = RING_OFF + STAGES * STAGE;            // STAGES buffers, one per tile in flight
-    static constexpr int ST_OFF = SB_OFF + STAGES * SB_BYTES;
-    static constexpr int SROWS = BT / EP;
-    static constexpr int SROW_B = BO * ES + 16;                         // staged row stride (the pad spreads banks)
-    static constexpr int LDS = ST_OFF + SROWS * SROW_B;
-    static_assert(NW % 2 == 0, "half of the wavefronts load, half store");
+    static constexpr int RING_OFF = KS * X_SLICE;
+    static constexpr int SB_OFF = RING_OFF + STAGES * STAGE;            // per column tile: 1 KB scales, 1 KB biases
+    static constexpr int LDS = SB_OFF + CT * 2048;
+    static_assert(XB % NW == 0, "every wavefront loads the same number of X blocks");
     static_assert(!G::PAIR_V && !G::PAIR_M, "whole 16-byte rows per stage only");
+    static_assert(BO <= 256, "one direct load brings the scales of 256 columns");
     static_assert(LDS <= 160 * 1024, "exceeds the 160 KB of LDS of a CU");
 };
 
-__device__ __forceinline__ void xs_barrier() { asm volatile("s_barrier" ::: "memory"); }
-__device__ __forceinline__ void xs_barrier_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-// Grid: 8 * ceil(row_tiles / 8) * splits workgroups.  Workgroup id w: XCD x = w % 8 owns the token
-// tiles x * rows_per_xcd ..; inside it i = w / 8 -> token tile i / splits, share i % splits of
-// the column tiles (a contiguous range), so the workgroups that share a token tile share an L2.
-template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KS, int EP, int ES>
+// Grid: 8 * ceil(n_wgs / 8) workgroups; workgroup w -> unit (w % 8) * per_xcd + w / 8, unit u ->
+// token tile u / groups, column tiles (u % groups) * CT ..: the workgroups that share a token tile
+// sit on one XCD and share its L2.
+template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int KS>
 __global__ void __launch_bounds__(64 * WAVES_T * WAVES_O)
-gemm_xstat_kernel(const GemmArgs a, const int tiles_o, const int row_tiles, const int rows_per_xcd, const int splits)
+gemm_xres_kernel(const GemmArgs a, const int groups, const int n_wgs)
 {
     using U = Unit<N, M, BITS>;
-    using S = XstatGeom<N, M, BITS, BT, BO, WAVES_T, WAVES_O, STAGES, KS, EP, ES>;
+    using S = XresGeom<N, M, BITS, BT, BO, WAVES_T, WAVES_O, KS>;
     using G = typename S::G;
-    constexpr int NW = S::NW, LW = S::LW, SW = S::SW, PER_LW = S::PER_LW, STAGE = S::STAGE;
+    constexpr int NW = S::NW, PX = S::PX, PW = S::PW, STAGE = S::STAGE, STAGES = S::STAGES, CT = S::CT;
     constexpr int WT = BT / WAVES_T, WO = BO / WAVES_O;
     constexpr int FT = WT / 16, FO = WO / 16;
     static_assert(WT % 16 == 0 && WO % 16 == 0, "wave tile must be whole 16x16 fragments");
-    static_assert(FT % EP == 0, "every pass takes the same number of fragment rows of each wavefront");
-    static_assert(BT % 8 == 0 && BO % 4 == 0, "X blocks hold 8 rows; scales travel in 16-byte pieces");
-    constexpr int AHEAD = STAGES - 2;
-    static_assert(AHEAD >= 1, "at least three stages");
-    constexpr int X_PER_LW = (KS * S::XB_PER_SLICE + LW - 1) / LW;     // most X loads a loading wavefront issues
-    static_assert(X_PER_LW + (AHEAD + 1) * PER_LW + 2 * S::SB_BLOCKS < 64, "loads in flight must fit the counter");
+    static_assert(FO % 2 == 0, "fragments pair up along the columns in the epilogue");
+    static_assert((KS - 3) * PX + 3 * (PX + PW) + 1 < 64, "loads in flight must fit the counter");
 
     extern __shared__ __align__(1024) uint8_t smem[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const bool loader = wave_u < LW;
     const int wt = wave % WAVES_T, wo = wave / WAVES_T;
     const int li = lane & 15, lg = lane >> 4;
 
-    // ---- this workgroup's token tile and column tiles ---------------------------------------------
-    const int xcd = (int)(blockIdx.x & 7), wi = (int)(blockIdx.x >> 3);
-    const int rt = xcd * rows_per_xcd + wi / splits;
-    const int sp = wi % splits;
-    if (wi / splits >= rows_per_xcd || rt >= row_tiles) return;       // whole workgroup leaves before any barrier
-    const int c_first = (int)(((long long)tiles_o * sp) / splits);
-    const int c_last = (int)(((long long)tiles_o * (sp + 1)) / splits);
-    const int cnt = c_last - c_first;                                 // column tiles of this workgroup
-    if (cnt <= 0) return;
-    const int t0 = rt * BT;
-    const int ns = a.K >> 7;                                          // 128-column slices (<= KS: the host checks)
-    const int total = cnt * ns;                                       // weight stages this workgroup streams
+    const int per_xcd = (n_wgs + 7) >> 3;
+    const int unit = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (unit >= n_wgs) return;                 // whole workgroup leaves before any barrier
+    const int t0 = (unit / groups) * BT;
+    const int o_first = (unit % groups) * CT * BO;
+    const int ns = a.K >> 7;                   // 128-column slices, 3 <= ns <= KS (the host checks)
+    const int total = CT * ns;                 // weight stages this workgroup streams
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
 
-    // ---- producer: the loading wavefronts ------------------------------------------------------
-    // Load p of loading wavefront w fills block b = p * LW + w of the stage; blocks past the last
-    // real one are padding and refetch it.
-    const uint8_t* src[PER_LW];
-    uint32_t step[PER_LW];                                    // bytes per stage along the source row
-    const uint8_t* sbsrc[S::SB_BLOCKS];
-    int p_ct = c_first, p_k = 0, p_tl = 0;
-    auto setup_src = [&](int ct) __attribute__((always_inline)) {
-        const int o0 = ct * BO;
+    // Scales and biases of both column tiles first: being the oldest loads of their wavefronts,
+    // every later wait on the in-order counter covers them.  Lane l brings columns 4l .. 4l+3.
+    static_assert(NW >= 2 * CT, "one wavefront per scale and bias block");
+    if (wave_u < CT) {
+        const uint32_t off = (uint32_t)min(o_first + wave_u * BO + 4 * lane, a.O - 4) * 4u;
+        dma16s(lds0 + S::SB_OFF + wave_u * 2048, off, reinterpret_cast<const uint8_t*>(a.scales));
+    } else if (wave_u < 2 * CT && a.bias != nullptr) {
+        const uint32_t off = (uint32_t)min(o_first + (wave_u - CT) * BO + 4 * lane, a.O - 4) * 4u;
+        dma16s(lds0 + S::SB_OFF + (wave_u - CT) * 2048 + 1024, off, reinterpret_cast<const uint8_t*>(a.bias));
+    }
+
+    // ---- sources ------------------------------------------------------------------------------
+    // X: load p of wave w fills block p * NW + w of a slice (8 rows x 128 bytes, chunks swizzled).
+    uint32_t xoff[PX];
 #pragma unroll
-        for (int p = 0; p < PER_LW; ++p) {
-            const int b = min(p * LW + wave_u, S::W_BLOCKS - 1);
-            if (b < G::V_BLOCKS) {
-                const int q = b * 64 + lane;                   // 16-byte slot index in the codes array
-                const int row = min(q / (G::RV / 16), BO - 1);
-                const int slot = q % (G::RV / 16);
-                src[p] = a.vals + (size_t)(o0 + row) * a.vstride + slot * 16;
-                step[p] = G::RV;
-            } else {
-                const int q = (b - G::V_BLOCKS) * 64 + lane;
-                const int row = min(q / (G::RM / 16), BO - 1);
-                src[p] = a.meta + (size_t)(o0 + row) * a.mstride + (q % (G::RM / 16)) * 16;
-                step[p] = G::RM;
+    for (int p = 0; p < PX; ++p) {
+        const int b = p * NW + wave_u;
+        const int row = b * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        xoff[p] = (uint32_t)min(t0 + row, a.tokens - 1) * (uint32_t)a.ldx + chunk * 16;
+    }
+    // W: load p of wave w fills block p * NW + w of a stage; blocks past the last real one are
+    // padding and refetch it.  Codes or index rows: decided by the wavefront, so base and step are scalars.
+    uint32_t woff[PW];
+    const uint8_t* wbase[PW];
+    uint32_t wstep[PW], wjump[PW];             // bytes per slice; bytes from one column tile's rows to the next one's
+#pragma unroll
+    for (int p = 0; p < PW; ++p) {
+        const int b = min(p * NW + wave_u, S::W_BLOCKS - 1);
+        if (b < G::V_BLOCKS) {
+            const int q = b * 64 + lane;                       // 16-byte slot index in the codes array
+            const int row = min(q / (G::RV / 16), BO - 1);
+            const int slot = q % (G::RV / 16);
+            wbase[p] = a.vals;
+            wstep[p] = G::RVS;
+            wjump[p] = (uint32_t)BO * (uint32_t)a.vstride;
+            woff[p] = (uint32_t)(o_first + row) * (uint32_t)a.vstride + (slot ^ G::v_xor(row)) * 16;
+        } else {
+            const int q = (b - G::V_BLOCKS) * 64 + lane;
+            const int row = min(q / (G::RM / 16), BO - 1);
+            wbase[p] = a.meta;
+            wstep[p] = G::RMS;
+            wjump[p] = (uint32_t)BO * (uint32_t)a.mstride;
+            woff[p] = (uint32_t)(o_first + row) * (uint32_t)a.mstride + (q % (G::RM / 16)) * 16;
+        }
+    }
+    const uint32_t lds_mine = lds0 + (uint32_t)wave_u * 1024u;
+    int x_issue = 0;                           // next X slice to issue
+    auto issue_x = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < PX; ++p) {
+            dma16s(lds_mine + (uint32_t)x_issue * S::X_SLICE + p * NW * 1024, xoff[p], reinterpret_cast<const uint8_t*>(a.X));
+            xoff[p] += 128;
+        }
+        ++x_issue;
+    };
+    int w_k = 0;                               // slice of the next W stage to issue
+    // Piece PART of PARTS of the next weight stage, into ring slot SLOT.
+    auto issue_w = [&](auto slot, auto part, auto parts) __attribute__((always_inline)) {
+        constexpr int SLOT = decltype(slot)::value, PART = decltype(part)::value, PARTS = decltype(parts)::value;
+        constexpr int P0 = PART * PW / PARTS, P1 = (PART + 1) * PW / PARTS;
+#pragma unroll
+        for (int p = P0; p < P1; ++p) {
+            dma16s(lds_mine + S::RING_OFF + SLOT * STAGE + p * NW * 1024, woff[p], wbase[p]);
+            woff[p] += wstep[p];
+        }
+        if constexpr (PART == PARTS - 1) {
+            if (++w_k == ns) {                 // on to the next column tile's rows
+                w_k = 0;
+#pragma unroll
+                for (int p = 0; p < PW; ++p) woff[p] += wjump[p] - (uint32_t)ns * wstep[p];
             }
         }
-#pragma unroll
-        for (int sb = 0; sb < S::SB_BLOCKS; ++sb) {
-            const int f = (sb * 64 + lane) * 4;                // first of this lane's four floats
-            const float* base = a.scales + o0;                 // lanes past both arrays refetch the first piece
-            if (f < BO) base = a.scales + o0 + f;
-            else if (f < 2 * BO && a.bias != nullptr) base = a.bias + o0 + (f - BO);
-            sbsrc[sb] = reinterpret_cast<const uint8_t*>(base);
-        }
     };
-    // Issues the next weight stage of the stream into ring slot `slot` and moves the producer cursor.
-    auto issue_next = [&](int slot) __attribute__((always_inline)) {
-        if (p_k == 0 && wave_u == 0) {
-#pragma unroll
-            for (int sb = 0; sb < S::SB_BLOCKS; ++sb)
-                dma16(lds0 + S::SB_OFF + (p_tl % STAGES) * S::SB_BYTES + sb * 1024, sbsrc[sb]);
-        }
-#pragma unroll
-        for (int p = 0; p < PER_LW; ++p)
-            dma16(lds0 + S::RING_OFF + slot * STAGE + (p * LW + wave_u) * 1024, src[p] + (uint32_t)p_k * step[p]);
-        if (++p_k == ns) {
-            p_k = 0;
-            ++p_tl;
-            ++p_ct;
-            if (p_ct < c_last) setup_src(p_ct);
-        }
-    };
+    using One = std::integral_constant<int, 1>;
+    using Zero = std::integral_constant<int, 0>;
 
-    // ---- consumer: fragments and accumulators ---------------------------------------------------
     v4i acc[FO][FT];
-#pragma unroll
-    for (int fo = 0; fo < FO; ++fo)
-#pragma unroll
-        for (int ft = 0; ft < FT; ++ft) acc[fo][ft] = v4i{0, 0, 0, 0};
-
-    // X rows are 128 B with the 16-byte chunk c of row r in slot c ^ ((r >> 1) & 7); B fragment
-    // rows start at multiples of 16, so the swizzle term only depends on the lane.
-    const int xsw = (li >> 1) & 7;
-    const int frag_x_lo = (wt * WT + li) * 128 + ((lg ^ xsw) * 16);
-    const int frag_x_hi = (wt * WT + li) * 128 + (((lg + 4) ^ xsw) * 16);
-    const int voff = lg * U::VBYTES;                           // byte offset of this lane's unit in the row
-    const int frag_v = S::V_OFF + (wo * WO + li) * G::RV + voff;
-    const int frag_m = S::M_OFF + (wo * WO + li) * G::RM + lg * U::MBYTES;
-
-    struct Frags {
-        v8i b[FT];
-        typename U::Raw w[FO];
-    };
-    // Fragments of K slice k: activations from the resident tile, weights from ring slot `slot`.
-    auto fetch = [&](int k, int slot, Frags& f) __attribute__((always_inline)) {
-        const uint8_t* xb = smem + k * S::X_SLICE;
-        const uint8_t* wb = smem + S::RING_OFF + slot * STAGE;
-#pragma unroll
-        for (int ft = 0; ft < FT; ++ft) {
-            const v4i lo = *reinterpret_cast<const v4i*>(xb + frag_x_lo + ft * 16 * 128);
-            const v4i hi = *reinterpret_cast<const v4i*>(xb + frag_x_hi + ft * 16 * 128);
-            f.b[ft] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        }
-#pragma unroll
-        for (int fo = 0; fo < FO; ++fo)
-            f.w[fo] = U::load(wb + frag_v + fo * 16 * G::RV, wb + frag_m + fo * 16 * G::RM, 0);
-    };
-    auto mma = [&](const Frags& f) __attribute__((always_inline)) {
-#pragma unroll
-        for (int fo = 0; fo < FO; ++fo) {
-            v4i codes; int pos;
-            U::decode(f.w[fo], codes, pos);
-#pragma unroll
-            for (int ft = 0; ft < FT; ++ft)
-                acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(codes, f.b[ft], acc[fo][ft], pos, 0, 0);
-        }
-    };
-    auto interleave = [&]() __attribute__((always_inline)) {
-        // Issue order of one slice: the LDS reads of the next slice that outnumber the MFMAs go
-        // first, then one MFMA and one read alternate.  A wavefront issues in order; reads left
-        // behind the last MFMA would still be in flight at the next barrier and the step would
-        // cost the MFMA time plus the LDS latency instead of the larger of the two.
-        constexpr int READS = 2 * FT + 2 * FO;                   // ds_read instructions of fetch() (upper bound)
-        constexpr int LEAD = READS > FO * FT ? READS - FO * FT : 0;
-        if constexpr (LEAD > 0) __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0);
-#pragma unroll
-        for (int i = 0; i < FO * FT; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
-        }
-    };
-
-    // ---- epilogue of one column tile: Eq. 4 with offset 0 on the product of two quantised operands
-    int c_ct = c_first, c_k = 0, c_tl = 0;
-    auto epilogue = [&]() __attribute__((always_inline)) {
-        const int o0 = c_ct * BO;
-        const uint8_t* sbuf = smem + S::SB_OFF + (c_tl % STAGES) * S::SB_BYTES;
-        const bool hb = a.bias != nullptr;
-        uint8_t* stg = smem + S::ST_OFF;
-        uint8_t* out = reinterpret_cast<uint8_t*>(a.out) + (size_t)o0 * ES;
-        int_for<EP>([&](auto pass) __attribute__((always_inline)) {
-            constexpr int P = decltype(pass)::value;
-            constexpr int FPP = FT / EP;                        // fragment rows of a wavefront per pass
-            xs_barrier();                                       // staging area is free (its last readers are done)
-#pragma unroll
-            for (int fo = 0; fo < FO; ++fo) {
-                const int col = wo * WO + fo * 16 + 4 * lg;
-                const float4 s4 = *reinterpret_cast<const float4*>(sbuf + col * 4);
-                const float4 b4 = *reinterpret_cast<const float4*>(sbuf + (BO + col) * 4);
-                const float sc[4] = {a.act_scale * s4.x, a.act_scale * s4.y, a.act_scale * s4.z, a.act_scale * s4.w};
-                const float bs[4] = {hb ? b4.x : 0.f, hb ? b4.y : 0.f, hb ? b4.z : 0.f, hb ? b4.w : 0.f};
-#pragma unroll
-                for (int f = 0; f < FPP; ++f) {
-                    const int srow = wt * (WT / EP) + f * 16 + li;
-                    const v4i c = acc[fo][P * FPP + f];
-                    float y[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) y[r] = (float)c[r] * sc[r] + bs[r];
-                    uint8_t* dst = stg + srow * S::SROW_B + col * ES;
-                    if constexpr (ES == 4) {
-                        *reinterpret_cast<float4*>(dst) = make_float4(y[0], y[1], y[2], y[3]);
-                    } else {
-                        uint2 pk;
-                        pk.x = pack_bf16x2(y[0], y[1]);
-                        pk.y = pack_bf16x2(y[2], y[3]);
-                        *reinterpret_cast<uint2*>(dst) = pk;
-                    }
-                }
-            }
-            xs_barrier_lds();                                   // staged rows complete
-            if (!loader) {
-                constexpr int CPR = BO * ES / 16;               // 16-byte chunks per staged row
-                constexpr int CHUNKS = S::SROWS * CPR;
-                constexpr int ITER = (CHUNKS + 64 * SW - 1) / (64 * SW);
-                constexpr int BATCH = ITER < 6 ? ITER : 6;      // chunks a lane holds in registers at a time
-                const int c0 = tid - 64 * LW;
-#pragma unroll
-                for (int i0 = 0; i0 < ITER; i0 += BATCH) {
-                    v4i v[BATCH];
-#pragma unroll
-                    for (int i = 0; i < BATCH; ++i) {
-                        const int c = min(c0 + (i0 + i) * 64 * SW, CHUNKS - 1);
-                        const int srow = c / CPR, ch = c - srow * CPR;
-                        v[i] = *reinterpret_cast<const v4i*>(stg + srow * S::SROW_B + ch * 16);
-                    }
-#pragma unroll
-                    for (int i = 0; i < BATCH; ++i) {
-                        const int c = c0 + (i0 + i) * 64 * SW;
-                        const int srow = c / CPR, ch = c - srow * CPR;
-                        // staged row -> row of the tile: wavefront row band, this pass's slice of it
-                        const int band = srow / (WT / EP), in = srow - band * (WT / EP);
-                        const int t = t0 + band * WT + P * (WT / EP) + in;
-                        if (i0 + i < ITER && c < CHUNKS && t < a.tokens)
-                            *reinterpret_cast<v4i*>(out + (size_t)t * a.ldo * ES + ch * 16) = v[i];
-                    }
-                }
-            }
-        });
+    auto clear_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int fo = 0; fo < FO; ++fo)
 #pragma unroll
             for (int ft = 0; ft < FT; ++ft) acc[fo][ft] = v4i{0, 0, 0, 0};
     };
+    clear_acc();
 
-    // ---- pipeline --------------------------------------------------------------------------------
-    // The token tile first (every slice, once), then weight stage q in ring slot q % STAGES.  While
-    // stage q is multiplied, stages q+1 .. q+AHEAD are landed or in flight, and the slot of stage
-    // q-1 is refilled.
-    if (loader) {
-        const int xblocks = ns * S::XB_PER_SLICE;
-        for (int b = wave_u; b < xblocks; b += LW) {
-            const int s = b / S::XB_PER_SLICE;
-            const int row = (b - s * S::XB_PER_SLICE) * 8 + (lane >> 3);
-            const int chunk = (lane & 7) ^ ((row >> 1) & 7);
-            const int trow = min(t0 + row, a.tokens - 1);
-            dma16(lds0 + b * 1024, reinterpret_cast<const uint8_t*>(a.X) + (size_t)trow * a.ldx + s * 128 + chunk * 16);
-        }
-        setup_src(p_ct);
-#pragma unroll
-        for (int j = 0; j <= AHEAD; ++j)
-            if (j < total) issue_next(j % STAGES);
-        // stage 0 landed (and, being older, the token tile); the AHEAD stages behind it may still fly
-        if (total > AHEAD) wait_vm<AHEAD * PER_LW>();
-        else wait_vm<0>();
-    }
-    xs_barrier();
+    // Fragment addresses (as in the ordinary kernel: fragment rows start at multiples of 16, so the
+    // swizzle terms depend on the lane only).
+    const int xsw = (li >> 1) & 7;
+    const int frag_x_lo = (wt * WT + li) * 128 + ((lg ^ xsw) * 16);
+    const int frag_x_hi = (wt * WT + li) * 128 + (((lg + 4) ^ xsw) * 16);
+    const int voff_u = lg * U::VBYTES;
+    const int frag_v = S::RING_OFF + S::V_OFF + (wo * WO + li) * G::RV + (((voff_u >> 4) ^ G::v_xor(li)) * 16) + (voff_u & 15);
+    const int frag_m = S::RING_OFF + S::M_OFF + (wo * WO + li) * G::RM + lg * U::MBYTES;
 
+    struct Frags {
+        v8i b[FT];
+        typename U::Raw w[FO];
+    };
     Frags fr[2];
-    fetch(0, 0, fr[0]);
-    int slot_c = 0;                             // ring slot of the stage being multiplied
-    int slot_i = (AHEAD + 1) % STAGES;          // ring slot the next issue refills
-    int k_next = (ns > 1) ? 1 : 0;              // K slice of the stage after the one being multiplied
-    // Everything needed before the fragments of stage q+1 can be read.
-    auto advance = [&](int q) __attribute__((always_inline)) {
-        if (q + 1 < total) {
-            if (loader) {
-                // this wavefront's loads of stages q+1 .. min(q+AHEAD, total-1) are in flight, oldest first
-                if (q + AHEAD < total) wait_vm<(AHEAD - 1) * PER_LW>();
-                else wait_vm<0>();
+    auto read_b = [&](int k, auto ftc, v8i& dst) __attribute__((always_inline)) {
+        constexpr int ft = decltype(ftc)::value;
+        const uint8_t* base = smem + k * S::X_SLICE;
+        const v4i lo = *reinterpret_cast<const v4i*>(base + frag_x_lo + ft * 16 * 128);
+        const v4i hi = *reinterpret_cast<const v4i*>(base + frag_x_hi + ft * 16 * 128);
+        dst = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    };
+    auto read_w = [&](auto slot, auto foc, typename U::Raw& dst) __attribute__((always_inline)) {
+        constexpr int fo = decltype(foc)::value;
+        const uint8_t* base = smem + decltype(slot)::value * STAGE;
+        dst = U::load(base + frag_v + fo * 16 * G::RV, base + frag_m + fo * 16 * G::RM, 0);
+    };
+
+    // ---- epilogue of one column tile (Eq. 4 with offset 0; layout as in the ordinary kernel) --
+    // NST store instructions per wavefront, every one of them issued by every wavefront.
+    uint8_t* out = reinterpret_cast<uint8_t*>(a.out);
+    const int row0 = t0 + wt * WT + li;
+    typedef unsigned v2u __attribute__((ext_vector_type(2)));
+    auto epilogue = [&](int c) __attribute__((always_inline)) {
+        const int col0 = o_first + c * BO + wo * WO;
+        const uint8_t* sb = smem + S::SB_OFF + c * 2048;
+        int_for<FO / 2>([&](auto h) __attribute__((always_inline)) {
+            constexpr int fo = 2 * decltype(h)::value;
+            float4 sw[2], bw[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int cc = wo * WO + (fo + i) * 16 + 4 * lg;
+                sw[i] = *reinterpret_cast<const float4*>(sb + cc * 4);
+                bw[i] = a.bias ? *reinterpret_cast<const float4*>(sb + 1024 + cc * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
             }
-            xs_barrier();
-            if (loader && q + 1 + AHEAD < total) issue_next(slot_i);
-        }
-        slot_c = (slot_c + 1 == STAGES) ? 0 : slot_c + 1;
-        slot_i = (slot_i + 1 == STAGES) ? 0 : slot_i + 1;
+            int_for<FT>([&](auto ftc) __attribute__((always_inline)) {
+                constexpr int ft = decltype(ftc)::value;
+                float y[2][4];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const v4i cv = acc[fo + i][ft];
+                    y[i][0] = (float)cv[0] * (a.act_scale * sw[i].x) + bw[i].x;
+                    y[i][1] = (float)cv[1] * (a.act_scale * sw[i].y) + bw[i].y;
+                    y[i][2] = (float)cv[2] * (a.act_scale * sw[i].z) + bw[i].z;
+                    y[i][3] = (float)cv[3] * (a.act_scale * sw[i].w) + bw[i].w;
+                }
+                const size_t row = (size_t)(row0 + ft * 16);
+                if (a.out_dtype == 1) {
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        store16_through(out + (row * a.ldo + col0 + (fo + i) * 16 + 4 * lg) * 4,
+                                        v4i{(int)__float_as_uint(y[i][0]), (int)__float_as_uint(y[i][1]),
+                                            (int)__float_as_uint(y[i][2]), (int)__float_as_uint(y[i][3])});
+                } else {
+                    const v2u p = __builtin_amdgcn_permlane16_swap(pack_bf16x2(y[0][0], y[0][1]), pack_bf16x2(y[1][0], y[1][1]), false, false);
+                    const v2u q = __builtin_amdgcn_permlane16_swap(pack_bf16x2(y[0][2], y[0][3]), pack_bf16x2(y[1][2], y[1][3]), false, false);
+                    store16_through(out + (row * a.ldo + col0 + fo * 16 + (lg & 1) * 16 + (lg >> 1) * 8) * 2,
+                                    v4i{(int)p[0], (int)q[0], (int)p[1], (int)q[1]});
+                }
+            });
+        });
     };
-    auto tile_end = [&]() __attribute__((always_inline)) {
-        k_next = (k_next + 1 == ns) ? 0 : k_next + 1;
-        if (++c_k == ns) {
-            epilogue();
-            c_k = 0;
-            ++c_tl;
-            ++c_ct;
-        }
+    constexpr int NST_BF16 = FT * FO / 2, NST_F32 = FT * FO;
+    static_assert(PW + NST_F32 < 64, "stores in flight must fit the counter");
+
+    // ---- prologue -----------------------------------------------------------------------------
+    // X slice k travels with weight stage k for k < 3; the remaining slices follow in one go, so
+    // that every later issue is a weight stage and nothing else.
+    int_for<STAGES>([&](auto q) __attribute__((always_inline)) {
+        issue_x();
+        issue_w(q, Zero{}, One{});
+    });
+    const int late = ns - STAGES;              // X slices issued behind the first three stages
+    for (int k = STAGES; k < ns; ++k) issue_x();
+
+    // Waits until at most `base + late * PX` of this wavefront's memory operations are outstanding.
+    auto wait_late = [&](auto base) __attribute__((always_inline)) {
+        constexpr int B = decltype(base)::value;
+        static_assert(KS - STAGES <= 3, "one case per number of late slices");
+        if (late <= 0) wait_vm<B>();
+        else if (late == 1) wait_vm<B + PX>();
+        else if (late == 2) wait_vm<B + 2 * PX>();
+        else wait_vm<B + 3 * PX>();
     };
-    // The fragment fetch is unconditional (after the last stage it re-reads an idle slot and the
-    // values are dropped) so that the two register sets never merge across a branch.
-    int q = 0;
-    for (; q + 2 <= total; q += 2) {
-        advance(q);
-        __builtin_amdgcn_s_waitcnt(0xC07F);     // lgkmcnt(0): see the note in the LDS-direct kernel
-        mma(fr[0]);
-        fetch(k_next, slot_c, fr[1]);
-        interleave();
-        tile_end();
-        advance(q + 1);
-        mma(fr[1]);
-        fetch(k_next, slot_c, fr[0]);
-        interleave();
-        tile_end();
-    }
-    if (q < total) {
-        advance(q);
-        mma(fr[0]);
-        tile_end();
+    wait_late(std::integral_constant<int, 2 * (PX + PW)>{});   // slice 0 and stage 0 landed
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    int_for<FT>([&](auto ftc) __attribute__((always_inline)) { read_b(0, ftc, fr[0].b[decltype(ftc)::value]); });
+    int_for<FO>([&](auto foc) __attribute__((always_inline)) { read_w(Zero{}, foc, fr[0].w[decltype(foc)::value]); });
+
+    // ---- main loop ----------------------------------------------------------------------------
+    // Stage q = c * ns + k (column tile c, slice k) sits in ring slot q % 3 and is multiplied in
+    // step q.  By the barrier of step q every wavefront has read the last of stage q out of the
+    // LDS (fragments are read a step ahead), so its slot is refilled with stage q + 3 right away:
+    // two steps of latency from three slots.  The body covers 6 steps so that slots and fragment
+    // sets are compile-time values.
+    int c = 0, k = 0;
+    const bool f32 = a.out_dtype == 1;
+    for (int q0 = 0; q0 < total; q0 += 2 * STAGES) {
+        int_for<2 * STAGES>([&](auto ss) __attribute__((always_inline)) {
+            constexpr int SS = decltype(ss)::value;
+            using Slot = std::integral_constant<int, SS % STAGES>;
+            using Next = std::integral_constant<int, (SS + 1) % STAGES>;
+            const int q = q0 + SS;
+            if (q < total) {
+                if (q + 1 < total) {
+                    // Outstanding, oldest first, when stage q+1 must have landed:
+                    //   q = 0:  slice 1 + stage 1 | slice 2 + stage 2, late slices
+                    //   q = 1:  slice 2 + stage 2 | late slices, stage 3
+                    //   first two steps of a later column tile: stage q+1 | stage q+2 and the
+                    //   previous tile's stores (in either order)
+                    //   otherwise: stage q+1 | stage q+2
+                    if (q + 2 >= total) wait_vm<0>();
+                    else if (q == 0) wait_late(std::integral_constant<int, PX + PW>{});
+                    else if (q == 1) wait_late(std::integral_constant<int, PW>{});
+                    else if (c > 0 && k < 2) {
+                        if (f32) wait_vm<PW + NST_F32>();
+                        else wait_vm<PW + NST_BF16>();
+                    } else wait_vm<PW>();
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // own reads of stage q done: its slot may be refilled
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                }
+                const bool more = q + STAGES < total;
+                const int kn = (k + 1 == ns) ? 0 : k + 1;    // slice of stage q+1
+                int_for<FO>([&](auto g) __attribute__((always_inline)) {
+                    constexpr int fo = decltype(g)::value;
+                    // fragments of stage q+1 (after the last stage: a stale slot, dropped)
+                    read_w(Next{}, g, fr[1 - SS % 2].w[fo]);
+                    int_for<(fo + 1) * FT / FO - fo * FT / FO>([&](auto i) __attribute__((always_inline)) {
+                        constexpr int ft = fo * FT / FO + decltype(i)::value;
+                        read_b(kn, std::integral_constant<int, ft>{}, fr[1 - SS % 2].b[ft]);
+                    });
+                    v4i codes; int pos;
+                    U::decode(fr[SS % 2].w[fo], codes, pos);
+#pragma unroll
+                    for (int ft = 0; ft < FT; ++ft)
+                        acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(codes, fr[SS % 2].b[ft], acc[fo][ft], pos, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (more) issue_w(Slot{}, g, std::integral_constant<int, FO>{});
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                if (k + 1 == ns) {
+                    epilogue(c);
+                    clear_acc();
+                    ++c;
+                    k = 0;
+                } else {
+                    ++k;
+                }
+            }
+        });
     }
 }
 
-template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KS, int EP, int ES>
-bool launch_xstat_es(const GemmArgs& a, hipStream_t st)
+template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int KS>
+bool launch_xres_tile(const GemmArgs& a, hipStream_t st)
 {
-    using S = XstatGeom<N, M, BITS, BT, BO, WAVES_T, WAVES_O, STAGES, KS, EP, ES>;
-    if (a.O % BO != 0 || a.K > KS * 128) return false;
-    const int row_tiles = (a.tokens + BT - 1) / BT, tiles_o = a.O / BO;
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return false;
-        cus = prop.multiProcessorCount;
-    }
-    // Workgroups per token tile: as many as fill the CUs once, at most one per column tile.
-    int splits = cus / row_tiles;
-    if (splits < 1) splits = 1;
-    if (splits > tiles_o) splits = tiles_o;
-    const int rows_per_xcd = (row_tiles + 7) / 8;
-    auto kern = gemm_xstat_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O, STAGES, KS, EP, ES>;
-    // Once per instantiation: raise the dynamic LDS limit (the attribute is sticky), and refuse a
-    // build of the kernel that touches scratch memory (scratch accesses are vector-memory
-    // instructions the hand-counted waits of the loading wavefronts know nothing about).
+    using S = XresGeom<N, M, BITS, BT, BO, WAVES_T, WAVES_O, KS>;
+    const int ns = a.K / 128;
+    if (a.K % 128 != 0 || ns < S::STAGES || ns > KS) return false;
+    if (a.tokens % BT != 0 || a.O % (S::CT * BO) != 0) return false;   // whole tiles only: every wavefront stores every fragment
+    if ((unsigned long long)a.tokens * a.ldx >= (1ull << 32) || (unsigned long long)a.O * a.vstride >= (1ull << 32)) return false;
+    const int groups = a.O / (S::CT * BO);
+    const int n_wgs = (a.tokens / BT) * groups;
+    auto kern = gemm_xres_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O, KS>;
+    // Once per instantiation: raise the dynamic-LDS limit, and refuse a kernel that spills (scratch
+    // accesses are memory instructions the hand-counted waits know nothing about).
     static int usable = -1;
     if (usable < 0) {
         hipFuncAttributes attr;
@@ -388,23 +355,20 @@ bool launch_xstat_es(const GemmArgs& a, hipStream_t st)
                                          (int)S::LDS) == hipSuccess;
     }
     if (!usable) return false;
-    hipLaunchKernelGGL(kern, dim3(8 * rows_per_xcd * splits), dim3(64 * S::NW), S::LDS, st, a, tiles_o, row_tiles,
-                       rows_per_xcd, splits);
+    hipLaunchKernelGGL(kern, dim3(8 * ((n_wgs + 7) / 8)), dim3(64 * S::NW), S::LDS, st, a, groups, n_wgs);
     return true;
 }
 
 template <int N, int M, int BITS>
-bool launch_xstat_pattern(const GemmArgs& a, hipStream_t st, int cfg)
+bool launch_xres_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 {
     using U = Unit<N, M, BITS>;
     if constexpr ((4 * U::VBYTES) % 16 != 0 || (4 * U::MBYTES) % 16 != 0) {
         return false;                                            // stage rows must be whole 16-byte pieces
     } else {
-        const bool f32 = a.out_dtype == 1;
         switch (cfg) {
-            case 301:                                            // 128 x 96, 8 wavefronts, 4 weight stages
-                return f32 ? launch_xstat_es<N, M, BITS, 128, 96, 4, 2, 4, 6, 2, 4>(a, st)
-                           : launch_xstat_es<N, M, BITS, 128, 96, 4, 2, 4, 6, 1, 2>(a, st);
+            case 301: return launch_xres_tile<N, M, BITS, 128, 192, 4, 2, 6>(a, st);   // wave tile 32 x 96
+            case 302: return launch_xres_tile<N, M, BITS, 128, 192, 2, 2, 6>(a, st);   // 4 wavefronts, wave tile 64 x 96
             default: return false;
         }
     }
@@ -418,10 +382,10 @@ bool launch_gemm_xstat(const GemmArgs& a, hipStream_t st, int cfg)
     const int esize = (a.out_dtype == 1) ? 4 : 2;
     if (a.acc != nullptr || a.out_dtype == 0 || a.out == nullptr) return false;
     if (((size_t)a.ldo * esize) % 16 != 0 || (uintptr_t)a.out % 16 != 0) return false;
-    if ((uintptr_t)a.scales % 16 != 0 || (uintptr_t)a.bias % 16 != 0 || (uintptr_t)a.meta % 16 != 0) return false;
-    if (a.K % 128 != 0 || a.K < 128) return false;
-#define NM_CASE(n, m, b) if (a.N == n && a.M == m && a.bits == b) return launch_xstat_pattern<n, m, b>(a, st, cfg)
-    NM_CASE(2, 4, 8);
+    if ((uintptr_t)a.scales % 16 != 0 || (uintptr_t)a.bias % 16 != 0) return false;
+    if ((uintptr_t)a.vals % 16 != 0 || (uintptr_t)a.meta % 16 != 0 || a.vstride % 16 != 0 || a.mstride % 16 != 0) return false;
+#define NM_CASE(n, m, b) if (a.N == n && a.M == m && a.bits == b) return launch_xres_pattern<n, m, b>(a, st, cfg)
+    NM_CASE(2, 4, 8); NM_CASE(2, 4, 4); NM_CASE(2, 8, 8); NM_CASE(2, 8, 4);
 #undef NM_CASE
     return false;
 }

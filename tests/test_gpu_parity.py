@@ -177,7 +177,7 @@ def _gemm_small(N, M, bits, tile):
         os.environ.pop("NM_GEMM_TILE", None)
 
 
-STREAM_TILES = ["201", "202", "203", "204", "205", "206", "301"]
+STREAM_TILES = ["201", "202", "203", "204", "205", "206"]
 
 
 @pytest.mark.parametrize("tile", STREAM_TILES)
@@ -198,6 +198,37 @@ def test_gemm_persistent_kernel_several_tiles_per_workgroup(tile):
                 f32p = run_gemm(Xq, sx, packed, O, 2, 4, 8, bias, want=("f32",), ldo=O + 32)["f32"]
                 assert np.all(f32p[:, O:] == -7.0)
                 check_outputs(acc_ref, sx, ref[2], bias, None, f32p[:, :O], None, what="padded T%d" % T)
+    finally:
+        os.environ.pop("NM_GEMM_TILE", None)
+
+
+@pytest.mark.parametrize("tile", ["301", "302"])
+@pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (2, 4, 4), (2, 8, 8), (2, 8, 4), (1, 4, 8)])
+def test_gemm_x_resident_kernel(N, M, bits, tile):
+    """Shapes the X-resident kernel takes (whole 128-token tiles, column tiles in pairs of 192,
+    K of 3 to 6 slices, dequantised output only): more workgroups than CUs, every admitted K,
+    with and without bias, padded output rows; and shapes it refuses (ragged tokens, odd number
+    of column tiles, a pattern with 8-byte stage rows), which must fall through to the other
+    kernels with the same results."""
+    say("gemm x-resident", N, M, bits, tile)
+    os.environ["NM_GEMM_TILE"] = tile
+    try:
+        cases = [(4480, 768, 1536, True), (256, 384, 768, False), (128, 512, 384, True), (384, 640, 768, True),
+                 (100, 768, 768, True), (256, 768, 576, True), (256, 896, 768, True)]
+        if (N, M, bits) != (2, 4, 8):
+            cases = cases[1:4]
+        for T, K, O, with_bias in cases:
+            W, Xq, sx, bias, ref, acc_ref = small_case(N, M, bits, T, K, O, 11, with_bias=with_bias)
+            packed = gpu_compress(W, N, M, bits)
+            f32 = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("f32",))["f32"]
+            b16 = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("bf16",))["bf16"]
+            check_outputs(acc_ref, sx, ref[2], bias, None, f32, b16, what="T%d K%d O%d" % (T, K, O))
+            if T == 256 and K == 384:     # padded output rows stay untouched
+                f32p = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("f32",), ldo=O + 32)["f32"]
+                assert np.all(f32p[:, O:] == -7.0)
+                check_outputs(acc_ref, sx, ref[2], bias, None, f32p[:, :O], None, what="padded T%d" % T)
+                b16p = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("bf16",), ldo=O + 32)["bf16"]
+                check_outputs(acc_ref, sx, ref[2], bias, None, None, b16p[:, :O], what="padded bf16 T%d" % T)
     finally:
         os.environ.pop("NM_GEMM_TILE", None)
 
