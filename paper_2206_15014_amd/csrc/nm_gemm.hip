@@ -319,7 +319,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t st)
         int tile_cfg = env ? atoi(env) : 0;
         // LDS-direct kernel first (tile_cfg 0 = its own choice, >= 100 = forced variant);
         // 1..99 force the register-staged kernel below.
-        if (tile_cfg >= 300 && launch_gemm_xstat(a, st, tile_cfg)) return launch_status();
+        if (tile_cfg >= 300 && launch_gemm_xres(a, st, tile_cfg)) return launch_status();
         if (tile_cfg >= 200 && tile_cfg < 300 && launch_gemm_stream(a, st, tile_cfg)) return launch_status();
         if ((tile_cfg == 0 || tile_cfg >= 100) && (uintptr_t)a.meta % 16 == 0 && launch_gemm_dma(a, st, tile_cfg))
             return launch_status();

@@ -377,7 +377,7 @@ bool launch_xres_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 }  // namespace
 
 // Returns true when it launched a kernel for this problem.
-bool launch_gemm_xstat(const GemmArgs& a, hipStream_t st, int cfg)
+bool launch_gemm_xres(const GemmArgs& a, hipStream_t st, int cfg)
 {
     const int esize = (a.out_dtype == 1) ? 4 : 2;
     if (a.acc != nullptr || a.out_dtype == 0 || a.out == nullptr) return false;

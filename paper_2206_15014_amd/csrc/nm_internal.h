@@ -45,7 +45,7 @@ int launch_decompress(const void* vals, const void* meta, int rows, int cols, in
 int launch_gemm(const GemmArgs& a, hipStream_t st);
 bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg);      // false: not handled, nothing launched
 bool launch_gemm_stream(const GemmArgs& a, hipStream_t st, int cfg);   // same
-bool launch_gemm_xstat(const GemmArgs& a, hipStream_t st, int cfg);    // same
+bool launch_gemm_xres(const GemmArgs& a, hipStream_t st, int cfg);    // same
 
 }  // namespace nm
 
