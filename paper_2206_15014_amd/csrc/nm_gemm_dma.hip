@@ -549,9 +549,11 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
     if (PAIR && !k256) return false;
     if (cfg == 0) {
         const long long n96 = (long long)((a.tokens + 127) / 128) * ((a.O + 95) / 96);
-        const long long n192 = (long long)((a.tokens + 255) / 256) * (a.O / 192);
-        if (a.O % 192 == 0 && n192 >= 176) cfg = 122;            // wide layers: 256 x 192, a quarter of the LDS fill per MAC
-        else if (!U::IDENTITY) cfg = 116;                        // decode work favours single-slice stages
+        const int c192 = (a.O + 191) / 192;
+        const long long n192 = (long long)((a.tokens + 255) / 256) * c192;
+        const bool fits192 = (c192 * 192 - a.O) * 8 <= a.O;      // at most an eighth of the columns computed in vain
+        if (fits192 && n192 >= 176) cfg = 122;                   // wide layers: 256 x 192, a quarter of the LDS fill per MAC
+        else if (!U::IDENTITY) cfg = (n96 <= 256 && k256 && a.K >= 1536) ? 113 : 116;   // decode work favours single-slice stages, a long K the fewer requests of 256-column ones
         else if (n96 <= 256 && k256) cfg = 113;                  // one round: deepest ring, 256-column stages
         else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
         else cfg = 116;                                          // 128 x 96, two workgroups per CU
