@@ -93,7 +93,7 @@ def run_gemm(Xq, sx, packed, O, N, M, bits, bias=None, want=("acc", "f32"), ldo=
         if out is not None:
             res["f32"] = out.cpu().numpy()
     if "bf16" in want:
-        out = torch.zeros((T, ldo), dtype=torch.bfloat16, device=DEV)
+        out = torch.full((T, ldo), -7.0, dtype=torch.bfloat16, device=DEV)
         nm.nm_gemm(X, float(sx), vals, meta, scales, O, N, M, bits, bias=b, out=out, out_dtype=NM_OUT_BF16, ldo=ldo)
         torch.cuda.synchronize()
         res["bf16"] = out.view(torch.int16).cpu().numpy().view(np.uint16)
@@ -244,6 +244,21 @@ def test_gemm_generic_path_odd_shapes(N, M, bits):
         assert_packed_equal(packed, ref, "compress")
         res = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("acc", "f32", "bf16"))
         check_outputs(acc_ref, sx, ref[2], bias, res["acc"], res["f32"], res["bf16"], what="T%d K%d O%d" % (T, K, O))
+
+
+def test_gemm_large_output_written_through_with_padded_rows():
+    """A bf16 output large enough (>= 14 MB) to take the written-through stores of the wide tile, with
+    padded output rows (the padding must stay untouched) and a ragged last column tile."""
+    say("gemm large output, padded rows")
+    T, K, O = 4096, 256, 2240          # 12 column tiles of 192, the last one 128 wide; 18.4 MB of bf16
+    W, Xq, sx, bias, ref, acc_ref = small_case(2, 4, 8, T, K, O, 5)
+    packed = gpu_compress(W, 2, 4, 8)
+    b16 = run_gemm(Xq, sx, packed, O, 2, 4, 8, bias, want=("bf16",), ldo=O + 64)["bf16"]
+    assert np.all(b16[:, O:] == 0xC0E0)            # -7.0 in bf16: the padding is as the caller left it
+    check_outputs(acc_ref, sx, ref[2], bias, None, None, b16[:, :O], what="bf16 through, padded")
+    f32 = run_gemm(Xq, sx, packed, O, 2, 4, 8, bias, want=("f32",), ldo=O + 64)["f32"]
+    assert np.all(f32[:, O:] == -7.0)
+    check_outputs(acc_ref, sx, ref[2], bias, None, f32[:, :O], None, what="f32 through, padded")
 
 
 def test_gemm_padded_output_rows_and_no_bias():
