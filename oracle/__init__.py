@@ -148,3 +148,17 @@ def dequant(acc, act_scale, scales, bias=None):
     _check(_load().nmo_dequant(_p(acc), T, O, O, ctypes.c_float(act_scale), _p(scales), _p(bias),
                                _p(f32), _p(b16), O))
     return f32, b16
+
+
+def requant(acc, act_scale, scales, out_scale, bias=None):
+    """(int8 output [tokens, O], max |y|): the layer output quantised for the next layer."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+    T, O = acc.shape
+    q = np.zeros((T, O), dtype=np.int8)
+    amax = ctypes.c_float(0.0)
+    _check(_load().nmo_requant(_p(acc), T, O, O, ctypes.c_float(act_scale), _p(scales), _p(bias),
+                               ctypes.c_float(out_scale), _p(q), O, ctypes.byref(amax)))
+    return q, float(amax.value)

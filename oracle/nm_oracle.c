@@ -23,6 +23,9 @@
  *   nmo_gemm_sparse    Sec. 5.3: only the kept products are computed, low-bit
  *                      weights widened to the activation type, int32 sums.
  *   nmo_dequant        Sec. 3.3, Eq. 4 with o = 0: x_d = s * x_q.
+ *   nmo_requant        Sec. 5.3 (activations are 8-bit integers) with the scalar
+ *                      quantiser of Sec. 3.3, Eq. 5 (o = 0) applied to a layer's
+ *                      output, so that the next layer reads int8 again.
  *
  * Readings where the paper is silent (all listed in the design notes):
  *   - "largest" means largest magnitude; equal magnitudes keep the lower column.
@@ -32,6 +35,10 @@
  *     qmax = 2^(b-1) - 1.
  *   - packed format: see nmo_packed_sizes.
  *   - the dequantized value is formed in double and rounded once.
+ *   - requantised output: the paper fixes neither where the activation scale
+ *     comes from nor the arithmetic; here the caller supplies the scale, and,
+ *     because a rounding decides an integer, the value is formed in fp32 in a
+ *     fixed order (see nmo_requant) that the GPU path follows bit for bit.
  *
  * Build: gcc -O2 -std=c11 -fno-fast-math -ffp-contract=off -fopenmp -shared -fPIC
  *
@@ -39,7 +46,8 @@
  * supports, N=1 == argmax, idempotence, max-survives-pruning invariant,
  * quantiser closed forms and half-way cases, an independent numpy decoder of
  * the byte format, numpy int64 matmul on the decompressed matrix, dequant
- * special cases.  The tie-break rule and the byte format are this build's own
+ * special cases; requantisation against exact rational arithmetic on inputs
+ * whose fp32 steps are exact, half-way and saturation cases.  The tie-break rule and the byte format are this build's own
  * choices (the paper fixes neither): pinned by the written format description
  * and the independent decoder, not by the paper.
  */
@@ -331,5 +339,36 @@ int nmo_dequant(const int32_t *acc, int tokens, int O, int ldacc, float act_scal
             if (out_f32) out_f32[(size_t)t * ldo + o] = yf;
             if (out_bf16) out_bf16[(size_t)t * ldo + o] = bf16_rne(yf);
         }
+    return NMO_OK;
+}
+
+/*
+ * Layer output as 8-bit activations for the next layer: Eq. 4 (o = 0) followed
+ * by Eq. 5 (o = 0, 8 bits) with the caller's scale.  Every step is one fp32
+ * operation, in this order:
+ *   p = act_scale * s_w[o]                      (multiplication)
+ *   y = fma((float)acc, p, bias[o] or 0)        (int32 -> float conversion rounds
+ *                                                to nearest even, then one fused
+ *                                                multiply-add)
+ *   q = clamp(rne(y / out_scale), -127, 127)    (division, round half to even)
+ * absmax, when given, receives max |y| over all outputs (the statistic a caller
+ * needs to choose the next out_scale).
+ */
+int nmo_requant(const int32_t *acc, int tokens, int O, int ldacc, float act_scale,
+                const float *scales, const float *bias, float out_scale,
+                int8_t *out, int ldo, float *absmax)
+{
+    if (!acc || !scales || !out) return NMO_ERR_NULL;
+    if (tokens <= 0 || O <= 0 || ldacc < O || ldo < O) return NMO_ERR_DIM;
+    if (!(out_scale > 0.0f) || !isfinite(out_scale)) return NMO_ERR_NONFINITE;
+    float amax = 0.0f;
+    for (int t = 0; t < tokens; ++t)
+        for (int o = 0; o < O; ++o) {
+            volatile float p = act_scale * scales[o];
+            volatile float y = fmaf((float)acc[(size_t)t * ldacc + o], p, bias ? bias[o] : 0.0f);
+            if (fabsf(y) > amax) amax = fabsf(y);
+            out[(size_t)t * ldo + o] = (int8_t)nmo_quantize_one(y, out_scale, 8);
+        }
+    if (absmax) *absmax = amax;
     return NMO_OK;
 }
