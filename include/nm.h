@@ -118,6 +118,30 @@ int nm_gemm(const int8_t *X_dev, int tokens, int K, int ldx, float act_scale,
             void *out_dev, int out_dtype,
             int ldo, void *hip_stream);
 
+/*
+ * The same layer with its output handed on as 8-bit activations (Sec. 5.3: activations are
+ * 8-bit integers), i.e. Eq. 4 followed by the scalar quantiser of Sec. 3.3, Eq. 5 (offset 0,
+ * 8 bits) with a scale the caller supplies, so that a chain of layers never writes or re-reads a
+ * floating-point tensor.  Arithmetic, one fp32 operation per step, in this order:
+ *
+ *   p       = act_scale * scales[o]
+ *   y[t][o] = fma(float(acc[t][o]), p, bias[o] or 0)      (int32 -> float rounds to nearest even)
+ *   q[t][o] = clamp(rne(y[t][o] / out_scale), -127, 127)  (true division, ties to even)
+ *
+ *   out_scale   > 0, finite (host value); out_dev[t][o] * out_scale approximates y.
+ *   out_dev     int8 [tokens][ldo], ldo >= O, 4-byte aligned.
+ *   absmax_dev  NULL, or one float that the caller has set (to 0, or to a running maximum
+ *               >= 0) before the call: max over all outputs of |y| is max-combined into it
+ *               atomically - the statistic from which the next out_scale is chosen.
+ * Other arguments as for nm_gemm.  Errors: as nm_gemm; NM_ERR_DIM for an out_scale that is not
+ * a positive finite number.
+ */
+int nm_gemm_q8(const int8_t *X_dev, int tokens, int K, int ldx, float act_scale,
+               const void *vals_dev, const void *meta_dev, const float *scales_dev,
+               int O, int N, int M, int bits,
+               const float *bias_dev, float out_scale,
+               int8_t *out_dev, int ldo, float *absmax_dev, void *hip_stream);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char *nm_status_string(int status);
 

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     nm_compress,
     nm_decompress_i8,
     nm_gemm,
+    nm_gemm_q8,
     nm_packed_sizes,
     nm_status_string,
 )

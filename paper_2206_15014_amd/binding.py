@@ -51,6 +51,9 @@ def _load():
     lib.nm_gemm.restype = c_int
     lib.nm_gemm.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp,
                             c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_int, c_int, c_vp]
+    lib.nm_gemm_q8.restype = c_int
+    lib.nm_gemm_q8.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp,
+                               c_int, c_int, c_int, c_int, c_vp, c_f, c_vp, c_int, c_vp, c_vp]
     lib.nm_status_string.restype = ctypes.c_char_p
     lib.nm_status_string.argtypes = [c_int]
     _lib = lib
@@ -137,3 +140,19 @@ def nm_gemm(X, act_scale: float, vals, meta, scales, O: int, N: int, M: int, bit
     if rc:
         raise NMError(rc, "nm_gemm")
     return acc, out
+
+
+def nm_gemm_q8(X, act_scale: float, vals, meta, scales, O: int, N: int, M: int, bits: int,
+               out_scale: float, out, bias=None, absmax=None, ldo: Optional[int] = None, stream=None):
+    """X: int8 CUDA tensor [tokens, K]; out: int8 [tokens, ldo] written in place with the layer's
+    output as 8-bit codes of scale out_scale; absmax: optional float32 tensor of one element,
+    max |y| is max-combined into it.  Returns out."""
+    tokens, K = X.shape
+    if ldo is None:
+        ldo = out.stride(0)
+    rc = _load().nm_gemm_q8(_ptr(X), tokens, K, X.stride(0), float(act_scale),
+                            _ptr(vals), _ptr(meta), _ptr(scales), O, N, M, bits,
+                            _ptr(bias), float(out_scale), _ptr(out), ldo, _ptr(absmax), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_gemm_q8")
+    return out

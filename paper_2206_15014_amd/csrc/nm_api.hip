@@ -86,6 +86,39 @@ int nm_gemm(const int8_t* X_dev, int tokens, int K, int ldx, float act_scale,
     a.vstride = (int)row_bytes(kc, bits);
     a.mstride = (int)row_bytes(kc, M == 4 ? 2 : 4);
     a.store_through = 0;
+    a.out_scale = 1.0f;
+    a.absmax = nullptr;
+    return nm::launch_gemm(a, static_cast<hipStream_t>(hip_stream));
+}
+
+int nm_gemm_q8(const int8_t* X_dev, int tokens, int K, int ldx, float act_scale,
+               const void* vals_dev, const void* meta_dev, const float* scales_dev,
+               int O, int N, int M, int bits,
+               const float* bias_dev, float out_scale,
+               int8_t* out_dev, int ldo, float* absmax_dev, void* hip_stream)
+{
+    const int rc = check_pattern(O, K, N, M, bits);
+    if (rc) return rc;
+    if (tokens <= 0) return NM_ERR_DIM;
+    if (!X_dev || !vals_dev || !meta_dev || !scales_dev || !out_dev) return NM_ERR_NULL;
+    if (ldx < K || ldo < O) return NM_ERR_DIM;
+    if (!(out_scale > 0.0f) || !(out_scale <= 3.402823466e38f)) return NM_ERR_DIM;
+    if ((uintptr_t)scales_dev % 4 || (uintptr_t)bias_dev % 4 || (uintptr_t)absmax_dev % 4 || (uintptr_t)out_dev % 4)
+        return NM_ERR_ALIGN;
+
+    nm::GemmArgs a;
+    a.X = X_dev; a.tokens = tokens; a.K = K; a.ldx = ldx; a.act_scale = act_scale;
+    a.vals = static_cast<const uint8_t*>(vals_dev);
+    a.meta = static_cast<const uint8_t*>(meta_dev);
+    a.scales = scales_dev;
+    a.O = O; a.N = N; a.M = M; a.bits = bits;
+    a.bias = bias_dev; a.acc = nullptr; a.out = out_dev; a.out_dtype = 3; a.ldo = ldo;
+    const size_t kc = (size_t)K / M * N;
+    a.vstride = (int)row_bytes(kc, bits);
+    a.mstride = (int)row_bytes(kc, M == 4 ? 2 : 4);
+    a.store_through = 0;
+    a.out_scale = out_scale;
+    a.absmax = absmax_dev;
     return nm::launch_gemm(a, static_cast<hipStream_t>(hip_stream));
 }
 

@@ -208,8 +208,10 @@ gemm_smfmac_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
 __global__ void __launch_bounds__(256)
 gemm_generic_kernel(const GemmArgs a)
 {
-    const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (id >= (long long)a.tokens * a.O) return;
+    const long long id_raw = (long long)blockIdx.x * 256 + threadIdx.x;
+    const long long total = (long long)a.tokens * a.O;
+    const bool live = id_raw < total;          // threads past the end recompute the last output and store nothing
+    const long long id = live ? id_raw : total - 1;
     const int t = (int)(id / a.O), o = (int)(id % a.O);
     const int ib = (a.M == 4) ? 2 : 4;
     const int kc = a.K / a.M * a.N;
@@ -226,6 +228,16 @@ gemm_generic_kernel(const GemmArgs a)
         sum += (int)x[(e / a.N) * a.M + off] * q;
     }
     const size_t at = (size_t)t * a.ldo + o;
+    if (a.out_dtype == 3) {                    // requantised output: every lane takes part in the reduction of max |y|
+        const float p[4] = {a.act_scale * a.scales[o], 0.f, 0.f, 0.f};
+        const float b[4] = {a.bias ? a.bias[o] : 0.0f, 0.f, 0.f, 0.f};
+        float m = 0.0f;
+        const uint32_t q = requant4(v4i{sum, 0, 0, 0}, p, b, a.out_scale, m);
+        if (live) reinterpret_cast<uint8_t*>(a.out)[at] = (uint8_t)q;
+        absmax_commit(m, a.absmax);
+        return;
+    }
+    if (!live) return;
     if (a.acc) a.acc[at] = sum;
     if (a.out_dtype != 0) {
         float y = (float)sum * (a.act_scale * a.scales[o]) + (a.bias ? a.bias[o] : 0.0f);
@@ -309,7 +321,7 @@ void launch_pattern(const GemmArgs& a, hipStream_t st, int tile_cfg)
 
 int launch_gemm(const GemmArgs& a, hipStream_t st)
 {
-    const bool out_ok = a.out_dtype == 0 || (uintptr_t)a.out % 16 == 0;
+    const bool out_ok = a.out_dtype == 0 || (uintptr_t)a.out % 16 == 0;   // (int8 codes: rows are then whole dwords, ldo % 4 == 0)
     const bool fast = a.N <= 2 && a.K % 128 == 0 && a.O % 4 == 0 && a.ldx % 16 == 0 && a.ldo % 4 == 0 &&
                       (uintptr_t)a.X % 16 == 0 && (uintptr_t)a.vals % 16 == 0 && (uintptr_t)a.meta % 4 == 0 &&
                       (uintptr_t)a.scales % 16 == 0 && (uintptr_t)a.bias % 16 == 0 && (uintptr_t)a.acc % 16 == 0 && out_ok;

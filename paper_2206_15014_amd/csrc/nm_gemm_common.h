@@ -272,12 +272,40 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, nm_bf16x2));
 }
 
+// Requantised output (Eq. 4, then Eq. 5 at 8 bits, both with offset 0): the four outputs a lane
+// holds of one token, as four codes packed little-endian (column r in byte r).  One fp32 operation
+// per step, in the order the declaration of nm_gemm_q8 fixes: p = act_scale * scale (the caller
+// passes it), y = fma(float(acc), p, bias), code = clamp(rne(y / out_scale), -127, 127).  `m`
+// collects max |y|.
+__device__ __forceinline__ uint32_t requant4(const v4i c, const float (&p)[4], const float (&b)[4], float out_scale, float& m)
+{
+    uint32_t packed = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float y = __fmaf_rn((float)c[r], p[r], b[r]);
+        m = fmaxf(m, fabsf(y));
+        const float q = fminf(fmaxf(rintf(__fdiv_rn(y, out_scale)), -127.0f), 127.0f);
+        packed |= ((uint32_t)(int)q & 255u) << (8 * r);
+    }
+    return packed;
+}
+
+// Largest of `m` (>= 0) over the wavefront, max-combined into *dst by one atomic: non-negative
+// floats order like their bit patterns.  Every lane of the wavefront must call it.
+__device__ __forceinline__ void absmax_commit(float m, float* dst)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+    if ((threadIdx.x & 63) == 0 && dst != nullptr) atomicMax(reinterpret_cast<unsigned int*>(dst), __float_as_uint(m));
+}
+
 // Epilogue shared by the MFMA kernels: Eq. 4 with offset 0 applied to the product of two quantised
 // operands.  acc[fo][ft] is the 16x16 accumulator fragment of weight rows o_base + fo*16 .. and
 // tokens t_base + ft*16 ..; lane (li, lg) holds rows 4*lg .. 4*lg+3 of token li.
 template <int FO, int FT, class Args>
 __device__ __forceinline__ void store_tile(const Args& a, const v4i (&acc)[FO][FT], int o_base, int t_base, int li, int lg)
 {
+    float m = 0.0f;                            // max |y| of this lane (requantised output only)
 #pragma unroll
     for (int fo = 0; fo < FO; ++fo) {
         const int o = o_base + fo * 16 + 4 * lg;
@@ -302,15 +330,18 @@ __device__ __forceinline__ void store_tile(const Args& a, const v4i (&acc)[FO][F
                 for (int r = 0; r < 4; ++r) y[r] = (float)c[r] * sc[r] + bs[r];
                 if (a.out_dtype == 1) {
                     *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + at) = make_float4(y[0], y[1], y[2], y[3]);
-                } else {
+                } else if (a.out_dtype == 2) {
                     uint2 p;
                     p.x = pack_bf16x2(y[0], y[1]);
                     p.y = pack_bf16x2(y[2], y[3]);
                     *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = p;
+                } else {
+                    *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.out) + at) = requant4(c, sc, bs, a.out_scale, m);
                 }
             }
         }
     }
+    if (a.out_dtype == 3) absmax_commit(m, a.absmax);
 }
 
 // Same, with the row scales and biases already in registers (sw[fo], bw[fo] hold rows
@@ -319,6 +350,7 @@ template <int FO, int FT, class Args>
 __device__ __forceinline__ void store_tile_pre(const Args& a, const v4i (&acc)[FO][FT], const float4 (&sw)[FO], const float4 (&bw)[FO],
                                                int o_base, int t_base, int li, int lg)
 {
+    float m = 0.0f;                            // max |y| of this lane (requantised output only)
 #pragma unroll
     for (int fo = 0; fo < FO; ++fo) {
         const int o = o_base + fo * 16 + 4 * lg;
@@ -338,15 +370,18 @@ __device__ __forceinline__ void store_tile_pre(const Args& a, const v4i (&acc)[F
                 for (int r = 0; r < 4; ++r) y[r] = (float)c[r] * sc[r] + bs[r];
                 if (a.out_dtype == 1) {
                     *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + at) = make_float4(y[0], y[1], y[2], y[3]);
-                } else {
+                } else if (a.out_dtype == 2) {
                     uint2 p;
                     p.x = pack_bf16x2(y[0], y[1]);
                     p.y = pack_bf16x2(y[2], y[3]);
                     *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = p;
+                } else {
+                    *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.out) + at) = requant4(c, sc, bs, a.out_scale, m);
                 }
             }
         }
     }
+    if (a.out_dtype == 3) absmax_commit(m, a.absmax);
 }
 
 }  // namespace

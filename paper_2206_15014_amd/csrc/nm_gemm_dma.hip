@@ -427,8 +427,8 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         store_tile_pre<FO, FT>(a, acc, sw, bw, o0 + wo * WO, t0 + wt * WT, li, lg);
         return;
     }
-    const int esize = (a.out_dtype == 1) ? 4 : 2;
-    if ((a.ldo * esize) % 16 != 0) {                       // rows not 16-byte aligned
+    const int esize = (a.out_dtype == 1) ? 4 : (a.out_dtype == 2) ? 2 : 1;
+    if ((a.ldo * esize) % (a.out_dtype == 3 ? 8 : 16) != 0) {   // rows not 16-byte (int8 codes: 8-byte) aligned
         store_tile_pre<FO, FT>(a, acc, sw, bw, o0 + wo * WO, t0 + wt * WT, li, lg);
         return;
     }
@@ -442,6 +442,42 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         y[2] = (float)c[2] * (a.act_scale * sw[fo].z) + bw[fo].z;
         y[3] = (float)c[3] * (a.act_scale * sw[fo].w) + bw[fo].w;
     };
+    typedef unsigned v2u __attribute__((ext_vector_type(2)));
+    if (a.out_dtype == 3) {
+        // int8 codes for the next layer: a fragment is one dword per lane; two fragments exchange
+        // 16-lane rows as for bf16 below and a lane stores 8 consecutive columns of one token.
+        float m = 0.0f;
+        auto codes = [&](auto foc, auto ftc) __attribute__((always_inline)) -> uint32_t {
+            constexpr int fo = decltype(foc)::value, ft = decltype(ftc)::value;
+            const float p[4] = {a.act_scale * sw[fo].x, a.act_scale * sw[fo].y, a.act_scale * sw[fo].z, a.act_scale * sw[fo].w};
+            const float b[4] = {bw[fo].x, bw[fo].y, bw[fo].z, bw[fo].w};
+            return requant4(acc[fo][ft], p, b, a.out_scale, m);
+        };
+        auto emit8 = [&](uint32_t da, uint32_t db, int row, int col) __attribute__((always_inline)) {
+            const v2u x = __builtin_amdgcn_permlane16_swap(da, db, false, false);
+            if (row < a.tokens) *reinterpret_cast<uint2*>(out + (size_t)row * a.ldo + col) = make_uint2(x[0], x[1]);
+        };
+        int_for<FT>([&](auto ftc) __attribute__((always_inline)) {
+            constexpr int ft = decltype(ftc)::value;
+            int_for<FO / 2>([&](auto h) __attribute__((always_inline)) {
+                constexpr int fo = 2 * decltype(h)::value;
+                const uint32_t da = codes(std::integral_constant<int, fo>{}, ftc);
+                const uint32_t db = codes(std::integral_constant<int, fo + 1>{}, ftc);
+                emit8(da, db, row0 + ft * 16, col0 + fo * 16 + (lg & 1) * 16 + (lg >> 1) * 8);
+            });
+        });
+        if constexpr (FO % 2 == 1) {
+            constexpr int fo = FO - 1;
+            int_for<FT / 2>([&](auto h) __attribute__((always_inline)) {
+                constexpr int ft = 2 * decltype(h)::value;
+                const uint32_t da = codes(std::integral_constant<int, fo>{}, std::integral_constant<int, ft>{});
+                const uint32_t db = codes(std::integral_constant<int, fo>{}, std::integral_constant<int, ft + 1>{});
+                emit8(da, db, row0 + (ft + (lg & 1)) * 16, col0 + fo * 16 + (lg >> 1) * 8);
+            });
+        }
+        absmax_commit(m, a.absmax);
+        return;
+    }
     if (a.out_dtype == 1) {
         // fp32: the accumulator layout is already 16 bytes per lane, 64 contiguous bytes per
         // token and instruction.  Always written through: measured faster at every size.
@@ -466,7 +502,6 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     // writes 64 contiguous bytes per token.  An odd last fragment pairs with its neighbour along
     // the tokens instead: lane row lg then holds columns (lg >> 1) * 8 onwards of token fragment
     // ft + (lg & 1).  No trip through the LDS, no barrier.
-    typedef unsigned v2u __attribute__((ext_vector_type(2)));
     const bool through = a.store_through != 0;
     auto emit = [&](const float (&ya)[4], const float (&yb)[4], int row, int col) __attribute__((always_inline)) {
         const v2u x = __builtin_amdgcn_permlane16_swap(pack_bf16x2(ya[0], ya[1]), pack_bf16x2(yb[0], yb[1]), false, false);

@@ -414,7 +414,7 @@ bool launch_stream_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 bool launch_gemm_stream(const GemmArgs& a, hipStream_t st, int cfg)
 {
     const int esize = (a.out_dtype == 1) ? 4 : 2;
-    if (a.acc != nullptr || a.out_dtype == 0 || a.out == nullptr) return false;
+    if (a.acc != nullptr || (a.out_dtype != 1 && a.out_dtype != 2) || a.out == nullptr) return false;
     if (((size_t)a.ldo * esize) % 16 != 0 || (uintptr_t)a.out % 16 != 0) return false;
     if ((uintptr_t)a.scales % 16 != 0 || (uintptr_t)a.bias % 16 != 0 || (uintptr_t)a.meta % 16 != 0) return false;
     if (a.K % 128 != 0 || a.K < 128) return false;

@@ -380,7 +380,7 @@ bool launch_xres_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 bool launch_gemm_xres(const GemmArgs& a, hipStream_t st, int cfg)
 {
     const int esize = (a.out_dtype == 1) ? 4 : 2;
-    if (a.acc != nullptr || a.out_dtype == 0 || a.out == nullptr) return false;
+    if (a.acc != nullptr || (a.out_dtype != 1 && a.out_dtype != 2) || a.out == nullptr) return false;
     if (((size_t)a.ldo * esize) % 16 != 0 || (uintptr_t)a.out % 16 != 0) return false;
     if ((uintptr_t)a.scales % 16 != 0 || (uintptr_t)a.bias % 16 != 0) return false;
     if ((uintptr_t)a.vals % 16 != 0 || (uintptr_t)a.meta % 16 != 0 || a.vstride % 16 != 0 || a.mstride % 16 != 0) return false;

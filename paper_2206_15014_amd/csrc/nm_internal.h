@@ -20,10 +20,12 @@ struct GemmArgs {
     const float* bias;     // [O] or null
     int32_t* acc;          // [tokens][ldo] or null
     void* out;             // [tokens][ldo] or null
-    int out_dtype;         // nm_out_dtype
+    int out_dtype;         // nm_out_dtype; 3 = int8 codes (nm_gemm_q8)
     int ldo;
     int vstride, mstride;  // packed row strides in bytes
     int store_through;     // set by a launcher: output stores bypass the L2's write-back (large outputs)
+    float out_scale;       // out_dtype 3: scale of the output codes
+    float* absmax;         // out_dtype 3: max |y| is max-combined into it, or null
 };
 
 // Launch-error bracket: begin_launch() drops any stale error left in this thread by earlier HIP

@@ -17,7 +17,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "nm.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", header))
-    assert names >= {"nm_packed_sizes", "nm_compress", "nm_decompress_i8", "nm_gemm", "nm_status_string"}
+    assert names >= {"nm_packed_sizes", "nm_compress", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8", "nm_status_string"}
     lib = ctypes.CDLL(binding.library_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -60,6 +60,18 @@ def test_entry_points_validate_before_launch():
     assert g(out=P) == -5                    # output buffer but dtype none
     assert g(acc=None) == -1                 # nothing to write
     assert g(acc=P + 1) == -6
+    q = lambda **k: lib.nm_gemm_q8(*[k.get(n, d) for n, d in [
+        ("X", P), ("T", 4), ("K", 8), ("ldx", 8), ("s", 1.0), ("v", P), ("m", P), ("sc", P), ("O", 8), ("N", 2),
+        ("M", 4), ("bits", 8), ("bias", None), ("so", 0.5), ("out", P), ("ldo", 8), ("amax", None), ("st", None)]])
+    assert q(out=None) == -1
+    assert q(X=None) == -1
+    assert q(T=0) == -2
+    assert q(ldo=4) == -2
+    assert q(N=4) == -3
+    assert q(bits=5) == -4
+    assert q(so=0.0) == -2 and q(so=-1.0) == -2 and q(so=float("inf")) == -2 and q(so=float("nan")) == -2
+    assert q(out=P + 2) == -6
+    assert q(amax=P + 1) == -6
 
 
 def test_status_strings():

@@ -377,3 +377,94 @@ def test_results_do_not_depend_on_repetition():
     a = run_gemm(Xq, sx, packed, g.O, g.N, g.M, g.bits, None, want=("acc",))["acc"]
     b = run_gemm(Xq, sx, packed, g.O, g.N, g.M, g.bits, None, want=("acc",))["acc"]
     assert np.array_equal(a, b)
+
+
+# ---- requantised output (nm_gemm_q8): codes and max |y| bit-exact -------------------------------
+def run_gemm_q8(Xq, sx, packed, O, N, M, bits, bias, out_scale, ldo=None, start_max=0.0):
+    vals, meta, scales = packed
+    X = torch.from_numpy(Xq).to(DEV)
+    T = Xq.shape[0]
+    ldo = ldo or O
+    b = None if bias is None else torch.from_numpy(bias).to(DEV)
+    out = torch.full((T, ldo), -77, dtype=torch.int8, device=DEV)
+    amax = torch.full((1,), start_max, dtype=torch.float32, device=DEV)
+    nm.nm_gemm_q8(X, float(sx), vals, meta, scales, O, N, M, bits, float(out_scale), out, bias=b, absmax=amax, ldo=ldo)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), float(amax.item())
+
+
+def check_q8(acc_ref, sx, scales_ref, bias, out_scale, q_gpu, amax_gpu, what=""):
+    q_ref, amax_ref = oracle.requant(acc_ref, float(sx), scales_ref, float(out_scale), bias)
+    assert np.array_equal(q_gpu, q_ref), "%s: int8 codes differ at %d places" % (what, np.count_nonzero(q_gpu != q_ref))
+    assert amax_gpu == amax_ref, "%s: max |y| %r against %r" % (what, amax_gpu, amax_ref)
+
+
+def q8_scale(acc_ref, sx, scales_ref, bias):
+    """An output scale that uses the code range: max |y| / 127, as a caller would choose it."""
+    f32, _ = oracle.dequant(acc_ref, float(sx), scales_ref, bias)
+    return np.float32(np.abs(f32).max() / 127.0)
+
+
+@pytest.mark.parametrize("tile", ["0", "2", "113", "116", "122", "201", "301"])
+@pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (1, 4, 4), (2, 8, 4)])
+def test_gemm_q8_fast_paths(N, M, bits, tile):
+    """Every kernel family (201 and 301 do not write codes and must hand the call on), whole and
+    ragged tiles, rows of 8-byte and of 4-byte granularity, with and without bias."""
+    say("gemm q8", N, M, bits, "tile", tile)
+    os.environ["NM_GEMM_TILE"] = tile
+    try:
+        for T, K, O, with_bias, pad in [(300, 256, 392, True, 0), (129, 512, 260, False, 0), (512, 768, 768, True, 8), (16, 384, 64, True, 4)]:
+            W, Xq, sx, bias, ref, acc_ref = small_case(N, M, bits, T, K, O, 21, with_bias=with_bias)
+            packed = gpu_compress(W, N, M, bits)
+            so = q8_scale(acc_ref, sx, ref[2], bias)
+            q, amax = run_gemm_q8(Xq, sx, packed, O, N, M, bits, bias, so, ldo=O + pad)
+            assert np.all(q[:, O:] == -77)                 # padding untouched
+            check_q8(acc_ref, sx, ref[2], bias, so, q[:, :O], amax, what="T%d K%d O%d" % (T, K, O))
+    finally:
+        os.environ.pop("NM_GEMM_TILE", None)
+
+
+@pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (3, 4, 8), (4, 8, 4), (1, 8, 8)])
+def test_gemm_q8_generic_path_and_saturation(N, M, bits):
+    say("gemm q8 generic", N, M, bits)
+    for T, K, O in [(7, 3 * M, 5), (33, 40, 18), (3, 136, 129)]:
+        if K % M:
+            continue
+        W, Xq, sx, bias, ref, acc_ref = small_case(N, M, bits, T, K, O, 22)
+        packed = gpu_compress(W, N, M, bits)
+        so = q8_scale(acc_ref, sx, ref[2], bias)
+        for scale in (so, np.float32(so / 16)):            # the second one saturates most codes at +-127
+            q, amax = run_gemm_q8(Xq, sx, packed, O, N, M, bits, bias, scale)
+            check_q8(acc_ref, sx, ref[2], bias, scale, q, amax, what="T%d K%d O%d scale %g" % (T, K, O, scale))
+            assert q.min() >= -127
+
+
+def test_gemm_q8_running_maximum_is_kept():
+    W, Xq, sx, bias, ref, acc_ref = small_case(2, 4, 8, 64, 256, 96, 23)
+    packed = gpu_compress(W, 2, 4, 8)
+    so = q8_scale(acc_ref, sx, ref[2], bias)
+    _, amax_ref = oracle.requant(acc_ref, float(sx), ref[2], float(so), bias)
+    _, amax = run_gemm_q8(Xq, sx, packed, 96, 2, 4, 8, bias, so, start_max=amax_ref * 4.0)
+    assert amax == np.float32(amax_ref * 4.0)              # a larger value already there survives
+    _, amax = run_gemm_q8(Xq, sx, packed, 96, 2, 4, 8, bias, so, start_max=amax_ref / 4.0)
+    assert amax == amax_ref
+
+
+def test_gemm_q8_full_size_layer_feeds_the_next_one():
+    """BERT-base FFN-up at 4096 tokens in the configuration the benchmark uses, its codes checked in
+    full, then used as the activations of FFN-down: the chain never leaves int8."""
+    say("gemm q8 full size")
+    g_up, g_down = [g for g in synth.config2() if g.name in ("ffn_up", "ffn_down")]
+    W = synth.weights(g_up); Xq, sx = synth.activations(g_up); bias = synth.bias(g_up)
+    ref = oracle.compress(W, 2, 4, 8)
+    acc_ref = oracle.gemm_sparse(Xq, ref[0], ref[1], g_up.O, 2, 4, 8)
+    packed = gpu_compress(W, 2, 4, 8)
+    so = q8_scale(acc_ref, sx, ref[2], bias)
+    q, amax = run_gemm_q8(Xq, sx, packed, g_up.O, 2, 4, 8, bias, so)
+    check_q8(acc_ref, sx, ref[2], bias, so, q, amax, what="ffn_up")
+    W2 = synth.weights(g_down)
+    ref2 = oracle.compress(W2, 2, 4, 8)
+    acc2_ref = oracle.gemm_sparse(q, ref2[0], ref2[1], g_down.O, 2, 4, 8)
+    packed2 = gpu_compress(W2, 2, 4, 8)
+    res = run_gemm(q, so, packed2, g_down.O, 2, 4, 8, None, want=("acc",))
+    assert np.array_equal(res["acc"], acc2_ref)
