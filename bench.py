@@ -32,7 +32,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--out-dtype", choices=["bf16", "f32"], default="bf16")
+    ap.add_argument("--out-dtype", choices=["bf16", "f32", "i8"], default="bf16",
+                    help="i8: nm_gemm_q8, the layer output as int8 codes for the next layer (not the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--workload", choices=["bert_base", "single", "copy"], default="bert_base",
@@ -86,7 +87,8 @@ def main():
         workload_name = ("BERT-base encoder layer linear set (QKV, attn-out, FFN-up, FFN-down), 2:4 int8, "
                          "32x128=4096 tokens")
     out_code = NM_OUT_BF16 if args.out_dtype == "bf16" else NM_OUT_F32
-    out_torch = torch.bfloat16 if args.out_dtype == "bf16" else torch.float32
+    out_torch = {"bf16": torch.bfloat16, "f32": torch.float32, "i8": torch.int8}[args.out_dtype]
+    out_bytes = {"bf16": 2, "f32": 4, "i8": 1}[args.out_dtype]
 
     # ---- resident inputs and preallocated outputs -------------------------------------------
     host = []
@@ -102,7 +104,8 @@ def main():
             W=torch.from_numpy(W).to(dev), X=torch.from_numpy(Xq).to(dev), bias=torch.from_numpy(b).to(dev),
             vals=torch.empty(vb, dtype=torch.uint8, device=dev), meta=torch.empty(mb, dtype=torch.uint8, device=dev),
             scales=torch.empty(g.O, dtype=torch.float32, device=dev),
-            out=torch.empty((g.T, g.O), dtype=out_torch, device=dev)))
+            out=torch.empty((g.T, g.O), dtype=out_torch, device=dev),
+            absmax=torch.zeros(1, dtype=torch.float32, device=dev)))
     stream = torch.cuda.current_stream().cuda_stream
 
     def compress_args(j):
@@ -110,8 +113,14 @@ def main():
         return (j["W"].data_ptr(), g.O, g.K, g.K, g.N, g.M, g.bits, j["vals"].data_ptr(), j["meta"].data_ptr(),
                 j["scales"].data_ptr(), stream)
 
+    gemm_fn = lib.nm_gemm_q8 if args.out_dtype == "i8" else lib.nm_gemm
+
     def gemm_args(j):
         g = j["g"]
+        if args.out_dtype == "i8":         # any positive scale times the same: 1/16 keeps most codes inside the range
+            return (j["X"].data_ptr(), g.T, g.K, g.K, j["sx"], j["vals"].data_ptr(), j["meta"].data_ptr(),
+                    j["scales"].data_ptr(), g.O, g.N, g.M, g.bits, j["bias"].data_ptr(), 0.0625, j["out"].data_ptr(),
+                    g.O, j["absmax"].data_ptr(), stream)
         return (j["X"].data_ptr(), g.T, g.K, g.K, j["sx"], j["vals"].data_ptr(), j["meta"].data_ptr(),
                 j["scales"].data_ptr(), g.O, g.N, g.M, g.bits, j["bias"].data_ptr(), None, j["out"].data_ptr(),
                 out_code, g.O, stream)
@@ -126,7 +135,7 @@ def main():
     def step():
         for ca, ga in zip(cargs, gargs):
             check(lib.nm_compress(*ca))
-            check(lib.nm_gemm(*ga))
+            check(gemm_fn(*ga))
 
     side = torch.cuda.Stream()
 
@@ -172,7 +181,7 @@ def main():
     for _ in range(max(args.warmup, 1)):
         step()
     torch.cuda.synchronize()
-    per_gemm_us = [timed_launches(lib.nm_gemm, a, 40) for a in gargs]
+    per_gemm_us = [timed_launches(gemm_fn, a, 40) for a in gargs]
     per_comp_us = [timed_launches(lib.nm_compress, a, 40) for a in cargs]
     dom = int(np.argmax(per_gemm_us))
 
@@ -194,7 +203,7 @@ def main():
                 for _ in range(steps_per_graph):
                     for ca, ga in zip(cg, gg):
                         check(lib.nm_compress(*ca))
-                        check(lib.nm_gemm(*ga))
+                        check(gemm_fn(*ga))
         torch.cuda.current_stream().wait_stream(side)
         for _ in range(3):
             graph.replay()
@@ -212,7 +221,7 @@ def main():
     # Launch duration of the dominant kernel: HIP events around back-to-back (graph-replayed) launches
     # of that same kernel, right after the timed steps; a rocprofv3 kernel trace of this command
     # reports the same kernel about a microsecond shorter (the gap between two launches).
-    dom_us = timed_launches(lib.nm_gemm, gargs[dom], 40)
+    dom_us = timed_launches(gemm_fn, gargs[dom], 40)
     dense_ops = sum(g.dense_ops for g in gemms)
     value = dense_ops / (ms_per_step * 1e-3) / 1e12
 
@@ -238,7 +247,7 @@ def main():
             "traffic": MEASURED_HBM_BYTES_BF16.get(gd.name) if (args.workload == "bert_base" and args.out_dtype == "bf16") else None,
             "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated on a copy; a stored figure)",
             "algorithmic_bytes": gd.T * gd.K + gd.O * (gd.K // gd.M * gd.N) * (gd.bits + 2) // 8 + 8 * gd.O
-                                 + gd.T * gd.O * (2 if args.out_dtype == "bf16" else 4),
+                                 + gd.T * gd.O * out_bytes,
             "kernel": "nm_gemm %s %dx%d->%d" % (gd.name, gd.T, gd.K, gd.O),
             "note": "int8 multiply-add ops, dense-equivalent (zeros counted), against the dense int8 MFMA peak; "
                     "duration = HIP events around 200 back-to-back launches of this kernel (5 replays of a 40-launch graph) after the timed steps",
@@ -261,10 +270,11 @@ def main():
         vb, mb, _ = nm.nm_packed_sizes(gs.O, gs.K, gs.N, gs.M, gs.bits)
         js.update(vals=torch.empty(vb, dtype=torch.uint8, device=dev), meta=torch.empty(mb, dtype=torch.uint8, device=dev),
                   scales=torch.empty(gs.O, dtype=torch.float32, device=dev),
-                  out=torch.empty((gs.T, gs.O), dtype=out_torch, device=dev))
+                  out=torch.empty((gs.T, gs.O), dtype=out_torch, device=dev),
+                  absmax=torch.zeros(1, dtype=torch.float32, device=dev))
         check(lib.nm_compress(*compress_args(js)))
-        us = timed_launches(lib.nm_gemm, gemm_args(js), 40)
-        esz = 2 if args.out_dtype == "bf16" else 4
+        us = timed_launches(gemm_fn, gemm_args(js), 40)
+        esz = out_bytes
         nbytes = gs.T * gs.K + vb + mb + 8 * gs.O + gs.T * gs.O * esz
         result["kernels"]["skinny_gemm_128x768x768"] = {
             "us_back_to_back": round(us, 2), "algorithmic_bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1),

@@ -38,7 +38,10 @@
  *   - requantised output: the paper fixes neither where the activation scale
  *     comes from nor the arithmetic; here the caller supplies the scale, and,
  *     because a rounding decides an integer, the value is formed in fp32 in a
- *     fixed order (see nmo_requant) that the GPU path follows bit for bit.
+ *     fixed order (see nmo_requant) that the GPU path follows bit for bit; the
+ *     division of Eq. 5 is applied to each column's multiplier and offset, not
+ *     to each output (a per-output division costs more than the whole rest of
+ *     the epilogue and changes a result by at most an fp32 rounding).
  *
  * Build: gcc -O2 -std=c11 -fno-fast-math -ffp-contract=off -fopenmp -shared -fPIC
  *
@@ -46,8 +49,8 @@
  * supports, N=1 == argmax, idempotence, max-survives-pruning invariant,
  * quantiser closed forms and half-way cases, an independent numpy decoder of
  * the byte format, numpy int64 matmul on the decompressed matrix, dequant
- * special cases; requantisation against exact rational arithmetic on inputs
- * whose fp32 steps are exact, half-way and saturation cases.  The tie-break rule and the byte format are this build's own
+ * special cases; requantisation against exact rational arithmetic with each
+ * fp32 rounding applied explicitly, half-way and saturation cases.  The tie-break rule and the byte format are this build's own
  * choices (the paper fixes neither): pinned by the written format description
  * and the independent decoder, not by the paper.
  */
@@ -344,15 +347,18 @@ int nmo_dequant(const int32_t *acc, int tokens, int O, int ldacc, float act_scal
 
 /*
  * Layer output as 8-bit activations for the next layer: Eq. 4 (o = 0) followed
- * by Eq. 5 (o = 0, 8 bits) with the caller's scale.  Every step is one fp32
- * operation, in this order:
- *   p = act_scale * s_w[o]                      (multiplication)
- *   y = fma((float)acc, p, bias[o] or 0)        (int32 -> float conversion rounds
+ * by Eq. 5 (o = 0, 8 bits) with the caller's scale.  The division by the scale
+ * is taken once per output column (folded into the column's multiplier and
+ * offset) instead of once per output; every step is one fp32 operation, in this
+ * order:
+ *   g[o] = (act_scale * s_w[o]) / out_scale     (multiplication, then division)
+ *   h[o] = bias[o] / out_scale, or 0            (division)
+ *   z    = fma((float)acc, g[o], h[o])          (int32 -> float conversion rounds
  *                                                to nearest even, then one fused
  *                                                multiply-add)
- *   q = clamp(rne(y / out_scale), -127, 127)    (division, round half to even)
- * absmax, when given, receives max |y| over all outputs (the statistic a caller
- * needs to choose the next out_scale).
+ *   q    = clamp(rne(z), -127, 127)             (round half to even)
+ * absmax, when given, receives (max |z|) * out_scale: max |y| up to rounding,
+ * the statistic a caller needs to choose the next out_scale.
  */
 int nmo_requant(const int32_t *acc, int tokens, int O, int ldacc, float act_scale,
                 const float *scales, const float *bias, float out_scale,
@@ -361,14 +367,23 @@ int nmo_requant(const int32_t *acc, int tokens, int O, int ldacc, float act_scal
     if (!acc || !scales || !out) return NMO_ERR_NULL;
     if (tokens <= 0 || O <= 0 || ldacc < O || ldo < O) return NMO_ERR_DIM;
     if (!(out_scale > 0.0f) || !isfinite(out_scale)) return NMO_ERR_NONFINITE;
-    float amax = 0.0f;
-    for (int t = 0; t < tokens; ++t)
-        for (int o = 0; o < O; ++o) {
-            volatile float p = act_scale * scales[o];
-            volatile float y = fmaf((float)acc[(size_t)t * ldacc + o], p, bias ? bias[o] : 0.0f);
-            if (fabsf(y) > amax) amax = fabsf(y);
-            out[(size_t)t * ldo + o] = (int8_t)nmo_quantize_one(y, out_scale, 8);
+    float zmax = 0.0f;
+    for (int o = 0; o < O; ++o) {
+        volatile float p = act_scale * scales[o];
+        volatile float g = p / out_scale;
+        volatile float h = bias ? bias[o] / out_scale : 0.0f;
+        for (int t = 0; t < tokens; ++t) {
+            volatile float z = fmaf((float)acc[(size_t)t * ldacc + o], g, h);
+            if (fabsf(z) > zmax) zmax = fabsf(z);
+            float r = nearbyintf(z);
+            if (r > 127.0f) r = 127.0f;
+            if (r < -127.0f) r = -127.0f;
+            out[(size_t)t * ldo + o] = (int8_t)r;
         }
-    if (absmax) *absmax = amax;
+    }
+    if (absmax) {
+        volatile float m = zmax * out_scale;
+        *absmax = m;
+    }
     return NMO_OK;
 }

@@ -290,13 +290,21 @@ __device__ __forceinline__ uint32_t requant4(const v4i c, const float (&p)[4], c
     return packed;
 }
 
-// Largest of `m` (>= 0) over the wavefront, max-combined into *dst by one atomic: non-negative
-// floats order like their bit patterns.  Every lane of the wavefront must call it.
+// Largest of `m` (>= 0) over the wavefront, max-combined into *dst: non-negative floats order like
+// their bit patterns, so an unsigned atomic maximum does it.  Thousands of wavefronts meet at that
+// one address and an atomic there costs some 15 ns, so a wavefront first reads the value (at agent
+// scope; it only ever grows, so one that is too old merely costs an atomic that was not needed)
+// and leaves the atomic out unless its own is larger - which after the first few is rare.
+// Every lane of the wavefront must call it.
 __device__ __forceinline__ void absmax_commit(float m, float* dst)
 {
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
-    if ((threadIdx.x & 63) == 0 && dst != nullptr) atomicMax(reinterpret_cast<unsigned int*>(dst), __float_as_uint(m));
+    if ((threadIdx.x & 63) == 0 && dst != nullptr) {
+        unsigned int* u = reinterpret_cast<unsigned int*>(dst);
+        if (__float_as_uint(m) > __hip_atomic_load(u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            atomicMax(u, __float_as_uint(m));
+    }
 }
 
 // Epilogue shared by the MFMA kernels: Eq. 4 with offset 0 applied to the product of two quantised
