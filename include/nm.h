@@ -122,17 +122,21 @@ int nm_gemm(const int8_t *X_dev, int tokens, int K, int ldx, float act_scale,
  * The same layer with its output handed on as 8-bit activations (Sec. 5.3: activations are
  * 8-bit integers), i.e. Eq. 4 followed by the scalar quantiser of Sec. 3.3, Eq. 5 (offset 0,
  * 8 bits) with a scale the caller supplies, so that a chain of layers never writes or re-reads a
- * floating-point tensor.  Arithmetic, one fp32 operation per step, in this order:
+ * floating-point tensor.  The division of Eq. 5 is taken once per output column, folded into the
+ * column's multiplier and offset; every step is one fp32 operation, in this order:
  *
- *   p       = act_scale * scales[o]
- *   y[t][o] = fma(float(acc[t][o]), p, bias[o] or 0)      (int32 -> float rounds to nearest even)
- *   q[t][o] = clamp(rne(y[t][o] / out_scale), -127, 127)  (true division, ties to even)
+ *   g[o]    = (act_scale * scales[o]) / out_scale        (multiplication, then true division)
+ *   h[o]    = bias[o] / out_scale, or 0 without bias
+ *   z[t][o] = fma(float(acc[t][o]), g[o], h[o])          (int32 -> float rounds to nearest even)
+ *   q[t][o] = clamp(rne(z[t][o]), -127, 127)             (ties to even)
  *
- *   out_scale   > 0, finite (host value); out_dev[t][o] * out_scale approximates y.
- *   out_dev     int8 [tokens][ldo], ldo >= O, 4-byte aligned.
+ *   out_scale   > 0, finite (host value); out_dev[t][o] * out_scale approximates the y of nm_gemm.
+ *   out_dev     int8 [tokens][ldo], ldo >= O, 4-byte aligned (rows that are whole 16-byte
+ *               pieces, ldo % 16 == 0 with a 16-byte aligned out_dev, are written fastest).
  *   absmax_dev  NULL, or one float that the caller has set (to 0, or to a running maximum
- *               >= 0) before the call: max over all outputs of |y| is max-combined into it
- *               atomically - the statistic from which the next out_scale is chosen.
+ *               >= 0) before the call: (max over all outputs of |z|) * out_scale, i.e. max |y|
+ *               up to rounding, is max-combined into it atomically - the statistic from which
+ *               the next out_scale is chosen.
  * Other arguments as for nm_gemm.  Errors: as nm_gemm; NM_ERR_DIM for an out_scale that is not
  * a positive finite number.
  */

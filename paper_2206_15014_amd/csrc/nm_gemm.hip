@@ -229,12 +229,12 @@ gemm_generic_kernel(const GemmArgs a)
     }
     const size_t at = (size_t)t * a.ldo + o;
     if (a.out_dtype == 3) {                    // requantised output: every lane takes part in the reduction of max |y|
-        const float p[4] = {a.act_scale * a.scales[o], 0.f, 0.f, 0.f};
-        const float b[4] = {a.bias ? a.bias[o] : 0.0f, 0.f, 0.f, 0.f};
+        float g[4] = {0.f, 0.f, 0.f, 0.f}, h[4] = {0.f, 0.f, 0.f, 0.f};
+        requant_column(a.act_scale, a.scales[o], a.bias ? a.bias[o] : 0.0f, a.out_scale, g[0], h[0]);
         float m = 0.0f;
-        const uint32_t q = requant4(v4i{sum, 0, 0, 0}, p, b, a.out_scale, m);
+        const uint32_t q = requant4(v4i{sum, 0, 0, 0}, g, h, m);
         if (live) reinterpret_cast<uint8_t*>(a.out)[at] = (uint8_t)q;
-        absmax_commit(m, a.absmax);
+        absmax_commit(m, a.out_scale, a.absmax);
         return;
     }
     if (!live) return;

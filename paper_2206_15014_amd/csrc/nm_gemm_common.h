@@ -272,22 +272,34 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, nm_bf16x2));
 }
 
-// Requantised output (Eq. 4, then Eq. 5 at 8 bits, both with offset 0): the four outputs a lane
-// holds of one token, as four codes packed little-endian (column r in byte r).  One fp32 operation
-// per step, in the order the declaration of nm_gemm_q8 fixes: p = act_scale * scale (the caller
-// passes it), y = fma(float(acc), p, bias), code = clamp(rne(y / out_scale), -127, 127).  `m`
-// collects max |y|.
-__device__ __forceinline__ uint32_t requant4(const v4i c, const float (&p)[4], const float (&b)[4], float out_scale, float& m)
+// Requantised output (Eq. 4, then Eq. 5 at 8 bits, both with offset 0), as the declaration of
+// nm_gemm_q8 fixes it: per column g = (act_scale * scale) / out_scale and h = bias / out_scale (one
+// fp32 operation each, true divisions), per output z = fma(float(acc), g, h) and
+// code = clamp(rne(z), -127, 127).
+__device__ __forceinline__ void requant_column(float act_scale, float scale, float bias, float out_scale, float& g, float& h)
 {
-    uint32_t packed = 0;
+    g = __fdiv_rn(act_scale * scale, out_scale);
+    h = __fdiv_rn(bias, out_scale);
+}
+
+// The four outputs a lane holds of one token, as four codes packed little-endian (column r in
+// byte r); `m` collects max |z|.
+__device__ __forceinline__ uint32_t requant4(const v4i c, const float (&g)[4], const float (&h)[4], float& m)
+{
+    // clamp(rne(z)) = rne(clamp(z)) because the bounds are integers; adding 1.5 * 2^23 to a value of
+    // magnitude <= 127 rounds it to an integer (nearest, ties to even: the add's own rounding) and
+    // leaves that integer, in two's complement, in the low byte of the sum's bit pattern.
+    uint32_t t[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const float y = __fmaf_rn((float)c[r], p[r], b[r]);
-        m = fmaxf(m, fabsf(y));
-        const float q = fminf(fmaxf(rintf(__fdiv_rn(y, out_scale)), -127.0f), 127.0f);
-        packed |= ((uint32_t)(int)q & 255u) << (8 * r);
+        const float z = __fmaf_rn((float)c[r], g[r], h[r]);
+        m = fmaxf(m, fabsf(z));
+        t[r] = __float_as_uint(__builtin_amdgcn_fmed3f(z, -127.0f, 127.0f) + 12582912.0f);
     }
-    return packed;
+    // bytes 0 of t[0..3] -> one dword
+    const uint32_t lo = __builtin_amdgcn_perm(t[1], t[0], 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm(t[3], t[2], 0x04000c0cu);
+    return lo | hi;
 }
 
 // Largest of `m` (>= 0) over the wavefront, max-combined into *dst: non-negative floats order like
@@ -295,11 +307,14 @@ __device__ __forceinline__ uint32_t requant4(const v4i c, const float (&p)[4], c
 // one address and an atomic there costs some 15 ns, so a wavefront first reads the value (at agent
 // scope; it only ever grows, so one that is too old merely costs an atomic that was not needed)
 // and leaves the atomic out unless its own is larger - which after the first few is rare.
-// Every lane of the wavefront must call it.
-__device__ __forceinline__ void absmax_commit(float m, float* dst)
+// Every lane of the wavefront must call it.  `m` is in units of the codes: the value committed is
+// m * out_scale (multiplying by a positive number keeps the order, so the largest product is the
+// product of the largest).
+__device__ __forceinline__ void absmax_commit(float m, float out_scale, float* dst)
 {
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+    m = m * out_scale;
     if ((threadIdx.x & 63) == 0 && dst != nullptr) {
         unsigned int* u = reinterpret_cast<unsigned int*>(dst);
         if (__float_as_uint(m) > __hip_atomic_load(u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
@@ -319,6 +334,7 @@ __device__ __forceinline__ void store_tile(const Args& a, const v4i (&acc)[FO][F
         const int o = o_base + fo * 16 + 4 * lg;
         if (o >= a.O) continue;
         const float4 sw = *reinterpret_cast<const float4*>(a.scales + o);
+        const float sws[4] = {sw.x, sw.y, sw.z, sw.w};
         const float sc[4] = {a.act_scale * sw.x, a.act_scale * sw.y, a.act_scale * sw.z, a.act_scale * sw.w};
         float bs[4] = {0.f, 0.f, 0.f, 0.f};
         if (a.bias) {
@@ -344,16 +360,20 @@ __device__ __forceinline__ void store_tile(const Args& a, const v4i (&acc)[FO][F
                     p.y = pack_bf16x2(y[2], y[3]);
                     *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = p;
                 } else {
-                    *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.out) + at) = requant4(c, sc, bs, a.out_scale, m);
+                    float g[4], h[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) requant_column(a.act_scale, sws[r], bs[r], a.out_scale, g[r], h[r]);
+                    *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.out) + at) = requant4(c, g, h, m);
                 }
             }
         }
     }
-    if (a.out_dtype == 3) absmax_commit(m, a.absmax);
+    if (a.out_dtype == 3) absmax_commit(m, a.out_scale, a.absmax);
 }
 
 // Same, with the row scales and biases already in registers (sw[fo], bw[fo] hold rows
-// o_base + fo*16 + 4*lg .. +3).
+// o_base + fo*16 + 4*lg .. +3).  For requantised output (out_dtype 3) they hold the columns'
+// multipliers g and offsets h instead.
 template <int FO, int FT, class Args>
 __device__ __forceinline__ void store_tile_pre(const Args& a, const v4i (&acc)[FO][FT], const float4 (&sw)[FO], const float4 (&bw)[FO],
                                                int o_base, int t_base, int li, int lg)
@@ -384,12 +404,13 @@ __device__ __forceinline__ void store_tile_pre(const Args& a, const v4i (&acc)[F
                     p.y = pack_bf16x2(y[2], y[3]);
                     *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out) + at) = p;
                 } else {
-                    *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.out) + at) = requant4(c, sc, bs, a.out_scale, m);
+                    const float g[4] = {sw[fo].x, sw[fo].y, sw[fo].z, sw[fo].w};
+                    *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.out) + at) = requant4(c, g, bs, m);
                 }
             }
         }
     }
-    if (a.out_dtype == 3) absmax_commit(m, a.absmax);
+    if (a.out_dtype == 3) absmax_commit(m, a.out_scale, a.absmax);
 }
 
 }  // namespace

@@ -422,6 +422,18 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     // accumulators, when asked for, and ragged column tiles take that route; the dequantised
     // output first trades registers between lanes so that every lane stores 16 bytes.
     const bool full_cols = (o0 + BO <= a.O);
+    if (a.out_dtype == 3) {
+        // Requantised output: the scale and bias of each column become its multiplier g and
+        // offset h (two divisions per column, done once by one lane each, in place in the LDS).
+        if (tid < BO) {
+            float* sp = reinterpret_cast<float*>(smem + SB_OFF) + tid;
+            float g, h;
+            requant_column(a.act_scale, sp[0], a.bias ? sp[256] : 0.0f, a.out_scale, g, h);
+            sp[0] = g;
+            sp[256] = h;
+        }
+        __syncthreads();
+    }
     read_scales();
     if (a.acc != nullptr || a.out_dtype == 0 || !full_cols) {
         store_tile_pre<FO, FT>(a, acc, sw, bw, o0 + wo * WO, t0 + wt * WT, li, lg);
@@ -449,18 +461,44 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         float m = 0.0f;
         auto codes = [&](auto foc, auto ftc) __attribute__((always_inline)) -> uint32_t {
             constexpr int fo = decltype(foc)::value, ft = decltype(ftc)::value;
-            const float p[4] = {a.act_scale * sw[fo].x, a.act_scale * sw[fo].y, a.act_scale * sw[fo].z, a.act_scale * sw[fo].w};
-            const float b[4] = {bw[fo].x, bw[fo].y, bw[fo].z, bw[fo].w};
-            return requant4(acc[fo][ft], p, b, a.out_scale, m);
+            const float g[4] = {sw[fo].x, sw[fo].y, sw[fo].z, sw[fo].w};    // the columns' multipliers and offsets
+            const float h[4] = {bw[fo].x, bw[fo].y, bw[fo].z, bw[fo].w};
+            return requant4(acc[fo][ft], g, h, m);
         };
         auto emit8 = [&](uint32_t da, uint32_t db, int row, int col) __attribute__((always_inline)) {
             const v2u x = __builtin_amdgcn_permlane16_swap(da, db, false, false);
             if (row < a.tokens) *reinterpret_cast<uint2*>(out + (size_t)row * a.ldo + col) = make_uint2(x[0], x[1]);
         };
+        // Four fragments side by side go one step further (v_permlane32_swap: upper half of the
+        // first operand against lower half of the second): lane row lg ends up with all 16 columns
+        // of fragment lg of the four, 16 bytes, in the order (P, R, Q, S) of the two exchanges.
+        constexpr int Q4 = FO / 4;
+        const bool wide = (a.ldo % 16 == 0) && ((uintptr_t)a.out % 16 == 0);
         int_for<FT>([&](auto ftc) __attribute__((always_inline)) {
             constexpr int ft = decltype(ftc)::value;
-            int_for<FO / 2>([&](auto h) __attribute__((always_inline)) {
-                constexpr int fo = 2 * decltype(h)::value;
+            if (wide) {
+                int_for<Q4>([&](auto h) __attribute__((always_inline)) {
+                    constexpr int fo = 4 * decltype(h)::value;
+                    const uint32_t ca = codes(std::integral_constant<int, fo>{}, ftc), cb = codes(std::integral_constant<int, fo + 1>{}, ftc);
+                    const uint32_t cc = codes(std::integral_constant<int, fo + 2>{}, ftc), cd = codes(std::integral_constant<int, fo + 3>{}, ftc);
+                    const v2u ab = __builtin_amdgcn_permlane16_swap(ca, cb, false, false);
+                    const v2u cd2 = __builtin_amdgcn_permlane16_swap(cc, cd, false, false);
+                    const v2u pq = __builtin_amdgcn_permlane32_swap(ab[0], cd2[0], false, false);
+                    const v2u rs = __builtin_amdgcn_permlane32_swap(ab[1], cd2[1], false, false);
+                    const int row = row0 + ft * 16;
+                    if (row < a.tokens)
+                        *reinterpret_cast<v4i*>(out + (size_t)row * a.ldo + col0 + (fo + lg) * 16) = v4i{(int)pq[0], (int)rs[0], (int)pq[1], (int)rs[1]};
+                });
+            } else {
+                int_for<2 * Q4>([&](auto h) __attribute__((always_inline)) {
+                    constexpr int fo = 2 * decltype(h)::value;
+                    const uint32_t da = codes(std::integral_constant<int, fo>{}, ftc);
+                    const uint32_t db = codes(std::integral_constant<int, fo + 1>{}, ftc);
+                    emit8(da, db, row0 + ft * 16, col0 + fo * 16 + (lg & 1) * 16 + (lg >> 1) * 8);
+                });
+            }
+            int_for<(FO - 4 * Q4) / 2>([&](auto h) __attribute__((always_inline)) {
+                constexpr int fo = 4 * Q4 + 2 * decltype(h)::value;
                 const uint32_t da = codes(std::integral_constant<int, fo>{}, ftc);
                 const uint32_t db = codes(std::integral_constant<int, fo + 1>{}, ftc);
                 emit8(da, db, row0 + ft * 16, col0 + fo * 16 + (lg & 1) * 16 + (lg >> 1) * 8);
@@ -475,7 +513,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
                 emit8(da, db, row0 + (ft + (lg & 1)) * 16, col0 + fo * 16 + (lg >> 1) * 8);
             });
         }
-        absmax_commit(m, a.absmax);
+        absmax_commit(m, a.out_scale, a.absmax);
         return;
     }
     if (a.out_dtype == 1) {

@@ -409,11 +409,11 @@ def q8_scale(acc_ref, sx, scales_ref, bias):
 @pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (1, 4, 4), (2, 8, 4)])
 def test_gemm_q8_fast_paths(N, M, bits, tile):
     """Every kernel family (201 and 301 do not write codes and must hand the call on), whole and
-    ragged tiles, rows of 8-byte and of 4-byte granularity, with and without bias."""
+    ragged tiles, rows of 16-byte, 8-byte and 4-byte granularity, with and without bias."""
     say("gemm q8", N, M, bits, "tile", tile)
     os.environ["NM_GEMM_TILE"] = tile
     try:
-        for T, K, O, with_bias, pad in [(300, 256, 392, True, 0), (129, 512, 260, False, 0), (512, 768, 768, True, 8), (16, 384, 64, True, 4)]:
+        for T, K, O, with_bias, pad in [(300, 256, 392, True, 0), (129, 512, 260, False, 0), (512, 768, 768, True, 8), (16, 384, 64, True, 4), (300, 256, 384, True, 16)]:
             W, Xq, sx, bias, ref, acc_ref = small_case(N, M, bits, T, K, O, 21, with_bias=with_bias)
             packed = gpu_compress(W, N, M, bits)
             so = q8_scale(acc_ref, sx, ref[2], bias)
