@@ -162,3 +162,19 @@ def requant(acc, act_scale, scales, out_scale, bias=None):
     _check(_load().nmo_requant(_p(acc), T, O, O, ctypes.c_float(act_scale), _p(scales), _p(bias),
                                ctypes.c_float(out_scale), _p(q), O, ctypes.byref(amax)))
     return q, float(amax.value)
+
+
+def admm_project(W, U, N, M, bits, rows_per_scale):
+    """(Z, U_out, scales): the Z-update Z = Pi(W + U) with both constraints and the dual update
+    U + W - Z; bits = 0 leaves the quantisation constraint out (scales is then None)."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    if U is not None:
+        U = np.ascontiguousarray(U, dtype=np.float32)
+        assert U.shape == W.shape
+    rows, cols = W.shape
+    Z = np.zeros((rows, cols), dtype=np.float32)
+    Uo = np.zeros((rows, cols), dtype=np.float32)
+    scales = np.zeros(rows, dtype=np.float32) if bits else None
+    _check(_load().nmo_admm_project(_p(W), _p(U), rows, cols, cols, N, M, bits, rows_per_scale,
+                                    _p(Z), _p(Uo), cols, _p(scales)))
+    return Z, Uo, scales

@@ -23,6 +23,12 @@
  *   nmo_gemm_sparse    Sec. 5.3: only the kept products are computed, low-bit
  *                      weights widened to the activation type, int32 sums.
  *   nmo_dequant        Sec. 3.3, Eq. 4 with o = 0: x_d = s * x_q.
+ *   nmo_admm_project   Sec. 3.1, the Z-update Z = Pi(W + U) (Eq. 3 on W + U), with
+ *                      the quantisation constraint solved after the sparsity one
+ *                      (Sec. 3.3.1, ADMM-Max: scale = largest magnitude of W + U in
+ *                      the scale group / largest code; "group" = a run of output
+ *                      neurons, Sec. 4: 32 by default) and the scaled dual update
+ *                      U <- U + W - Z of the ADMM decomposition.
  *   nmo_requant        Sec. 5.3 (activations are 8-bit integers) with the scalar
  *                      quantiser of Sec. 3.3, Eq. 5 (o = 0) applied to a layer's
  *                      output, so that the next layer reads int8 again.
@@ -384,6 +390,83 @@ int nmo_requant(const int32_t *acc, int tokens, int O, int ldacc, float act_scal
     if (absmax) {
         volatile float m = zmax * out_scale;
         *absmax = m;
+    }
+    return NMO_OK;
+}
+
+/*
+ * The ADMM Z-update and dual update on one weight matrix, in fp32, one operation
+ * per step:
+ *   V      = W + U                                (U == NULL: V = W)
+ *   keep   = Eq. 3 on V (N largest magnitudes of every M, ties to the lower column)
+ *   bits 0 : Z = V on kept positions, +0 elsewhere
+ *   bits b : scale group = rows_per_scale consecutive rows (the last one may be
+ *            shorter); s = (largest |V| in the group) / qmax, 1 for an all-zero
+ *            group; q = Eq. 5 (o = 0) of V with s; Z = s * q on kept positions
+ *            (one multiplication), +0 elsewhere
+ *   U_out  = V - Z                                (when U_out is given)
+ * scales, when given (bits > 0), receives the scale of every row (rows of one
+ * group hold the same value).
+ */
+int nmo_admm_project(const float *W, const float *U, int rows, int cols, int ldw,
+                     int N, int M, int bits, int rows_per_scale,
+                     float *Z, float *U_out, int ldz, float *scales)
+{
+    int rc = check_pattern(rows, cols, N, M, bits ? bits : 8);
+    if (rc) return rc;
+    if (!W || !Z) return NMO_ERR_NULL;
+    if (ldw < cols || ldz < cols || rows_per_scale < 1) return NMO_ERR_DIM;
+    int groups = cols / M;
+    for (int r = 0; r < rows; ++r)
+        for (int c = 0; c < cols; ++c) {
+            float w = W[(size_t)r * ldw + c], u = U ? U[(size_t)r * ldw + c] : 0.0f;
+            if (!isfinite(w) || !isfinite(u)) return NMO_ERR_NONFINITE;
+        }
+    for (int r0 = 0; r0 < rows; r0 += rows_per_scale) {
+        int r1 = r0 + rows_per_scale < rows ? r0 + rows_per_scale : rows;
+        float s = 1.0f;
+        if (bits) {
+            float amax = 0.0f;
+            for (int r = r0; r < r1; ++r)
+                for (int c = 0; c < cols; ++c) {
+                    volatile float v = U ? W[(size_t)r * ldw + c] + U[(size_t)r * ldw + c] : W[(size_t)r * ldw + c];
+                    if (fabsf(v) > amax) amax = fabsf(v);
+                }
+            float qmax = (float)((1 << (bits - 1)) - 1);
+            volatile float t = amax / qmax;
+            s = amax == 0.0f ? 1.0f : t;
+        }
+        for (int r = r0; r < r1; ++r) {
+            if (scales && bits) scales[r] = s;
+            for (int g = 0; g < groups; ++g) {
+                float v[8];
+                uint8_t kept[8];
+                for (int c = 0; c < M; ++c) {
+                    size_t at = (size_t)r * ldw + (size_t)g * M + c;
+                    volatile float sum = U ? W[at] + U[at] : W[at];
+                    v[c] = sum;
+                }
+                project_group(v, N, M, kept);
+                float z[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+                for (int j = 0; j < N; ++j) {
+                    int c = kept[j];
+                    if (bits) {
+                        volatile float zq = s * (float)nmo_quantize_one(v[c], s, bits);
+                        z[c] = zq;
+                    } else {
+                        z[c] = v[c];
+                    }
+                }
+                for (int c = 0; c < M; ++c) {
+                    size_t at = (size_t)r * ldz + (size_t)g * M + c;
+                    Z[at] = z[c];
+                    if (U_out) {
+                        volatile float d = v[c] - z[c];
+                        U_out[at] = d;
+                    }
+                }
+            }
+        }
     }
     return NMO_OK;
 }
