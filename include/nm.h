@@ -119,6 +119,35 @@ int nm_gemm(const int8_t *X_dev, int tokens, int K, int ldx, float act_scale,
             int ldo, void *hip_stream);
 
 /*
+ * Training side of the same constraints: the Z-update of the ADMM decomposition (Sec. 3.1),
+ * Z = Pi(W + U), i.e. Eq. 3 applied to W + U, with the quantisation constraint solved after the
+ * sparsity constraint (Sec. 3.3.1: in that order the two projections in sequence are the joint
+ * projection; scale by the largest-parameter rule, "ADMM-Max") and one scale per group of
+ * rows_per_scale consecutive output neurons (Sec. 4: 32 by default), plus the scaled dual update
+ * U <- U + W - Z.  fp32 throughout, one operation per step, in this order:
+ *
+ *   V     = W + U                                   (U_dev NULL: V = W)
+ *   keep  = the N largest |V| of every M consecutive columns; equal magnitudes: the lower column
+ *   bits 0: Z = V on kept positions, +0 elsewhere   (the sparsity constraint alone)
+ *   bits 4 or 8: s = (largest |V| over the rows of the scale group) / (2^(bits-1) - 1), 1 for an
+ *           all-zero group; q = clamp(rne(V / s)) as in nm_compress; Z = s * q on kept
+ *           positions, +0 elsewhere
+ *   U_out = V - Z                                   (when U_out_dev is given)
+ *
+ *   W_dev, U_dev     float [rows][ldw]; U_dev may be NULL.  16-byte aligned, ldw % 4 == 0.
+ *   Z_dev, U_out_dev float [rows][ldz]; U_out_dev may be NULL, and with ldz == ldw it may be U_dev
+ *                    itself (every element is read before it is written, by the same thread);
+ *                    Z_dev must not overlap the inputs.  16-byte aligned, ldz % 4 == 0.
+ *   scales_dev       float[rows], required when bits > 0: receives every row's scale (the rows of
+ *                    one group hold the same value); it also serves as the call's scratch space.
+ *   rows_per_scale   >= 1; the last group may be shorter.
+ * Errors as for nm_compress (bits may also be 0 here).
+ */
+int nm_project(const float *W_dev, const float *U_dev, int rows, int cols, int ldw,
+               int N, int M, int bits, int rows_per_scale,
+               float *Z_dev, float *U_out_dev, int ldz, float *scales_dev, void *hip_stream);
+
+/*
  * The same layer with its output handed on as 8-bit activations (Sec. 5.3: activations are
  * 8-bit integers), i.e. Eq. 4 followed by the scalar quantiser of Sec. 3.3, Eq. 5 (offset 0,
  * 8 bits) with a scale the caller supplies, so that a chain of layers never writes or re-reads a

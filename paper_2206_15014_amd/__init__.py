@@ -12,5 +12,6 @@ from .binding import (  # noqa: F401
     nm_gemm,
     nm_gemm_q8,
     nm_packed_sizes,
+    nm_project,
     nm_status_string,
 )

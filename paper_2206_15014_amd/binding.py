@@ -51,6 +51,8 @@ def _load():
     lib.nm_gemm.restype = c_int
     lib.nm_gemm.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp,
                             c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_int, c_int, c_vp]
+    lib.nm_project.restype = c_int
+    lib.nm_project.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_int, c_vp, c_vp]
     lib.nm_gemm_q8.restype = c_int
     lib.nm_gemm_q8.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp,
                                c_int, c_int, c_int, c_int, c_vp, c_f, c_vp, c_int, c_vp, c_vp]
@@ -156,3 +158,26 @@ def nm_gemm_q8(X, act_scale: float, vals, meta, scales, O: int, N: int, M: int, 
     if rc:
         raise NMError(rc, "nm_gemm_q8")
     return out
+
+
+def nm_project(W, U, N: int, M: int, bits: int, rows_per_scale: int, Z=None, U_out=None, scales=None, stream=None):
+    """W, U (or None): float32 CUDA tensors [rows, cols].  Returns (Z, U_out, scales): the ADMM
+    Z-update Z = Pi(W + U) with both constraints (bits = 0: sparsity only, scales is then None)
+    and the dual update U + W - Z.  Buffers that are not passed are allocated here."""
+    import torch
+    rows, cols = W.shape
+    if Z is None:
+        Z = torch.empty((rows, cols), dtype=torch.float32, device=W.device)
+    if U_out is None:
+        U_out = torch.empty((rows, cols), dtype=torch.float32, device=W.device)
+    if scales is None and bits:
+        scales = torch.empty(rows, dtype=torch.float32, device=W.device)
+    if U is not None and U.stride(0) != W.stride(0):
+        raise ValueError("W and U must share their leading dimension")
+    if U_out.stride(0) != Z.stride(0):
+        raise ValueError("Z and U_out must share their leading dimension")
+    rc = _load().nm_project(_ptr(W), _ptr(U), rows, cols, W.stride(0), N, M, bits, rows_per_scale,
+                            _ptr(Z), _ptr(U_out), Z.stride(0), _ptr(scales), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_project")
+    return Z, U_out, scales

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnm.so")
-SOURCES = ["nm_api.hip", "nm_compress.hip", "nm_gemm.hip", "nm_gemm_dma.hip", "nm_gemm_stream.hip", "nm_gemm_xres.hip"]
+SOURCES = ["nm_api.hip", "nm_compress.hip", "nm_gemm.hip", "nm_gemm_dma.hip", "nm_gemm_stream.hip", "nm_gemm_xres.hip", "nm_project.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

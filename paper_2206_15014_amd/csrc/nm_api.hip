@@ -91,6 +91,21 @@ int nm_gemm(const int8_t* X_dev, int tokens, int K, int ldx, float act_scale,
     return nm::launch_gemm(a, static_cast<hipStream_t>(hip_stream));
 }
 
+int nm_project(const float* W_dev, const float* U_dev, int rows, int cols, int ldw,
+               int N, int M, int bits, int rows_per_scale,
+               float* Z_dev, float* U_out_dev, int ldz, float* scales_dev, void* hip_stream)
+{
+    const int rc = check_pattern(rows, cols, N, M, bits ? bits : 8);
+    if (rc) return rc;
+    if (!W_dev || !Z_dev || (bits && !scales_dev)) return NM_ERR_NULL;
+    if (ldw < cols || ldz < cols || rows_per_scale < 1) return NM_ERR_DIM;
+    if ((uintptr_t)W_dev % 16 || (uintptr_t)U_dev % 16 || (uintptr_t)Z_dev % 16 || (uintptr_t)U_out_dev % 16 ||
+        (uintptr_t)scales_dev % 4 || ldw % 4 || ldz % 4)
+        return NM_ERR_ALIGN;
+    return nm::launch_project(W_dev, U_dev, rows, cols, ldw, N, M, bits, rows_per_scale, Z_dev, U_out_dev, ldz,
+                              scales_dev, static_cast<hipStream_t>(hip_stream));
+}
+
 int nm_gemm_q8(const int8_t* X_dev, int tokens, int K, int ldx, float act_scale,
                const void* vals_dev, const void* meta_dev, const float* scales_dev,
                int O, int N, int M, int bits,

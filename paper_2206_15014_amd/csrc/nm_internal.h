@@ -44,6 +44,8 @@ int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, i
                     void* vals, void* meta, float* scales, hipStream_t st);
 int launch_decompress(const void* vals, const void* meta, int rows, int cols, int N, int M, int bits,
                       int8_t* Wq, hipStream_t st);
+int launch_project(const float* W, const float* U, int rows, int cols, int ldw, int N, int M, int bits,
+                   int rows_per_scale, float* Z, float* U_out, int ldz, float* scales, hipStream_t st);
 int launch_gemm(const GemmArgs& a, hipStream_t st);
 bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg);      // false: not handled, nothing launched
 bool launch_gemm_stream(const GemmArgs& a, hipStream_t st, int cfg);   // same

@@ -1,0 +1,142 @@
+// nm_project: the Z-update of the ADMM decomposition, Z = Pi(W + U) (Sec. 3.1, Eq. 3 applied to
+// W + U), with the quantisation constraint solved after the sparsity constraint (Sec. 3.3.1,
+// ADMM-Max scale per group of output neurons, Sec. 4) and the dual update U + W - Z, on gfx950.
+//
+// Purely HBM-bound: 4 (W) + 4 (U) bytes read and 4 (Z) + 4 (U') bytes written per weight, plus
+// one more read of W and U for the scales.  Three small kernels, no workspace: the per-row scale
+// array the caller passes first receives the rows' largest magnitudes, is then turned in place into
+// the scales of the row groups, and is finally read by the projection proper.  Every arithmetic
+// step is one fp32 operation, in the order the declaration of nm_project states.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nm_internal.h"
+
+namespace nm {
+
+namespace {
+
+__device__ __forceinline__ float wave_max_f(float m)
+{
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+    return m;
+}
+
+// Largest |W + U| of every row (one wavefront per row, four rows per workgroup).
+__global__ void __launch_bounds__(256)
+project_amax_kernel(const float* __restrict__ W, const float* __restrict__ U, int rows, int cols, int ldw,
+                    float* __restrict__ amax)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= rows) return;                   // no barrier below
+    const float4* __restrict__ w4 = reinterpret_cast<const float4*>(W + (size_t)row * ldw);
+    const float4* __restrict__ u4 = U ? reinterpret_cast<const float4*>(U + (size_t)row * ldw) : nullptr;
+    float m = 0.0f;
+    for (int i = lane; i < cols / 4; i += 64) {
+        float4 v = w4[i];
+        if (u4) {
+            const float4 u = u4[i];
+            v.x = __fadd_rn(v.x, u.x); v.y = __fadd_rn(v.y, u.y); v.z = __fadd_rn(v.z, u.z); v.w = __fadd_rn(v.w, u.w);
+        }
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    }
+    m = wave_max_f(m);
+    if (lane == 0) amax[row] = m;
+}
+
+// Row maxima -> scales of the row groups, in place: one wavefront per group of rows_per_scale
+// rows; s = largest magnitude / largest code (Sec. 3.3.1), 1 for an all-zero group.
+__global__ void __launch_bounds__(256)
+project_scale_kernel(float* __restrict__ s, int rows, int rows_per_scale, float qmax)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long r0 = ((long long)blockIdx.x * 4 + wave) * rows_per_scale;
+    if (r0 >= rows) return;
+    const int r1 = (int)((r0 + rows_per_scale < rows) ? r0 + rows_per_scale : rows);
+    float m = 0.0f;
+    for (int r = (int)r0 + lane; r < r1; r += 64) m = fmaxf(m, s[r]);
+    m = wave_max_f(m);
+    const float scale = (m == 0.0f) ? 1.0f : __fdiv_rn(m, qmax);
+    for (int r = (int)r0 + lane; r < r1; r += 64) s[r] = scale;
+}
+
+// One thread per group of M consecutive columns.
+template <int M>
+__global__ void __launch_bounds__(256)
+project_kernel(const float* __restrict__ W, const float* U, int rows, int cols, int ldw,
+               int N, int bits, const float* __restrict__ scales,
+               float* __restrict__ Z, float* U_out, int ldz)     // U_out may be U (same leading dimension): no restrict on the two
+{
+    const int groups = cols / M;
+    const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (long long)rows * groups) return;
+    const int row = (int)(id / groups), g = (int)(id - (long long)row * groups);
+    const size_t in_at = (size_t)row * ldw + (size_t)g * M, out_at = (size_t)row * ldz + (size_t)g * M;
+
+    float v[M];
+#pragma unroll
+    for (int f = 0; f < M / 4; ++f) {
+        float4 x = *reinterpret_cast<const float4*>(W + in_at + 4 * f);
+        if (U) {
+            const float4 u = *reinterpret_cast<const float4*>(U + in_at + 4 * f);
+            x.x = __fadd_rn(x.x, u.x); x.y = __fadd_rn(x.y, u.y); x.z = __fadd_rn(x.z, u.z); x.w = __fadd_rn(x.w, u.w);
+        }
+        v[4 * f + 0] = x.x; v[4 * f + 1] = x.y; v[4 * f + 2] = x.z; v[4 * f + 3] = x.w;
+    }
+    // Eq. 3: an entry is kept when fewer than N entries outrank it; a larger magnitude outranks a
+    // smaller one and, between equal magnitudes, the lower column the higher.
+    float a[M];
+#pragma unroll
+    for (int c = 0; c < M; ++c) a[c] = fabsf(v[c]);
+    const float s = bits ? scales[row] : 1.0f;
+    const float qmax = (float)((1 << (bits ? bits - 1 : 7)) - 1);
+    float z[M];
+#pragma unroll
+    for (int c = 0; c < M; ++c) {
+        int outranked = 0;
+#pragma unroll
+        for (int d = 0; d < M; ++d) {
+            if (d == c) continue;
+            outranked += (d < c) ? (a[d] >= a[c]) : (a[d] > a[c]);
+        }
+        float kept_value = v[c];
+        if (bits) {                            // Eq. 5 (offset 0), then Eq. 4: the value the integer code stands for
+            const int q = (int)fminf(fmaxf(rintf(__fdiv_rn(v[c], s)), -qmax), qmax);   // an integer code: its zero has no sign
+            kept_value = __fmul_rn(s, (float)q);
+        }
+        z[c] = (outranked < N) ? kept_value : 0.0f;
+    }
+#pragma unroll
+    for (int f = 0; f < M / 4; ++f) {
+        *reinterpret_cast<float4*>(Z + out_at + 4 * f) = make_float4(z[4 * f + 0], z[4 * f + 1], z[4 * f + 2], z[4 * f + 3]);
+        if (U_out)
+            *reinterpret_cast<float4*>(U_out + out_at + 4 * f) =
+                make_float4(__fsub_rn(v[4 * f + 0], z[4 * f + 0]), __fsub_rn(v[4 * f + 1], z[4 * f + 1]),
+                            __fsub_rn(v[4 * f + 2], z[4 * f + 2]), __fsub_rn(v[4 * f + 3], z[4 * f + 3]));
+    }
+}
+
+}  // namespace
+
+int launch_project(const float* W, const float* U, int rows, int cols, int ldw, int N, int M, int bits,
+                   int rows_per_scale, float* Z, float* U_out, int ldz, float* scales, hipStream_t st)
+{
+    begin_launch();
+    if (bits) {
+        hipLaunchKernelGGL(project_amax_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, W, U, rows, cols, ldw, scales);
+        const long long n_groups = ((long long)rows + rows_per_scale - 1) / rows_per_scale;
+        hipLaunchKernelGGL(project_scale_kernel, dim3((unsigned)((n_groups + 3) / 4)), dim3(256), 0, st,
+                           scales, rows, rows_per_scale, (float)((1 << (bits - 1)) - 1));
+    }
+    const long long total = (long long)rows * (cols / M);
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (M == 4)
+        hipLaunchKernelGGL(project_kernel<4>, grid, dim3(256), 0, st, W, U, rows, cols, ldw, N, bits, scales, Z, U_out, ldz);
+    else
+        hipLaunchKernelGGL(project_kernel<8>, grid, dim3(256), 0, st, W, U, rows, cols, ldw, N, bits, scales, Z, U_out, ldz);
+    return launch_status();
+}
+
+}  // namespace nm

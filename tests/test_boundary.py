@@ -17,7 +17,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "nm.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", header))
-    assert names >= {"nm_packed_sizes", "nm_compress", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8", "nm_status_string"}
+    assert names >= {"nm_packed_sizes", "nm_compress", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8", "nm_project", "nm_status_string"}
     lib = ctypes.CDLL(binding.library_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -60,6 +60,16 @@ def test_entry_points_validate_before_launch():
     assert g(out=P) == -5                    # output buffer but dtype none
     assert g(acc=None) == -1                 # nothing to write
     assert g(acc=P + 1) == -6
+    pj = lambda **k: lib.nm_project(*[k.get(n, d) for n, d in [
+        ("W", P), ("U", None), ("rows", 8), ("cols", 8), ("ldw", 8), ("N", 2), ("M", 4), ("bits", 8), ("rps", 32),
+        ("Z", P), ("Uo", None), ("ldz", 8), ("sc", P), ("st", None)]])
+    assert pj(W=None) == -1 and pj(Z=None) == -1
+    assert pj(sc=None) == -1                 # scales are required with a quantisation constraint ...
+    assert pj(sc=None, bits=0, W=None) == -1 # ... and not without one (the call gets as far as the next check)
+    assert pj(rps=0) == -2 and pj(ldz=4) == -2 and pj(ldw=4) == -2
+    assert pj(N=4) == -3 and pj(cols=6) == -3
+    assert pj(bits=5) == -4
+    assert pj(W=P + 4) == -6 and pj(Uo=P + 8) == -6 and pj(ldw=10, cols=8) == -6
     q = lambda **k: lib.nm_gemm_q8(*[k.get(n, d) for n, d in [
         ("X", P), ("T", 4), ("K", 8), ("ldx", 8), ("s", 1.0), ("v", P), ("m", P), ("sc", P), ("O", 8), ("N", 2),
         ("M", 4), ("bits", 8), ("bias", None), ("so", 0.5), ("out", P), ("ldo", 8), ("amax", None), ("st", None)]])

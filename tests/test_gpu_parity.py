@@ -468,3 +468,62 @@ def test_gemm_q8_full_size_layer_feeds_the_next_one():
     packed2 = gpu_compress(W2, 2, 4, 8)
     res = run_gemm(q, so, packed2, g_down.O, 2, 4, 8, None, want=("acc",))
     assert np.array_equal(res["acc"], acc2_ref)
+
+
+# ---- ADMM Z-update (nm_project): Z, the dual update and the scales bit-exact ---------------------
+def run_project(W, U, N, M, bits, rps, pad=0, in_place=False):
+    rows, cols = W.shape
+    ld = cols + pad
+    Wd = torch.zeros((rows, ld), dtype=torch.float32, device=DEV)
+    Wd[:, :cols] = torch.from_numpy(W).to(DEV)
+    Ud = None
+    if U is not None:
+        Ud = torch.zeros((rows, ld), dtype=torch.float32, device=DEV)
+        Ud[:, :cols] = torch.from_numpy(U).to(DEV)
+    Z = torch.full((rows, ld), -7.0, dtype=torch.float32, device=DEV)
+    Uo = Ud if in_place else torch.full((rows, ld), -7.0, dtype=torch.float32, device=DEV)
+    Zv, Uov, scales = nm.nm_project(Wd[:, :cols], None if Ud is None else Ud[:, :cols], N, M, bits, rps,
+                                    Z=Z[:, :cols], U_out=Uo[:, :cols])
+    torch.cuda.synchronize()
+    return Z.cpu().numpy(), Uo.cpu().numpy(), None if scales is None else scales.cpu().numpy()
+
+
+@pytest.mark.parametrize("rps", [1, 32, 1000])
+@pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (2, 4, 4), (1, 4, 8), (3, 4, 0), (2, 8, 4), (4, 8, 8), (1, 8, 0), (2, 4, 0)])
+def test_project_matches_oracle(N, M, bits, rps):
+    say("project", N, M, bits, "rows per scale", rps)
+    rng = np.random.default_rng([N, M, bits, rps])
+    for rows, cols, with_u, pad in [(70, 24 * M, True, 0), (257, 96, False, 4), (5, M, True, 8), (768, 768, True, 0)]:
+        W = (rng.standard_normal((rows, cols)) * rng.random((rows, 1)) * 0.05).astype(np.float32)
+        W[rng.integers(0, rows), :] = 0.0                                   # a zero row
+        W[:, : 2 * M] = np.round(W[:, : 2 * M] * 64) / 64                   # ties inside groups
+        U = (rng.standard_normal((rows, cols)) * 0.004).astype(np.float32) if with_u else None
+        Zr, Ur, sr = oracle.admm_project(W, U, N, M, bits, rps)
+        Z, Uo, s = run_project(W, U, N, M, bits, rps, pad=pad)
+        what = "rows %d cols %d" % (rows, cols)
+        assert np.array_equal(Z[:, :cols].view(np.uint32), Zr.view(np.uint32)), what + ": Z differs"   # signed zeros too
+        assert np.array_equal(Uo[:, :cols].view(np.uint32), Ur.view(np.uint32)), what + ": U differs"
+        if pad:
+            assert np.all(Z[:, cols:] == -7.0) and np.all(Uo[:, cols:] == -7.0)
+        if bits:
+            assert np.array_equal(s, sr), what + ": scales differ"
+        else:
+            assert s is None
+
+
+def test_project_dual_update_in_place_and_full_size():
+    """BERT-base FFN-up weights with the paper's default scale groups (32 neurons); U updated in place."""
+    say("project full size")
+    g = [g for g in synth.config2() if g.name == "ffn_up"][0]
+    W = synth.weights(g)
+    rng = np.random.default_rng(9)
+    U = (rng.standard_normal(W.shape) * 0.002).astype(np.float32)
+    Zr, Ur, sr = oracle.admm_project(W, U, 2, 4, 8, 32)
+    Z, Uo, s = run_project(W, U, 2, 4, 8, 32, in_place=True)
+    assert np.array_equal(Z.view(np.uint32), Zr.view(np.uint32))
+    assert np.array_equal(Uo.view(np.uint32), Ur.view(np.uint32))
+    assert np.array_equal(s, sr)
+    # what the projection is for: Z satisfies both constraints
+    assert np.all(np.count_nonzero(Z.reshape(W.shape[0], -1, 4), axis=2) <= 2)
+    codes = Z / s[:, None]
+    assert np.all(np.abs(codes - np.rint(codes)) < 1e-3) and np.abs(np.rint(codes)).max() == 127
