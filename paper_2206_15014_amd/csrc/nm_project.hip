@@ -62,6 +62,36 @@ project_scale_kernel(float* __restrict__ s, int rows, int rows_per_scale, float 
     for (int r = (int)r0 + lane; r < r1; r += 64) s[r] = scale;
 }
 
+// Both of the above in one launch for scale groups of moderate size: one workgroup per group of
+// rows, its four wavefronts sharing the rows, the largest magnitude combined through LDS.
+__global__ void __launch_bounds__(256)
+project_group_scale_kernel(const float* __restrict__ W, const float* __restrict__ U, int rows, int cols, int ldw,
+                           int rows_per_scale, float qmax, float* __restrict__ s)
+{
+    __shared__ float part[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long r0 = (long long)blockIdx.x * rows_per_scale;
+    const int r1 = (int)((r0 + rows_per_scale < rows) ? r0 + rows_per_scale : rows);
+    const int c4 = cols / 4;
+    const long long total = (long long)(r1 - (int)r0) * c4;          // 16-byte pieces of the group
+    float m = 0.0f;
+    for (long long i = threadIdx.x; i < total; i += 256) {
+        const int r = (int)r0 + (int)(i / c4), c = (int)(i % c4);
+        float4 v = reinterpret_cast<const float4*>(W + (size_t)r * ldw)[c];
+        if (U) {
+            const float4 u = reinterpret_cast<const float4*>(U + (size_t)r * ldw)[c];
+            v.x = __fadd_rn(v.x, u.x); v.y = __fadd_rn(v.y, u.y); v.z = __fadd_rn(v.z, u.z); v.w = __fadd_rn(v.w, u.w);
+        }
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    }
+    m = wave_max_f(m);
+    if (lane == 0) part[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+    const float scale = (m == 0.0f) ? 1.0f : __fdiv_rn(m, qmax);
+    for (int r = (int)r0 + threadIdx.x; r < r1; r += 256) s[r] = scale;
+}
+
 // One thread per group of M consecutive columns.
 template <int M>
 __global__ void __launch_bounds__(256)
@@ -125,10 +155,20 @@ int launch_project(const float* W, const float* U, int rows, int cols, int ldw, 
 {
     begin_launch();
     if (bits) {
-        hipLaunchKernelGGL(project_amax_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, W, U, rows, cols, ldw, scales);
+        const float qmax = (float)((1 << (bits - 1)) - 1);
         const long long n_groups = ((long long)rows + rows_per_scale - 1) / rows_per_scale;
-        hipLaunchKernelGGL(project_scale_kernel, dim3((unsigned)((n_groups + 3) / 4)), dim3(256), 0, st,
-                           scales, rows, rows_per_scale, (float)((1 << (bits - 1)) - 1));
+        // A workgroup per scale group reads the group alone: fine while a group is a row or a few
+        // (3072 x 768, one row per scale: 10.4 against 11.7 us); for 32 rows per scale the 96
+        // workgroups that remain are too few to pull the matrix in (20.6 against 14.0 us), so then
+        // row maxima first, all rows at once, and the groups in a second small launch.
+        if (n_groups >= 512 && (long long)rows_per_scale * cols <= 4096) {
+            hipLaunchKernelGGL(project_group_scale_kernel, dim3((unsigned)n_groups), dim3(256), 0, st,
+                               W, U, rows, cols, ldw, rows_per_scale, qmax, scales);
+        } else {
+            hipLaunchKernelGGL(project_amax_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, W, U, rows, cols, ldw, scales);
+            hipLaunchKernelGGL(project_scale_kernel, dim3((unsigned)((n_groups + 3) / 4)), dim3(256), 0, st,
+                               scales, rows, rows_per_scale, qmax);
+        }
     }
     const long long total = (long long)rows * (cols / M);
     const dim3 grid((unsigned)((total + 255) / 256));
