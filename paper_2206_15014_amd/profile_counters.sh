@@ -8,7 +8,7 @@
 # calibrates FETCH_SIZE / WRITE_SIZE against a known number of bytes).
 set -u
 export TMPDIR=/tmp
-OUT=${1:-gpurun_out/counters}
+OUT=${1:-counters_out}
 mkdir -p "$OUT"
 run() {  # name, counters, bench args...
   local name=$1 counters=$2; shift 2
