@@ -108,6 +108,20 @@ def compress(W, N, M, bits):
     return vals, meta, scales
 
 
+def compress_grouped(W, N, M, bits, rows_per_scale):
+    """As compress, with one scale per group of rows_per_scale consecutive rows (scales is still
+    float32 [rows]: every row's scale)."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    rows, cols = W.shape
+    vb, mb, _ = packed_sizes(rows, cols, N, M, bits)
+    vals = np.zeros((rows, vb // rows), dtype=np.uint8)
+    meta = np.zeros((rows, mb // rows), dtype=np.uint8)
+    scales = np.zeros(rows, dtype=np.float32)
+    _check(_load().nmo_compress_grouped(_p(W), rows, cols, cols, N, M, bits, rows_per_scale,
+                                        _p(vals), _p(meta), _p(scales)))
+    return vals, meta, scales
+
+
 def decompress(vals, meta, rows, cols, N, M, bits):
     vals = np.ascontiguousarray(vals, dtype=np.uint8)
     meta = np.ascontiguousarray(meta, dtype=np.uint8)

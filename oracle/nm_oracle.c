@@ -20,6 +20,8 @@
  *   nmo_compress       Sec. 3.3.1 last paragraph: the two constraints solved in
  *                      sequence, sparsity first; Sec. 4: constraining a trained
  *                      matrix directly (no fine-tuning).
+ *   nmo_compress_grouped  the same with one scale per group of rows (Sec. 3.3
+ *                      "group-wise quantization", Sec. 4: 32 neurons per scale).
  *   nmo_gemm_sparse    Sec. 5.3: only the kept products are computed, low-bit
  *                      weights widened to the activation type, int32 sums.
  *   nmo_dequant        Sec. 3.3, Eq. 4 with o = 0: x_d = s * x_q.
@@ -175,6 +177,9 @@ int nmo_quantize_one(float w, float s, int bits)
     return (int)r;
 }
 
+static int nmo_compress_given(const float *W, int rows, int cols, int ldw, int N, int M, int bits,
+                              uint8_t *vals, uint8_t *meta, const float *scales);
+
 static void put_bits(uint8_t *row, size_t bit_offset, int nbits, unsigned value)
 {
     for (int b = 0; b < nbits; ++b) {
@@ -193,9 +198,49 @@ static unsigned get_bits(const uint8_t *row, size_t bit_offset, int nbits)
     return v;
 }
 
-/* project (Eq. 3), then scale and quantise the kept entries (Eq. 5), then pack. */
+/*
+ * project (Eq. 3), then scale and quantise the kept entries (Eq. 5), then pack.
+ * One scale per group of rows_per_scale consecutive rows (Sec. 4: the paper's
+ * default is 32 output neurons per scale; the last group may be shorter): the
+ * largest magnitude over the group's rows / the largest code, 1 for an all-zero
+ * group.  scales[] receives every row's scale.
+ */
+int nmo_compress_grouped(const float *W, int rows, int cols, int ldw, int N, int M, int bits,
+                         int rows_per_scale, uint8_t *vals, uint8_t *meta, float *scales)
+{
+    int rc = check_pattern(rows, cols, N, M, bits);
+    if (rc) return rc;
+    if (!W || !vals || !meta || !scales) return NMO_ERR_NULL;
+    if (ldw < cols || rows_per_scale < 1) return NMO_ERR_DIM;
+    for (int r0 = 0; r0 < rows; r0 += rows_per_scale) {
+        int r1 = r0 + rows_per_scale < rows ? r0 + rows_per_scale : rows;
+        float s = 0.0f;                      /* the largest of the rows' own scales is the group's: */
+        int all_zero = 1;                    /* amax / qmax is monotonic in amax                     */
+        for (int r = r0; r < r1; ++r) {
+            float sr = nmo_row_scale(W + (size_t)r * ldw, cols, bits);
+            int zero_row = 1;
+            for (int c = 0; c < cols; ++c)
+                if (W[(size_t)r * ldw + c] != 0.0f) zero_row = 0;
+            if (!zero_row) {
+                all_zero = 0;
+                if (sr > s) s = sr;
+            }
+        }
+        for (int r = r0; r < r1; ++r) scales[r] = all_zero ? 1.0f : s;
+    }
+    return nmo_compress_given(W, rows, cols, ldw, N, M, bits, vals, meta, scales);
+}
+
+/* The same with one scale per row (the library's default granularity). */
 int nmo_compress(const float *W, int rows, int cols, int ldw, int N, int M, int bits,
                  uint8_t *vals, uint8_t *meta, float *scales)
+{
+    return nmo_compress_grouped(W, rows, cols, ldw, N, M, bits, 1, vals, meta, scales);
+}
+
+/* Projection, quantisation with the scales given per row, packing. */
+static int nmo_compress_given(const float *W, int rows, int cols, int ldw, int N, int M, int bits,
+                              uint8_t *vals, uint8_t *meta, const float *scales)
 {
     int rc = check_pattern(rows, cols, N, M, bits);
     if (rc) return rc;
@@ -222,8 +267,7 @@ int nmo_compress(const float *W, int rows, int cols, int ldw, int N, int M, int 
         }
         memset(vrow, 0, vstride);
         memset(mrow, 0, mstride);
-        float s = nmo_row_scale(w, cols, bits);
-        scales[r] = s;
+        float s = scales[r];
         for (int g = 0; g < groups; ++g) {
             uint8_t kept[8];
             project_group(w + (size_t)g * M, N, M, kept);

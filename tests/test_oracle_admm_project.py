@@ -121,3 +121,35 @@ def test_zero_group_and_errors():
     bad[0, 0] = np.inf
     with pytest.raises(oracle.OracleError):
         oracle.admm_project(bad, None, 2, 4, 8, 1)
+
+
+@pytest.mark.parametrize("N,M,bits,rps", [(2, 4, 8, 32), (2, 4, 4, 5), (1, 4, 8, 70), (2, 8, 4, 32), (4, 8, 8, 2)])
+def test_grouped_compress_is_the_packed_form_of_the_projection(N, M, bits, rps):
+    """One scale per group of rows in the packed format: scales from numpy group maxima, codes
+    that dequantise to exactly the Z of the ADMM projection (bit for bit), and, entry by entry,
+    the quantiser applied with the group's scale at the positions Eq. 3 keeps."""
+    rng = np.random.default_rng([N, M, bits, rps])
+    rows, cols = 70, 12 * M
+    W = (rng.standard_normal((rows, cols)) * rng.random((rows, 1)) * 0.05).astype(np.float32)
+    W[3 * (rps > 1):3 * (rps > 1) + min(rps, 4)] = 0.0       # zero rows; a whole zero group when the group is small
+    vals, meta, scales = oracle.compress_grouped(W, N, M, bits, rps)
+    qmax = np.float32((1 << (bits - 1)) - 1)
+    want = np.zeros(rows, np.float32)
+    for r0 in range(0, rows, rps):
+        m = np.float32(np.abs(W[r0:r0 + rps]).max())
+        want[r0:r0 + rps] = np.float32(1.0) if m == 0 else m / qmax
+    assert np.array_equal(scales, want)
+    codes = oracle.decompress(vals, meta, rows, cols, N, M, bits)
+    Z, _, s2 = oracle.admm_project(W, None, N, M, bits, rps)
+    assert np.array_equal(s2, scales)
+    assert np.array_equal((scales[:, None] * codes.astype(np.float32)).astype(np.float32).view(np.uint32), Z.view(np.uint32))
+    kept = oracle.project(W, N, M)
+    for r in range(0, rows, 7):
+        for g in range(cols // M):
+            for j in range(N):
+                c = g * M + int(kept[r, g, j])
+                assert codes[r, c] == oracle.quantize_one(W[r, c], scales[r], bits)
+    # rows_per_scale = 1 is the library's default granularity
+    v1, m1, s1 = oracle.compress_grouped(W, N, M, bits, 1)
+    v0, m0, s0 = oracle.compress(W, N, M, bits)
+    assert np.array_equal(v1, v0) and np.array_equal(m1, m0) and np.array_equal(s1, s0)
