@@ -82,6 +82,20 @@ int nm_compress(const float *W_dev, int rows, int cols, int ldw,
                 void *hip_stream);
 
 /*
+ * The same with one scale per group of rows_per_scale consecutive output neurons (Sec. 3.3:
+ * group-wise quantisation, parameters of one neuron always sharing a scale; Sec. 4: 32 neurons
+ * per scale is the paper's default): s = (largest |w| over the rows of the group) /
+ * (2^(bits-1)-1), 1 for an all-zero group; the last group may be shorter.  The packed format is
+ * unchanged - scales_dev still receives one float per row, the rows of a group holding the same
+ * value - so nm_gemm and nm_decompress_i8 take the result as it is.  rows_per_scale = 1 is
+ * nm_compress.  scales_dev also serves as the call's scratch space.
+ */
+int nm_compress_grouped(const float *W_dev, int rows, int cols, int ldw,
+                        int N, int M, int bits, int rows_per_scale,
+                        void *vals_dev, void *meta_dev, float *scales_dev,
+                        void *hip_stream);
+
+/*
  * Expand packed weights to the dense integer matrix Wq_dev[rows][cols] (int8,
  * zeros at pruned positions, int4 codes sign-extended).  Inverse of the packing
  * step; used to check that the sparse product equals the dense one.

@@ -46,6 +46,8 @@ def _load():
     lib.nm_packed_sizes.argtypes = [c_int] * 5 + [szp] * 3
     lib.nm_compress.restype = c_int
     lib.nm_compress.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
+    lib.nm_compress_grouped.restype = c_int
+    lib.nm_compress_grouped.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
     lib.nm_decompress_i8.restype = c_int
     lib.nm_decompress_i8.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp]
     lib.nm_gemm.restype = c_int
@@ -114,6 +116,25 @@ def nm_compress(W, N: int, M: int, bits: int, vals=None, meta=None, scales=None,
                              _ptr(vals), _ptr(meta), _ptr(scales), _stream(stream))
     if rc:
         raise NMError(rc, "nm_compress")
+    return vals, meta, scales
+
+
+def nm_compress_grouped(W, N: int, M: int, bits: int, rows_per_scale: int, vals=None, meta=None, scales=None, stream=None):
+    """As nm_compress, with one scale per group of rows_per_scale consecutive rows; scales is
+    still float32 [rows] (the rows of a group hold the same value)."""
+    import torch
+    rows, cols = W.shape
+    vb, mb, _ = nm_packed_sizes(rows, cols, N, M, bits)
+    if vals is None:
+        vals = torch.empty((rows, vb // rows), dtype=torch.uint8, device=W.device)
+    if meta is None:
+        meta = torch.empty((rows, mb // rows), dtype=torch.uint8, device=W.device)
+    if scales is None:
+        scales = torch.empty(rows, dtype=torch.float32, device=W.device)
+    rc = _load().nm_compress_grouped(_ptr(W), rows, cols, W.stride(0), N, M, bits, rows_per_scale,
+                                     _ptr(vals), _ptr(meta), _ptr(scales), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_compress_grouped")
     return vals, meta, scales
 
 

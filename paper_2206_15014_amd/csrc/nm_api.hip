@@ -43,7 +43,19 @@ int nm_compress(const float* W_dev, int rows, int cols, int ldw, int N, int M, i
     if (!W_dev || !vals_dev || !meta_dev || !scales_dev) return NM_ERR_NULL;
     if (ldw < cols) return NM_ERR_DIM;
     if ((uintptr_t)W_dev % 4 || (uintptr_t)scales_dev % 4) return NM_ERR_ALIGN;
-    return nm::launch_compress(W_dev, rows, cols, ldw, N, M, bits, vals_dev, meta_dev, scales_dev,
+    return nm::launch_compress(W_dev, rows, cols, ldw, N, M, bits, 1, vals_dev, meta_dev, scales_dev,
+                               static_cast<hipStream_t>(hip_stream));
+}
+
+int nm_compress_grouped(const float* W_dev, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale,
+                        void* vals_dev, void* meta_dev, float* scales_dev, void* hip_stream)
+{
+    const int rc = check_pattern(rows, cols, N, M, bits);
+    if (rc) return rc;
+    if (!W_dev || !vals_dev || !meta_dev || !scales_dev) return NM_ERR_NULL;
+    if (ldw < cols || rows_per_scale < 1) return NM_ERR_DIM;
+    if ((uintptr_t)W_dev % 4 || (uintptr_t)scales_dev % 4) return NM_ERR_ALIGN;
+    return nm::launch_compress(W_dev, rows, cols, ldw, N, M, bits, rows_per_scale, vals_dev, meta_dev, scales_dev,
                                static_cast<hipStream_t>(hip_stream));
 }
 

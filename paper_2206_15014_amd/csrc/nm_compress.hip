@@ -124,7 +124,7 @@ template <int N, int M, int BITS, int WPR, int RES>
 __global__ void __launch_bounds__(256)
 compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
                      uint32_t* __restrict__ vals, uint32_t* __restrict__ meta, float* __restrict__ scales,
-                     int vstride_dw, int mstride_dw)
+                     int vstride_dw, int mstride_dw, int given)      // given != 0: scales[] holds the rows' scales already
 {
     constexpr int IB = (M == 4) ? 2 : 4;
     constexpr int VB = N * BITS;           // value bits per group
@@ -189,8 +189,8 @@ compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
         for (int k = 1; k < WPR; ++k) amax = fmaxf(amax, part[first + k]);
     }
     // Sec. 3.3.1: largest magnitude over the largest code; an all-zero row keeps scale 1
-    const float s = (amax == 0.0f) ? 1.0f : amax / QMAX;
-    if (live && w == 0 && lane == 0) scales[row] = s;
+    const float s = given ? scales[row] : ((amax == 0.0f) ? 1.0f : amax / QMAX);
+    if (!given && live && w == 0 && lane == 0) scales[row] = s;
 
     uint32_t* __restrict__ vrow = vals + (size_t)row * vstride_dw;
     uint32_t* __restrict__ mrow = meta + (size_t)row * mstride_dw;
@@ -238,7 +238,7 @@ compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
 __global__ void __launch_bounds__(64)
 compress_generic_kernel(const float* __restrict__ W, int rows, int cols, int ldw, int N, int M, int bits,
                         uint8_t* __restrict__ vals, uint8_t* __restrict__ meta, float* __restrict__ scales,
-                        int vstride, int mstride)
+                        int vstride, int mstride, int given)
 {
     const int row = blockIdx.x * 64 + threadIdx.x;
     if (row >= rows) return;
@@ -247,8 +247,8 @@ compress_generic_kernel(const float* __restrict__ W, int rows, int cols, int ldw
     const int qmaxi = (1 << (bits - 1)) - 1;
     float amax = 0.0f;
     for (int c = 0; c < cols; ++c) amax = fmaxf(amax, fabsf(w[c]));
-    const float s = (amax == 0.0f) ? 1.0f : amax / (float)qmaxi;
-    scales[row] = s;
+    const float s = given ? scales[row] : ((amax == 0.0f) ? 1.0f : amax / (float)qmaxi);
+    if (!given) scales[row] = s;
     uint8_t* vrow = vals + (size_t)row * vstride;
     uint8_t* mrow = meta + (size_t)row * mstride;
     uint32_t vacc = 0, macc = 0;
@@ -306,11 +306,11 @@ decompress_kernel(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ 
 
 template <int N, int M, int BITS, int WPR, int RES>
 void launch_wave_res(const float* W, int rows, int cols, int ldw, uint32_t* v, uint32_t* m, float* scales,
-                     int vstride, int mstride, hipStream_t st)
+                     int vstride, int mstride, int given, hipStream_t st)
 {
     constexpr int RPB = 4 / WPR;
     hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, WPR, RES>), dim3((rows + RPB - 1) / RPB), dim3(256), 0, st,
-                       W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4);
+                       W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4, given);
 }
 
 // WPR = wavefronts per row: enough that a wavefront walks at most ~4 passes of 64 groups.  RES =
@@ -319,33 +319,33 @@ void launch_wave_res(const float* W, int rows, int cols, int ldw, uint32_t* v, u
 // nothing); rows too long for the largest size are read twice.
 template <int N, int M, int BITS, int WPR>
 void launch_wave_wpr(const float* W, int rows, int cols, int ldw, uint32_t* v, uint32_t* m, float* scales,
-                     int vstride, int mstride, hipStream_t st)
+                     int vstride, int mstride, int given, hipStream_t st)
 {
     constexpr int MAXRES = 16 / (M / 4);
     const int passes = (cols / M + 63) / 64;
     const int mine = (passes + WPR - 1) / WPR;                 // of wavefront 0, the longest share
-    if (mine <= 1) launch_wave_res<N, M, BITS, WPR, 1>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
-    else if (mine <= 2) launch_wave_res<N, M, BITS, WPR, 2>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
-    else if (mine <= 3) launch_wave_res<N, M, BITS, WPR, 3>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
-    else if (mine <= 4) launch_wave_res<N, M, BITS, WPR, 4>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
-    else launch_wave_res<N, M, BITS, WPR, MAXRES>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
+    if (mine <= 1) launch_wave_res<N, M, BITS, WPR, 1>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
+    else if (mine <= 2) launch_wave_res<N, M, BITS, WPR, 2>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
+    else if (mine <= 3) launch_wave_res<N, M, BITS, WPR, 3>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
+    else if (mine <= 4) launch_wave_res<N, M, BITS, WPR, 4>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
+    else launch_wave_res<N, M, BITS, WPR, MAXRES>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
 }
 
 template <int N, int M, int BITS>
 void launch_wave(const float* W, int rows, int cols, int ldw, void* vals, void* meta, float* scales,
-                 int vstride, int mstride, hipStream_t st)
+                 int vstride, int mstride, int given, hipStream_t st)
 {
     const int passes = (cols / M + 63) / 64;
     uint32_t* v = (uint32_t*)vals;
     uint32_t* m = (uint32_t*)meta;
-    if (passes > 8) launch_wave_wpr<N, M, BITS, 4>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
-    else if (passes > 4) launch_wave_wpr<N, M, BITS, 2>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
-    else launch_wave_wpr<N, M, BITS, 1>(W, rows, cols, ldw, v, m, scales, vstride, mstride, st);
+    if (passes > 8) launch_wave_wpr<N, M, BITS, 4>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
+    else if (passes > 4) launch_wave_wpr<N, M, BITS, 2>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
+    else launch_wave_wpr<N, M, BITS, 1>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
 }
 
 }  // namespace
 
-int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, int bits,
+int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale,
                     void* vals, void* meta, float* scales, hipStream_t st)
 {
     const int ib = (M == 4) ? 2 : 4;
@@ -356,9 +356,13 @@ int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, i
                          ((uintptr_t)meta % 4 == 0) && (kc * bits % 32 == 0) && (kc * ib % 32 == 0);
     bool done = false;
     begin_launch();
+    // One scale per group of rows: the scales are computed first (row maxima, then the groups'),
+    // and the kernels below quantise with what they find in scales[].
+    const int given = rows_per_scale > 1 ? 1 : 0;
+    if (given) launch_group_scales(W, rows, cols, ldw, rows_per_scale, (float)((1 << (bits - 1)) - 1), scales, st);
     if (aligned) {
         done = true;
-#define NM_CASE(n, m, b) else if (N == n && M == m && bits == b) launch_wave<n, m, b>(W, rows, cols, ldw, vals, meta, scales, vstride, mstride, st)
+#define NM_CASE(n, m, b) else if (N == n && M == m && bits == b) launch_wave<n, m, b>(W, rows, cols, ldw, vals, meta, scales, vstride, mstride, given, st)
         if (false) {}
         NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4);
         NM_CASE(1, 8, 8); NM_CASE(2, 8, 8); NM_CASE(4, 8, 8);
@@ -368,7 +372,7 @@ int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, i
     }
     if (!done)
         hipLaunchKernelGGL(compress_generic_kernel, dim3((rows + 63) / 64), dim3(64), 0, st,
-                           W, rows, cols, ldw, N, M, bits, (uint8_t*)vals, (uint8_t*)meta, scales, vstride, mstride);
+                           W, rows, cols, ldw, N, M, bits, (uint8_t*)vals, (uint8_t*)meta, scales, vstride, mstride, given);
     return launch_status();
 }
 

@@ -40,8 +40,10 @@ inline int launch_status()
 }
 
 // Each returns 0 or NM_ERR_HIP (-7).
-int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, int bits,
+int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale,
                     void* vals, void* meta, float* scales, hipStream_t st);
+void launch_group_scales(const float* W, int rows, int cols, int ldw, int rows_per_scale, float qmax, float* scales,
+                         hipStream_t st);
 int launch_decompress(const void* vals, const void* meta, int rows, int cols, int N, int M, int bits,
                       int8_t* Wq, hipStream_t st);
 int launch_project(const float* W, const float* U, int rows, int cols, int ldw, int N, int M, int bits,

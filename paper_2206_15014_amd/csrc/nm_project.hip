@@ -26,11 +26,22 @@ __device__ __forceinline__ float wave_max_f(float m)
 // Largest |W + U| of every row (one wavefront per row, four rows per workgroup).
 __global__ void __launch_bounds__(256)
 project_amax_kernel(const float* __restrict__ W, const float* __restrict__ U, int rows, int cols, int ldw,
-                    float* __restrict__ amax)
+                    float* __restrict__ amax, int vec)         // vec: rows are whole, 16-byte aligned float4s
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int row = blockIdx.x * 4 + wave;
     if (row >= rows) return;                   // no barrier below
+    if (!vec) {                                // any alignment, any width: one float at a time
+        float m = 0.0f;
+        for (int c = lane; c < cols; c += 64) {
+            float v = W[(size_t)row * ldw + c];
+            if (U) v = __fadd_rn(v, U[(size_t)row * ldw + c]);
+            m = fmaxf(m, fabsf(v));
+        }
+        m = wave_max_f(m);
+        if (lane == 0) amax[row] = m;
+        return;
+    }
     const float4* __restrict__ w4 = reinterpret_cast<const float4*>(W + (size_t)row * ldw);
     const float4* __restrict__ u4 = U ? reinterpret_cast<const float4*>(U + (size_t)row * ldw) : nullptr;
     float m = 0.0f;
@@ -150,6 +161,17 @@ project_kernel(const float* __restrict__ W, const float* U, int rows, int cols, 
 
 }  // namespace
 
+// scales[row] <- the scale of the row's group: largest |W| over the group's rows / qmax, 1 for an
+// all-zero group.  Two launches, no workspace (scales[] first holds the rows' maxima).
+void launch_group_scales(const float* W, int rows, int cols, int ldw, int rows_per_scale, float qmax, float* scales,
+                         hipStream_t st)
+{
+    const int vec = ((uintptr_t)W % 16 == 0 && ldw % 4 == 0 && cols % 4 == 0) ? 1 : 0;
+    hipLaunchKernelGGL(project_amax_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, W, (const float*)nullptr, rows, cols, ldw, scales, vec);
+    const long long n_groups = ((long long)rows + rows_per_scale - 1) / rows_per_scale;
+    hipLaunchKernelGGL(project_scale_kernel, dim3((unsigned)((n_groups + 3) / 4)), dim3(256), 0, st, scales, rows, rows_per_scale, qmax);
+}
+
 int launch_project(const float* W, const float* U, int rows, int cols, int ldw, int N, int M, int bits,
                    int rows_per_scale, float* Z, float* U_out, int ldz, float* scales, hipStream_t st)
 {
@@ -165,7 +187,7 @@ int launch_project(const float* W, const float* U, int rows, int cols, int ldw, 
             hipLaunchKernelGGL(project_group_scale_kernel, dim3((unsigned)n_groups), dim3(256), 0, st,
                                W, U, rows, cols, ldw, rows_per_scale, qmax, scales);
         } else {
-            hipLaunchKernelGGL(project_amax_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, W, U, rows, cols, ldw, scales);
+            hipLaunchKernelGGL(project_amax_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, W, U, rows, cols, ldw, scales, 1);
             hipLaunchKernelGGL(project_scale_kernel, dim3((unsigned)((n_groups + 3) / 4)), dim3(256), 0, st,
                                scales, rows, rows_per_scale, qmax);
         }

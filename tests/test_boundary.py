@@ -17,7 +17,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "nm.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", header))
-    assert names >= {"nm_packed_sizes", "nm_compress", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8", "nm_project", "nm_status_string"}
+    assert names >= {"nm_packed_sizes", "nm_compress", "nm_compress_grouped", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8", "nm_project", "nm_status_string"}
     lib = ctypes.CDLL(binding.library_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -45,6 +45,9 @@ def test_entry_points_validate_before_launch():
     assert lib.nm_compress(P, 8, 8, 8, 2, 4, 5, P, P, P, None) == -4
     assert lib.nm_compress(P + 2, 8, 8, 8, 2, 4, 8, P, P, P, None) == -6
     assert lib.nm_decompress_i8(P, None, 8, 8, 2, 4, 8, P, None) == -1
+    assert lib.nm_compress_grouped(P, 8, 8, 8, 2, 4, 8, 0, P, P, P, None) == -2   # rows_per_scale < 1
+    assert lib.nm_compress_grouped(P, 8, 8, 8, 2, 4, 8, 32, P, None, P, None) == -1
+    assert lib.nm_compress_grouped(P, 8, 8, 8, 2, 4, 3, 32, P, P, P, None) == -4
     g = lambda **k: lib.nm_gemm(*[k.get(n, d) for n, d in [
         ("X", P), ("T", 4), ("K", 8), ("ldx", 8), ("s", 1.0), ("v", P), ("m", P), ("sc", P), ("O", 8), ("N", 2),
         ("M", 4), ("bits", 8), ("bias", None), ("acc", P), ("out", None), ("dt", 0), ("ldo", 8), ("st", None)]])

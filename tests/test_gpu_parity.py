@@ -527,3 +527,33 @@ def test_project_dual_update_in_place_and_full_size():
     assert np.all(np.count_nonzero(Z.reshape(W.shape[0], -1, 4), axis=2) <= 2)
     codes = Z / s[:, None]
     assert np.all(np.abs(codes - np.rint(codes)) < 1e-3) and np.abs(np.rint(codes)).max() == 127
+
+
+# ---- one scale per group of rows (nm_compress_grouped): packed bytes and scales bit-exact --------
+@pytest.mark.parametrize("rps", [2, 32, 100])
+@pytest.mark.parametrize("N,M,bits", FAST_SCHEMES + [(3, 4, 8), (4, 8, 4)])
+def test_compress_grouped_matches_oracle_and_feeds_the_gemm(N, M, bits, rps):
+    say("compress grouped", N, M, bits, "rows per scale", rps)
+    rng = np.random.default_rng([N, M, bits, rps, 3])
+    for rows, cols, ldw in [(70, 256, None), (257, 1408, None), (768, 768, 776), (5, 8 * M, None), (33, 40, None)]:
+        if cols % M:
+            continue
+        W = (rng.standard_normal((rows, cols)) * rng.random((rows, 1)) * 0.05).astype(np.float32)
+        W[rng.integers(0, rows)] = 0.0
+        ref = oracle.compress_grouped(W, N, M, bits, rps)
+        Wt = torch.from_numpy(W).to(DEV)
+        if ldw is not None:
+            buf = torch.zeros((rows, ldw), dtype=torch.float32, device=DEV)
+            buf[:, :cols] = Wt
+            Wt = buf[:, :cols]
+        packed = nm.nm_compress_grouped(Wt, N, M, bits, rps)
+        torch.cuda.synchronize()
+        assert_packed_equal(packed, ref, "grouped %dx%d" % (rows, cols))
+    # the packed result is an ordinary operand of nm_gemm
+    T, K, O = 200, 256, 136
+    W, Xq, sx, bias, _, _ = small_case(N, M, bits, T, K, O, 4)
+    ref = oracle.compress_grouped(W, N, M, bits, rps)
+    acc_ref = oracle.gemm_sparse(Xq, ref[0], ref[1], O, N, M, bits)
+    packed = nm.nm_compress_grouped(torch.from_numpy(W).to(DEV), N, M, bits, rps)
+    res = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("acc", "f32"))
+    check_outputs(acc_ref, sx, ref[2], bias, res["acc"], res["f32"], None, what="gemm on grouped scales")
