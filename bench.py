@@ -36,8 +36,10 @@ def parse():
                     help="i8: nm_gemm_q8, the layer output as int8 codes for the next layer (not the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
-    ap.add_argument("--workload", choices=["bert_base", "single", "copy"], default="bert_base",
+    ap.add_argument("--workload", choices=["bert_base", "bert_large", "single", "copy"], default="bert_base",
                     help="bert_base: the four GEMMs of a BERT-base layer at 4096 tokens (the benchmark); "
+                         "bert_large: those of a BERT-large layer at 32x384 = 12288 tokens (the third workload of the "
+                         "task's list; not the headline configuration); "
                          "single: one 768x768 layer at 128 tokens (the skinny shape, for profiling); "
                          "copy: a plain 256 MiB device copy (calibrates the HBM traffic counters)")
     ap.add_argument("--only", default=None,
@@ -80,11 +82,13 @@ def main():
         gemms = [synth.Gemm("single", g1.T, g1.K, g1.O, g1.N, g1.M, g1.bits, (1, 0, 0), outliers=False)]
         workload_name = "single 768x768 linear layer, 128 tokens, 2:4 int8"
     else:
-        gemms = synth.config2()
+        gemms = synth.config3() if args.workload == "bert_large" else synth.config2()
         if args.only is not None:
             gemms = [g for g in gemms if g.name == args.only]
             assert gemms, "--only names no layer of the workload"
-        workload_name = ("BERT-base encoder layer linear set (QKV, attn-out, FFN-up, FFN-down), 2:4 int8, "
+        workload_name = ("BERT-large encoder layer linear set (QKV, attn-out, FFN-up, FFN-down), 2:4 int8, "
+                         "32x384=12288 tokens" if args.workload == "bert_large" else
+                         "BERT-base encoder layer linear set (QKV, attn-out, FFN-up, FFN-down), 2:4 int8, "
                          "32x128=4096 tokens")
     out_code = NM_OUT_BF16 if args.out_dtype == "bf16" else NM_OUT_F32
     out_torch = {"bf16": torch.bfloat16, "f32": torch.float32, "i8": torch.int8}[args.out_dtype]
@@ -239,7 +243,7 @@ def main():
         "config": {"workload": workload_name + "; step = %d x (nm_compress, nm_gemm) layer by layer (bias, %s out), %s launch%s"
                                % (len(gemms), args.out_dtype, args.launch,
                                   " (%d steps per graph)" % steps_per_graph if graph is not None else ""),
-                   "tokens": gemms[0].T, "hidden": 768, "pattern": "2:4", "weight_bits": 8, "out_dtype": args.out_dtype},
+                   "tokens": gemms[0].T, "hidden": min(g.K for g in gemms), "pattern": "2:4", "weight_bits": 8, "out_dtype": args.out_dtype},
         "pct_of_int8_dense_peak": round(100.0 * value / INT8_DENSE_PEAK_TOPS, 2),
         "roofline": {
             "bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_DENSE_PEAK_TOPS, "unit": "TFLOP/s",
