@@ -625,7 +625,16 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
         const int c192 = (a.O + 191) / 192;
         const long long n192 = (long long)((a.tokens + 255) / 256) * c192;
         const bool fits192 = (c192 * 192 - a.O) * 8 <= a.O;      // at most an eighth of the columns computed in vain
-        if (fits192 && n192 >= 176) cfg = 122;                   // wide layers: 256 x 192, a quarter of the LDS fill per MAC
+        if (fits192 && n192 >= 176) {                            // wide layers: 256 x 192, a quarter of the LDS fill per MAC
+            cfg = 122;
+            // ... unless its tiles leave most of a last round empty and 192 x 128 tiles (about 1.5
+            // times the cost per multiply-add) divide evenly: 12288 tokens x 1024 columns is 288
+            // of the former (two rounds, the second an eighth full) or 512 of the latter (two full
+            // rounds): 16.4 against 21.4 us at K = 1024, 57.0 against 63.0 us at K = 4096.
+            const long long n128 = (long long)((a.tokens + 191) / 192) * ((a.O + 127) / 128);
+            const long long cost192 = ((n192 + 255) / 256) * (256 * 192) * 2, cost128 = ((n128 + 255) / 256) * (192 * 128) * 3;
+            if (cost128 * 10 < cost192 * 9) cfg = 128;
+        }
         else if (!U::IDENTITY) cfg = (n96 <= 256 && k256 && a.K >= 1536) ? 113 : 116;   // decode work favours single-slice stages, a long K the fewer requests of 256-column ones
         else if (n96 <= 256 && k256) cfg = 113;                  // one round: deepest ring, 256-column stages
         else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
@@ -637,6 +646,7 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
     if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
     if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
     if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
+    if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(a, st);
     if constexpr (U::IDENTITY) {                                 // further shapes, kept selectable for tuning
         switch (cfg) {
             case 101: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 4, 1>(a, st);

@@ -158,7 +158,7 @@ def test_gemm_mfma_path_small(N, M, bits, tile):
     _gemm_small(N, M, bits, tile)
 
 
-@pytest.mark.parametrize("tile", [str(i) for i in range(4, 18)] + ["101", "105", "109", "112", "113", "115", "116", "117", "119", "121", "122", "201", "202", "203", "204", "205", "206"])
+@pytest.mark.parametrize("tile", [str(i) for i in range(4, 18)] + ["101", "105", "109", "112", "113", "115", "116", "117", "119", "121", "122", "128", "201", "202", "203", "204", "205", "206"])
 def test_gemm_mfma_path_every_tile_shape(tile):
     _gemm_small(2, 4, 8, tile)
 
