@@ -36,10 +36,12 @@ def parse():
                     help="i8: nm_gemm_q8, the layer output as int8 codes for the next layer (not the headline configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
-    ap.add_argument("--workload", choices=["bert_base", "bert_large", "single", "copy"], default="bert_base",
+    ap.add_argument("--workload", choices=["bert_base", "bert_large", "hetero", "single", "copy"], default="bert_base",
                     help="bert_base: the four GEMMs of a BERT-base layer at 4096 tokens (the benchmark); "
                          "bert_large: those of a BERT-large layer at 32x384 = 12288 tokens (the third workload of the "
                          "task's list; not the headline configuration); "
+                         "hetero: the 48 GEMMs of a 12-layer BERT-base encoder with a seeded mix of 2:4 / 1:4 / 2:8 and "
+                         "int8 / int4 schemes at 4096 tokens (the fifth workload of the task's list); "
                          "single: one 768x768 layer at 128 tokens (the skinny shape, for profiling); "
                          "copy: a plain 256 MiB device copy (calibrates the HBM traffic counters)")
     ap.add_argument("--only", default=None,
@@ -81,6 +83,10 @@ def main():
         g1 = synth.config1_tensors()[0]
         gemms = [synth.Gemm("single", g1.T, g1.K, g1.O, g1.N, g1.M, g1.bits, (1, 0, 0), outliers=False)]
         workload_name = "single 768x768 linear layer, 128 tokens, 2:4 int8"
+    elif args.workload == "hetero":
+        gemms = synth.config5()
+        workload_name = ("heterogeneous 12-layer BERT-base encoder, 48 GEMMs, schemes drawn from {2:4 i8, 1:4 i8, 2:4 i4, "
+                         "1:4 i4, 2:8 i4} by a seeded sampler, 32x128=4096 tokens")
     else:
         gemms = synth.config3() if args.workload == "bert_large" else synth.config2()
         if args.only is not None:
@@ -230,6 +236,9 @@ def main():
     value = dense_ops / (ms_per_step * 1e-3) / 1e12
 
     gd = gemms[dom]
+    names = [g.name for g in gemms]
+    if len(set(names)) < len(names):       # several layers: say which layer and scheme
+        names = ["L%02d.%s %d:%d i%d" % (g.seed[1], g.name, g.N, g.M, g.bits) for g in gemms]
     achieved = gd.dense_ops / (dom_us * 1e-6) / 1e12
     comp_bytes = sum(g.O * g.K * 4 + g.O * (g.K // g.M * g.N) * (g.bits + 2) // 8 + g.O * 4 for g in gemms)
     result = {
@@ -243,7 +252,8 @@ def main():
         "config": {"workload": workload_name + "; step = %d x (nm_compress, nm_gemm) layer by layer (bias, %s out), %s launch%s"
                                % (len(gemms), args.out_dtype, args.launch,
                                   " (%d steps per graph)" % steps_per_graph if graph is not None else ""),
-                   "tokens": gemms[0].T, "hidden": min(g.K for g in gemms), "pattern": "2:4", "weight_bits": 8, "out_dtype": args.out_dtype},
+                   "tokens": gemms[0].T, "hidden": min(g.K for g in gemms), "pattern": "/".join(sorted({"%d:%d" % (g.N, g.M) for g in gemms})),
+                   "weight_bits": "/".join(sorted({str(g.bits) for g in gemms})), "out_dtype": args.out_dtype},
         "pct_of_int8_dense_peak": round(100.0 * value / INT8_DENSE_PEAK_TOPS, 2),
         "roofline": {
             "bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_DENSE_PEAK_TOPS, "unit": "TFLOP/s",
@@ -252,15 +262,15 @@ def main():
             "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated on a copy; a stored figure)",
             "algorithmic_bytes": gd.T * gd.K + gd.O * (gd.K // gd.M * gd.N) * (gd.bits + 2) // 8 + 8 * gd.O
                                  + gd.T * gd.O * out_bytes,
-            "kernel": "nm_gemm %s %dx%d->%d" % (gd.name, gd.T, gd.K, gd.O),
+            "kernel": "nm_gemm %s %dx%d->%d %d:%d int%d" % (gd.name, gd.T, gd.K, gd.O, gd.N, gd.M, gd.bits),
             "note": "int8 multiply-add ops, dense-equivalent (zeros counted), against the dense int8 MFMA peak; "
                     "duration = HIP events around 200 back-to-back launches of this kernel (5 replays of a 40-launch graph) after the timed steps",
             "duration_us": round(dom_us, 2),
         },
         "kernels": {
-            "gemm_us_back_to_back": {g.name: round(u, 2) for g, u in zip(gemms, per_gemm_us)},
-            "gemm_dense_equiv_tops": {g.name: round(g.dense_ops / u / 1e6, 1) for g, u in zip(gemms, per_gemm_us)},
-            "compress_us_back_to_back": {g.name: round(u, 2) for g, u in zip(gemms, per_comp_us)},
+            "gemm_us_back_to_back": {n: round(u, 2) for n, u in zip(names, per_gemm_us)},
+            "gemm_dense_equiv_tops": {n: round(g.dense_ops / u / 1e6, 1) for n, g, u in zip(names, gemms, per_gemm_us)},
+            "compress_us_back_to_back": {n: round(u, 2) for n, u in zip(names, per_comp_us)},
             "compress_GBps": round(comp_bytes / (sum(per_comp_us) * 1e-6) / 1e9, 1),
             "compress_frac_of_hbm_peak": round(comp_bytes / (sum(per_comp_us) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
         },
@@ -287,7 +297,7 @@ def main():
     # ---- CPU oracle on a bounded sample of the same workload --------------------------------
     if not args.no_cpu_baseline:
         import oracle
-        n = min(args.cpu_sample_tokens, gemms[0].T)
+        n = min(args.cpu_sample_tokens, gemms[0].T, 4096 if len(gemms) <= 4 else 512)   # 48 GEMMs: a smaller token sample
         ops = 0
         c0 = time.perf_counter()
         for g, W, Xq, sx, b in host:
@@ -299,8 +309,8 @@ def main():
         result["cpu_baseline"] = {
             "value": round(ops / (c1 - c0) / 1e12, 6), "unit": "TOPS (dense-equivalent int8)",
             "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "all four weight matrices compressed in full, GEMM + dequant on the first %d of %d tokens "
-                      "of each layer (%.1f s)" % (n, gemms[0].T, c1 - c0),
+            "sample": "all %d weight matrices compressed in full, GEMM + dequant on the first %d of %d tokens "
+                      "of each layer (%.1f s)" % (len(host), n, gemms[0].T, c1 - c0),
         }
     print(json.dumps(result))
 

@@ -635,8 +635,8 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
             const long long cost192 = ((n192 + 255) / 256) * (256 * 192) * 2, cost128 = ((n128 + 255) / 256) * (192 * 128) * 3;
             if (cost128 * 10 < cost192 * 9) cfg = 128;
         }
-        else if (!U::IDENTITY) cfg = (n96 <= 256 && k256 && a.K >= 1536) ? 113 : 116;   // decode work favours single-slice stages, a long K the fewer requests of 256-column ones
-        else if (n96 <= 256 && k256) cfg = 113;                  // one round: deepest ring, 256-column stages
+        else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
+        else if (n96 <= 256) cfg = (k256 && a.K >= 1536) ? 113 : 115;   // one round: 256-column stages for a long K (fewer, larger requests), else four wavefronts of 64 x 48
         else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
         else cfg = 116;                                          // 128 x 96, two workgroups per CU
     }
@@ -647,11 +647,11 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
     if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
     if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
     if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(a, st);
+    if (cfg == 115) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
     if constexpr (U::IDENTITY) {                                 // further shapes, kept selectable for tuning
         switch (cfg) {
             case 101: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 4, 1>(a, st);
             case 109: return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 6, 1>(a, st);
-            case 115: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
             case 117: return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
             case 121: return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
             default: break;

@@ -177,6 +177,23 @@ def _gemm_small(N, M, bits, tile):
         os.environ.pop("NM_GEMM_TILE", None)
 
 
+@pytest.mark.parametrize("tile", ["105", "115", "122", "128"])
+@pytest.mark.parametrize("N,M,bits", FAST_SCHEMES[1:])
+def test_gemm_decoded_patterns_on_the_large_tiles(N, M, bits, tile):
+    """The patterns that are re-encoded in registers, on the tile shapes the launcher picks for
+    them on wide and on narrow or long layers: several tiles, ragged edges, K of 2 to 12 slices."""
+    say("gemm decoded patterns", N, M, bits, "tile", tile)
+    os.environ["NM_GEMM_TILE"] = tile
+    try:
+        for T, K, O in [(520, 768, 400), (200, 256, 136), (300, 1536, 200)]:
+            W, Xq, sx, bias, ref, acc_ref = small_case(N, M, bits, T, K, O, 3)
+            packed = gpu_compress(W, N, M, bits)
+            res = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("acc", "f32", "bf16"))
+            check_outputs(acc_ref, sx, ref[2], bias, res["acc"], res["f32"], res["bf16"], what="T%d K%d O%d" % (T, K, O))
+    finally:
+        os.environ.pop("NM_GEMM_TILE", None)
+
+
 STREAM_TILES = ["201", "202", "203", "204", "205", "206"]
 
 
