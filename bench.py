@@ -47,8 +47,11 @@ def parse():
     ap.add_argument("--only", default=None,
                     help="restrict the bert_base workload to one layer (qkv, attn_out, ffn_up, ffn_down): used by "
                          "the counter passes, which can tell dispatches apart only by kernel name and grid")
+    ap.add_argument("--compress", choices=["batched", "per_layer"], default="batched",
+                    help="batched: the step compresses all weight matrices with one nm_compress_batch call per scheme and "
+                         "then runs the GEMMs; per_layer: nm_compress and nm_gemm alternate, layer by layer")
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
-                    help="graph: the eight launches of a step are captured once in a HIP graph and replayed")
+                    help="graph: the launches of a step are captured once in a HIP graph and replayed")
     return ap.parse_args()
 
 
@@ -142,10 +145,27 @@ def main():
         if rc != 0:
             raise RuntimeError("libnm call failed: %s" % nm.nm_status_string(rc))
 
+    # one nm_compress_batch call per weight scheme (a single one for the homogeneous layer sets)
+    batches = []
+    for scheme in sorted({(j["g"].N, j["g"].M, j["g"].bits) for j in jobs}):
+        js = [j for j in jobs if (j["g"].N, j["g"].M, j["g"].bits) == scheme]
+        items = binding.compress_items([j["W"] for j in js], [(j["vals"], j["meta"], j["scales"]) for j in js])
+        batches.append((items, len(js)) + scheme)
+
+    def run_step(st):
+        """The launches of one step on stream `st`."""
+        if args.compress == "batched":
+            for b in batches:
+                check(lib.nm_compress_batch(*b, st))
+            for ga in gargs:
+                check(gemm_fn(*(ga[:-1] + (st,))))
+        else:
+            for ca, ga in zip(cargs, gargs):
+                check(lib.nm_compress(*(ca[:-1] + (st,))))
+                check(gemm_fn(*(ga[:-1] + (st,))))
+
     def step():
-        for ca, ga in zip(cargs, gargs):
-            check(lib.nm_compress(*ca))
-            check(gemm_fn(*ga))
+        run_step(stream)
 
     side = torch.cuda.Stream()
 
@@ -193,10 +213,11 @@ def main():
     torch.cuda.synchronize()
     per_gemm_us = [timed_launches(gemm_fn, a, 40) for a in gargs]
     per_comp_us = [timed_launches(lib.nm_compress, a, 40) for a in cargs]
+    batch_comp_us = sum(timed_launches(lib.nm_compress_batch, b + (stream,), 40) for b in batches)
     dom = int(np.argmax(per_gemm_us))
 
     # ---- timed region -----------------------------------------------------------------------
-    # The step's eight launches are short (4-20 us each), so they are captured once into a HIP
+    # The launches of a step are short (4-20 us each), so they are captured once into a HIP
     # graph and the graph is replayed; the eager mode issues them one by one from Python.
     graph = None
     # Several steps per graph (the largest divisor of --steps up to 20), so that the cost of starting
@@ -207,13 +228,9 @@ def main():
         with torch.cuda.stream(side):
             graph = torch.cuda.CUDAGraph()
             cap_stream = side.cuda_stream
-            cg = [a[:-1] + (cap_stream,) for a in cargs]
-            gg = [a[:-1] + (cap_stream,) for a in gargs]
             with torch.cuda.graph(graph, stream=side):
                 for _ in range(steps_per_graph):
-                    for ca, ga in zip(cg, gg):
-                        check(lib.nm_compress(*ca))
-                        check(gemm_fn(*ga))
+                    run_step(cap_stream)
         torch.cuda.current_stream().wait_stream(side)
         for _ in range(3):
             graph.replay()
@@ -249,8 +266,11 @@ def main():
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": workload_name + "; step = %d x (nm_compress, nm_gemm) layer by layer (bias, %s out), %s launch%s"
-                               % (len(gemms), args.out_dtype, args.launch,
+        "config": {"workload": workload_name + "; step = %s (bias, %s out), %s launch%s"
+                               % ("nm_compress_batch over the %d weight matrices (%d call%s), then the %d nm_gemm calls"
+                                  % (len(gemms), len(batches), "" if len(batches) == 1 else "s, one per scheme", len(gemms))
+                                  if args.compress == "batched" else
+                                  "%d x (nm_compress, nm_gemm) layer by layer" % len(gemms), args.out_dtype, args.launch,
                                   " (%d steps per graph)" % steps_per_graph if graph is not None else ""),
                    "tokens": gemms[0].T, "hidden": min(g.K for g in gemms), "pattern": "/".join(sorted({"%d:%d" % (g.N, g.M) for g in gemms})),
                    "weight_bits": "/".join(sorted({str(g.bits) for g in gemms})), "out_dtype": args.out_dtype},
@@ -271,6 +291,8 @@ def main():
             "gemm_us_back_to_back": {n: round(u, 2) for n, u in zip(names, per_gemm_us)},
             "gemm_dense_equiv_tops": {n: round(g.dense_ops / u / 1e6, 1) for n, g, u in zip(names, gemms, per_gemm_us)},
             "compress_us_back_to_back": {n: round(u, 2) for n, u in zip(names, per_comp_us)},
+            "compress_batch_us_back_to_back": round(batch_comp_us, 2),
+            "compress_batch_GBps": round(comp_bytes / (batch_comp_us * 1e-6) / 1e9, 1),
             "compress_GBps": round(comp_bytes / (sum(per_comp_us) * 1e-6) / 1e9, 1),
             "compress_frac_of_hbm_peak": round(comp_bytes / (sum(per_comp_us) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
         },

@@ -96,6 +96,27 @@ int nm_compress_grouped(const float *W_dev, int rows, int cols, int ldw,
                         void *hip_stream);
 
 /*
+ * nm_compress on several matrices of one pattern in one call - the weight matrices of an encoder
+ * layer, say (Sec. 4 compresses every linear layer of the encoder the same way).  Item i gives
+ * exactly what nm_compress(items[i].W_dev, rows, cols, ldw, N, M, bits, vals_dev, meta_dev,
+ * scales_dev) gives, byte for byte; the matrices that meet nm_compress's alignment share launches
+ * (the fixed cost of a launch is several times the time their bytes take), the others go one by
+ * one.  `items` is HOST memory, read during the call and not kept; the device buffers of
+ * different items must not overlap; count <= 0 is an error, as is any item nm_compress would
+ * refuse (then nothing is enqueued).
+ */
+typedef struct nm_compress_item {
+    const float *W_dev;   /* [rows][ldw] float                        */
+    int rows, cols, ldw;
+    void *vals_dev;       /* outputs, sizes from nm_packed_sizes      */
+    void *meta_dev;
+    float *scales_dev;
+} nm_compress_item;
+
+int nm_compress_batch(const nm_compress_item *items, int count,
+                      int N, int M, int bits, void *hip_stream);
+
+/*
  * Expand packed weights to the dense integer matrix Wq_dev[rows][cols] (int8,
  * zeros at pruned positions, int4 codes sign-extended).  Inverse of the packing
  * step; used to check that the sparse product equals the dense one.

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     NMError,
     library_path,
     nm_compress,
+    nm_compress_batch,
     nm_compress_grouped,
     nm_decompress_i8,
     nm_gemm,

@@ -15,6 +15,12 @@ _LIB_PATH = os.path.join(_HERE, "libnm.so")
 
 NM_OUT_NONE, NM_OUT_F32, NM_OUT_BF16 = 0, 1, 2
 
+
+class CompressItem(ctypes.Structure):
+    """nm_compress_item of include/nm.h."""
+    _fields_ = [("W_dev", ctypes.c_void_p), ("rows", ctypes.c_int), ("cols", ctypes.c_int), ("ldw", ctypes.c_int),
+                ("vals_dev", ctypes.c_void_p), ("meta_dev", ctypes.c_void_p), ("scales_dev", ctypes.c_void_p)]
+
 _lib = None
 
 
@@ -49,6 +55,8 @@ def _load():
     lib.nm_compress_grouped.restype = c_int
     lib.nm_compress_grouped.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
     lib.nm_decompress_i8.restype = c_int
+    lib.nm_compress_batch.argtypes = [ctypes.POINTER(CompressItem), c_int, c_int, c_int, c_int, c_vp]
+    lib.nm_compress_batch.restype = c_int
     lib.nm_decompress_i8.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp]
     lib.nm_gemm.restype = c_int
     lib.nm_gemm.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp,
@@ -136,6 +144,36 @@ def nm_compress_grouped(W, N: int, M: int, bits: int, rows_per_scale: int, vals=
     if rc:
         raise NMError(rc, "nm_compress_grouped")
     return vals, meta, scales
+
+
+def compress_items(Ws, outs):
+    """The nm_compress_item array for matrices Ws and their (vals, meta, scales) buffers."""
+    arr = (CompressItem * len(Ws))()
+    for i, (W, (vals, meta, scales)) in enumerate(zip(Ws, outs)):
+        rows, cols = W.shape
+        arr[i] = CompressItem(_ptr(W), rows, cols, W.stride(0), _ptr(vals), _ptr(meta), _ptr(scales))
+    return arr
+
+
+def nm_compress_batch(Ws, N: int, M: int, bits: int, outs=None, stream=None):
+    """nm_compress of every matrix of the list Ws (float32 CUDA tensors [rows, cols]) in one call.
+
+    Returns the list of (vals, meta, scales), one per matrix, as nm_compress would.
+    """
+    import torch
+    if outs is None:
+        outs = []
+        for W in Ws:
+            rows, cols = W.shape
+            vb, mb, _ = nm_packed_sizes(rows, cols, N, M, bits)
+            outs.append((torch.empty((rows, vb // rows), dtype=torch.uint8, device=W.device),
+                         torch.empty((rows, mb // rows), dtype=torch.uint8, device=W.device),
+                         torch.empty(rows, dtype=torch.float32, device=W.device)))
+    arr = compress_items(Ws, outs)
+    rc = _load().nm_compress_batch(arr, len(Ws), N, M, bits, _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_compress_batch")
+    return outs
 
 
 def nm_decompress_i8(vals, meta, rows: int, cols: int, N: int, M: int, bits: int, out=None, stream=None):

@@ -2,6 +2,8 @@
 // Nothing here touches the GPU before the arguments have been accepted.
 #include <hip/hip_runtime.h>
 
+#include <vector>
+
 #include "nm.h"
 #include "nm_internal.h"
 
@@ -57,6 +59,23 @@ int nm_compress_grouped(const float* W_dev, int rows, int cols, int ldw, int N, 
     if ((uintptr_t)W_dev % 4 || (uintptr_t)scales_dev % 4) return NM_ERR_ALIGN;
     return nm::launch_compress(W_dev, rows, cols, ldw, N, M, bits, rows_per_scale, vals_dev, meta_dev, scales_dev,
                                static_cast<hipStream_t>(hip_stream));
+}
+
+int nm_compress_batch(const nm_compress_item* items, int count, int N, int M, int bits, void* hip_stream)
+{
+    if (count <= 0) return NM_ERR_DIM;
+    if (!items) return NM_ERR_NULL;
+    std::vector<nm::CompressItem> v((size_t)count);
+    for (int i = 0; i < count; ++i) {
+        const nm_compress_item& c = items[i];
+        const int rc = check_pattern(c.rows, c.cols, N, M, bits);
+        if (rc) return rc;
+        if (!c.W_dev || !c.vals_dev || !c.meta_dev || !c.scales_dev) return NM_ERR_NULL;
+        if (c.ldw < c.cols) return NM_ERR_DIM;
+        if ((uintptr_t)c.W_dev % 4 || (uintptr_t)c.scales_dev % 4) return NM_ERR_ALIGN;
+        v[(size_t)i] = nm::CompressItem{c.W_dev, c.rows, c.cols, c.ldw, c.vals_dev, c.meta_dev, c.scales_dev};
+    }
+    return nm::launch_compress_batch(v.data(), count, N, M, bits, static_cast<hipStream_t>(hip_stream));
 }
 
 int nm_decompress_i8(const void* vals_dev, const void* meta_dev, int rows, int cols,

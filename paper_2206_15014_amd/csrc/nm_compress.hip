@@ -120,11 +120,14 @@ __device__ __forceinline__ void encode_group(const float (&x)[M], float s, uint3
 // Requires: N*BITS and N*IB in {2,4,8,16,32}, packed row strides that are multiples of 4 bytes,
 // ldw % 4 == 0 and a 16-byte aligned W.
 // ---------------------------------------------------------------------------------------------
-template <int N, int M, int BITS, int WPR, int RES>
-__global__ void __launch_bounds__(256)
-compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
-                     uint32_t* __restrict__ vals, uint32_t* __restrict__ meta, float* __restrict__ scales,
-                     int vstride_dw, int mstride_dw, int given)      // given != 0: scales[] holds the rows' scales already
+// The rows of one workgroup: `block` is the workgroup's index among those of this matrix, WPR
+// (1, 2 or 4) a compile-time constant in the single-matrix kernel and a per-matrix value in the
+// batched one (uniform over the workgroup, so the barrier below is too).
+template <int N, int M, int BITS, int RES>
+__device__ __forceinline__ void
+compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
+              uint32_t* __restrict__ vals, uint32_t* __restrict__ meta, float* __restrict__ scales,
+              int vstride_dw, int mstride_dw, int given, const int WPR, const int block, float* part)
 {
     constexpr int IB = (M == 4) ? 2 : 4;
     constexpr int VB = N * BITS;           // value bits per group
@@ -133,13 +136,11 @@ compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
     constexpr int ML = 32 / MB;            // lanes per index dword
     constexpr int F4 = M / 4;              // 16-byte loads per group
     static_assert(RES * F4 <= 16, "at most 64 floats per lane stay in registers");
-    constexpr int RPB = 4 / WPR;           // rows per workgroup
+    const int RPB = 4 / WPR;               // rows per workgroup
     constexpr float QMAX = (float)((1 << (BITS - 1)) - 1);
 
-    __shared__ float part[4];
-
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int row_raw = blockIdx.x * RPB + wave / WPR;
+    const int row_raw = block * RPB + wave / WPR;
     const bool live = row_raw < rows;      // rows past the end are computed on the last row and not stored
     const int row = live ? row_raw : rows - 1;
     const int w = wave % WPR;
@@ -180,12 +181,11 @@ compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
         }
     }
     amax = wave_max(amax);
-    if constexpr (WPR > 1) {
+    if (WPR > 1) {
         if (lane == 0) part[wave] = amax;
         __syncthreads();
         const int first = (wave / WPR) * WPR;
         amax = part[first];
-#pragma unroll
         for (int k = 1; k < WPR; ++k) amax = fmaxf(amax, part[first + k]);
     }
     // Sec. 3.3.1: largest magnitude over the largest code; an all-zero row keeps scale 1
@@ -230,6 +230,46 @@ compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
             emit(grp, g);
         }
     }
+}
+
+template <int N, int M, int BITS, int WPR, int RES>
+__global__ void __launch_bounds__(256)
+compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
+                     uint32_t* __restrict__ vals, uint32_t* __restrict__ meta, float* __restrict__ scales,
+                     int vstride_dw, int mstride_dw, int given)      // given != 0: scales[] holds the rows' scales already
+{
+    __shared__ float part[4];
+    compress_rows<N, M, BITS, RES>(W, rows, cols, ldw, vals, meta, scales, vstride_dw, mstride_dw, given, WPR, blockIdx.x, part);
+}
+
+// Several matrices of one pattern in one launch: the descriptors travel by value in the kernel
+// arguments (no device table to allocate or copy), each matrix owns a contiguous range of
+// workgroups.  What a launch costs beside its bytes (a few microseconds: start-up, the latency of
+// the first loads, the drain) is then paid once for a layer's weight matrices, not once per matrix.
+constexpr int BATCH_MAX = 16;
+struct BatchItem {
+    const float* W;
+    uint32_t* vals;
+    uint32_t* meta;
+    float* scales;
+    int rows, cols, ldw, vstride_dw, mstride_dw, wpr, first_block, pad;
+};
+struct BatchArgs {
+    BatchItem it[BATCH_MAX];
+    int count;
+};
+
+template <int N, int M, int BITS, int RES>
+__global__ void __launch_bounds__(256)
+compress_batch_kernel(const BatchArgs b)
+{
+    __shared__ float part[4];
+    int i = 0;
+    for (int k = 1; k < b.count; ++k)
+        if ((int)blockIdx.x >= b.it[k].first_block) i = k;     // uniform: scalar loads from the argument segment
+    const BatchItem& t = b.it[i];
+    compress_rows<N, M, BITS, RES>(t.W, t.rows, t.cols, t.ldw, t.vals, t.meta, t.scales, t.vstride_dw, t.mstride_dw, 0,
+                                   t.wpr, (int)blockIdx.x - t.first_block, part);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -373,6 +413,74 @@ int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, i
     if (!done)
         hipLaunchKernelGGL(compress_generic_kernel, dim3((rows + 63) / 64), dim3(64), 0, st,
                            W, rows, cols, ldw, N, M, bits, (uint8_t*)vals, (uint8_t*)meta, scales, vstride, mstride, given);
+    return launch_status();
+}
+
+namespace {
+
+int wave_wpr(int cols, int M)
+{
+    const int passes = (cols / M + 63) / 64;
+    return passes > 8 ? 4 : (passes > 4 ? 2 : 1);
+}
+
+template <int N, int M, int BITS>
+void launch_batch(const BatchArgs& b, int max_mine, int blocks, hipStream_t st)
+{
+    constexpr int MAXRES = 16 / (M / 4);
+    const dim3 grid((unsigned)blocks), wg(256);
+    if (max_mine <= 1) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 1>), grid, wg, 0, st, b);
+    else if (max_mine <= 2) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 2>), grid, wg, 0, st, b);
+    else if (max_mine <= 3) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 3>), grid, wg, 0, st, b);
+    else if (max_mine <= 4) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 4>), grid, wg, 0, st, b);
+    else hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, MAXRES>), grid, wg, 0, st, b);
+}
+
+}  // namespace
+
+// Matrices that the wavefront kernel takes (alignment, whole dwords per packed row) go out in
+// launches of up to BATCH_MAX; the others one by one through launch_compress.
+int launch_compress_batch(const CompressItem* items, int count, int N, int M, int bits, hipStream_t st)
+{
+    const int ib = (M == 4) ? 2 : 4;
+    const bool pattern_ok = (M == 4 && (N == 1 || N == 2)) || (M == 8 && (N == 1 || N == 2 || N == 4));
+    begin_launch();
+    BatchArgs b;
+    b.count = 0;
+    int blocks = 0, max_mine = 0;
+    auto flush = [&]() {
+        if (b.count == 0) return;
+#define NM_CASE(n, m, bt) else if (N == n && M == m && bits == bt) launch_batch<n, m, bt>(b, max_mine, blocks, st)
+        if (false) {}
+        NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4);
+        NM_CASE(1, 8, 8); NM_CASE(2, 8, 8); NM_CASE(4, 8, 8);
+        NM_CASE(1, 8, 4); NM_CASE(2, 8, 4); NM_CASE(4, 8, 4);
+#undef NM_CASE
+        b.count = 0; blocks = 0; max_mine = 0;
+    };
+    for (int i = 0; i < count; ++i) {
+        const CompressItem& c = items[i];
+        const size_t kc = (size_t)c.cols / M * N;
+        const int vstride = (int)((kc * bits + 7) / 8), mstride = (int)((kc * ib + 7) / 8);
+        const bool aligned = ((uintptr_t)c.W % 16 == 0) && (c.ldw % 4 == 0) && ((uintptr_t)c.vals % 4 == 0) &&
+                             ((uintptr_t)c.meta % 4 == 0) && (kc * bits % 32 == 0) && (kc * ib % 32 == 0);
+        if (!pattern_ok || !aligned) {
+            int rc = launch_status();              // of the batches launched so far: the call below starts a bracket of its own
+            if (rc == 0) rc = launch_compress(c.W, c.rows, c.cols, c.ldw, N, M, bits, 1, c.vals, c.meta, c.scales, st);
+            if (rc) return rc;
+            continue;
+        }
+        const int wpr = wave_wpr(c.cols, M);
+        const int passes = (c.cols / M + 63) / 64, mine = (passes + wpr - 1) / wpr, rpb = 4 / wpr;
+        BatchItem& t = b.it[b.count++];
+        t.W = c.W; t.vals = (uint32_t*)c.vals; t.meta = (uint32_t*)c.meta; t.scales = c.scales;
+        t.rows = c.rows; t.cols = c.cols; t.ldw = c.ldw; t.vstride_dw = vstride / 4; t.mstride_dw = mstride / 4;
+        t.wpr = wpr; t.first_block = blocks; t.pad = 0;
+        blocks += (c.rows + rpb - 1) / rpb;
+        max_mine = mine > max_mine ? mine : max_mine;
+        if (b.count == BATCH_MAX) flush();
+    }
+    flush();
     return launch_status();
 }
 

@@ -42,6 +42,14 @@ inline int launch_status()
 // Each returns 0 or NM_ERR_HIP (-7).
 int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale,
                     void* vals, void* meta, float* scales, hipStream_t st);
+struct CompressItem {
+    const float* W;
+    int rows, cols, ldw;
+    void* vals;
+    void* meta;
+    float* scales;
+};
+int launch_compress_batch(const CompressItem* items, int count, int N, int M, int bits, hipStream_t st);
 void launch_group_scales(const float* W, int rows, int cols, int ldw, int rows_per_scale, float qmax, float* scales,
                          hipStream_t st);
 int launch_decompress(const void* vals, const void* meta, int rows, int cols, int N, int M, int bits,

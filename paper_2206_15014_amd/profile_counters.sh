@@ -16,7 +16,7 @@ run() {  # name, counters, bench args...
       > "$OUT/$name.log" 2>&1 || { echo "pass $name failed"; tail -5 "$OUT/$name.log"; return 1; }
   echo "pass $name done"
 }
-B="--steps 20 --warmup 2 --no-cpu-baseline --launch eager"
+B="--steps 20 --warmup 2 --no-cpu-baseline --launch eager --compress per_layer"
 SQ="SQ_WAVES SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_I8 SQ_WAIT_INST_ANY SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE"
 TCC="TCC_REQ_sum TCC_HIT_sum TCC_MISS_sum TCC_EA0_RDREQ_sum"
 for L in qkv attn_out ffn_up ffn_down; do

@@ -17,7 +17,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "nm.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", header))
-    assert names >= {"nm_packed_sizes", "nm_compress", "nm_compress_grouped", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8", "nm_project", "nm_status_string"}
+    assert names >= {"nm_packed_sizes", "nm_compress", "nm_compress_grouped", "nm_compress_batch", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8", "nm_project", "nm_status_string"}
     lib = ctypes.CDLL(binding.library_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -48,6 +48,15 @@ def test_entry_points_validate_before_launch():
     assert lib.nm_compress_grouped(P, 8, 8, 8, 2, 4, 8, 0, P, P, P, None) == -2   # rows_per_scale < 1
     assert lib.nm_compress_grouped(P, 8, 8, 8, 2, 4, 8, 32, P, None, P, None) == -1
     assert lib.nm_compress_grouped(P, 8, 8, 8, 2, 4, 3, 32, P, P, P, None) == -4
+    Item = binding.CompressItem
+    items = (Item * 2)(Item(P, 8, 8, 8, P, P, P), Item(P, 8, 16, 16, P, P, P))
+    assert lib.nm_compress_batch(items, 0, 2, 4, 8, None) == -2               # no items
+    assert lib.nm_compress_batch(None, 2, 2, 4, 8, None) == -1
+    assert lib.nm_compress_batch(items, 2, 2, 4, 7, None) == -4
+    for bad, code in [(Item(None, 8, 8, 8, P, P, P), -1), (Item(P, 8, 8, 8, P, None, P), -1), (Item(P, 8, 8, 4, P, P, P), -2),
+                      (Item(P, 0, 8, 8, P, P, P), -2), (Item(P, 8, 10, 12, P, P, P), -3), (Item(P + 2, 8, 8, 8, P, P, P), -6)]:
+        arr = (Item * 2)(items[0], bad)                                       # a bad item anywhere refuses the whole call
+        assert lib.nm_compress_batch(arr, 2, 2, 4, 8, None) == code
     g = lambda **k: lib.nm_gemm(*[k.get(n, d) for n, d in [
         ("X", P), ("T", 4), ("K", 8), ("ldx", 8), ("s", 1.0), ("v", P), ("m", P), ("sc", P), ("O", 8), ("N", 2),
         ("M", 4), ("bits", 8), ("bias", None), ("acc", P), ("out", None), ("dt", 0), ("ldo", 8), ("st", None)]])

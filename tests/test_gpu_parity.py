@@ -574,3 +574,44 @@ def test_compress_grouped_matches_oracle_and_feeds_the_gemm(N, M, bits, rps):
     packed = nm.nm_compress_grouped(torch.from_numpy(W).to(DEV), N, M, bits, rps)
     res = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("acc", "f32"))
     check_outputs(acc_ref, sx, ref[2], bias, res["acc"], res["f32"], None, what="gemm on grouped scales")
+
+
+# ---- several matrices in one call (nm_compress_batch): byte for byte what nm_compress gives -----
+@pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (1, 4, 4), (2, 8, 4), (4, 8, 8), (3, 4, 8)])
+def test_compress_batch_matches_oracle_item_by_item(N, M, bits):
+    """Matrices of different heights and widths in one call: one, two and four wavefronts per row
+    (widths up to 3072), a height that is not a multiple of the rows per workgroup, a padded
+    leading dimension, a matrix whose packed rows are not whole dwords (goes out on its own), more
+    matrices than one launch takes (17 of them follow), and 3:4, which no wavefront kernel covers."""
+    say("compress batch", N, M, bits)
+    rng = np.random.default_rng([N, M, bits, 77])
+    shapes = [(37, 768, 768), (5, 3072, 3072), (130, 1536, 1600), (9, 5 * M, 5 * M), (64, 256, 256)] + [(3 + i, 128, 128) for i in range(17)]
+    Ws, dev = [], []
+    for rows, cols, ldw in shapes:
+        W = (rng.standard_normal((rows, cols)) * 0.02).astype(np.float32)
+        W[rows // 2, :] = 0.0                                  # an all-zero row: scale 1
+        buf = torch.zeros((rows, ldw), dtype=torch.float32, device=DEV)
+        buf[:, :cols] = torch.from_numpy(W).to(DEV)
+        Ws.append(W)
+        dev.append(buf[:, :cols])
+    outs = nm.nm_compress_batch(dev, N, M, bits)
+    torch.cuda.synchronize()
+    for W, packed, shape in zip(Ws, outs, shapes):
+        assert_packed_equal(packed, oracle.compress(W, N, M, bits), "batch item %s" % (shape,))
+
+
+def test_compress_batch_full_size_layer_set_feeds_the_gemm():
+    gs = synth.config2()
+    Ws = [synth.weights(g) for g in gs]
+    outs = nm.nm_compress_batch([torch.from_numpy(W).to(DEV) for W in Ws], 2, 4, 8)
+    torch.cuda.synchronize()
+    for g, W, packed in zip(gs, Ws, outs):
+        ref = oracle.compress(W, g.N, g.M, g.bits)
+        assert_packed_equal(packed, ref, "batch " + g.name)
+    g, W, packed = gs[1], Ws[1], outs[1]
+    Xq, sx = synth.activations(g)
+    rows = sampled_tokens(g.T, n=16, seed=5)
+    ref = oracle.compress(W, g.N, g.M, g.bits)
+    acc_ref = oracle.gemm_sparse(Xq[rows], ref[0], ref[1], g.O, g.N, g.M, g.bits)
+    acc = run_gemm(Xq, sx, packed, g.O, g.N, g.M, g.bits, None, want=("acc",))["acc"]
+    assert np.array_equal(acc[rows], acc_ref)
