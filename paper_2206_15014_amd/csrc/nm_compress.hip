@@ -49,12 +49,37 @@ __device__ __forceinline__ uint32_t group_or(uint32_t v)
     return v;
 }
 
-// Eq. 5 with offset 0: true fp32 division, round half to even, symmetric clamp.
-template <int BITS>
-__device__ __forceinline__ int quantize(float w, float s)
+// The correctly rounded fp32 quotient w / s for many w and one s.  RECIP = false: the division
+// operator.  RECIP = true: the same value from y = RN(1 / s), computed once per row: q0 = RN(w y)
+// is within 1.5 ulp of w / s (y and the product each carry half an ulp of their own); one
+// residual step, q1 = RN(q0 + RN(w - s q0) y), lands within half an ulp plus a 2^-24th of an ulp,
+// i.e. on one of the two neighbours of w / s; and for such a q1 the residual w - s q1 is exact in
+// one fused multiply-add and q2 = RN(q1 + (w - s q1) y) is RN(w / s) itself when y is the
+// correctly rounded reciprocal (Markstein's theorem on fused-multiply-add division) - five
+// operations in place of the eleven of the division sequence.  Valid without overflow, underflow
+// or subnormal y; the caller takes this route only for 2^-60 <= s <= 2^60, where |w| <= 127 s
+// keeps every intermediate normal or, for quotients far below one half, irrelevant to the code.
+template <bool RECIP>
+struct Divisor {
+    float s, y;
+    __device__ __forceinline__ float quotient(float w) const
+    {
+        if constexpr (RECIP) {
+            const float q0 = __fmul_rn(w, y);
+            const float q1 = __fmaf_rn(__fmaf_rn(-s, q0, w), y, q0);
+            return __fmaf_rn(__fmaf_rn(-s, q1, w), y, q1);
+        } else {
+            return __fdiv_rn(w, s);
+        }
+    }
+};
+
+// Eq. 5 with offset 0: correctly rounded fp32 quotient, round half to even, symmetric clamp.
+template <int BITS, bool RECIP>
+__device__ __forceinline__ int quantize(float w, const Divisor<RECIP>& d)
 {
     constexpr float QMAX = (float)((1 << (BITS - 1)) - 1);
-    float r = rintf(w / s);
+    float r = rintf(d.quotient(w));
     r = fminf(fmaxf(r, -QMAX), QMAX);
     return (int)r;
 }
@@ -85,10 +110,39 @@ __device__ __forceinline__ uint32_t keep_mask(const float (&x)[M])
 // One group -> its value bits (N codes of BITS bits, ascending columns) and index bits.  Kept
 // column c goes to slot (number of kept columns below c); every register is addressed with a
 // compile-time index so the group never leaves the register file.
-template <int N, int M, int BITS>
-__device__ __forceinline__ void encode_group(const float (&x)[M], float s, uint32_t& vbits, uint32_t& mbits)
+template <int N, int M, int BITS, bool RECIP>
+__device__ __forceinline__ void encode_group(const float (&x)[M], const Divisor<RECIP>& s, uint32_t& vbits, uint32_t& mbits)
 {
     constexpr int IB = (M == 4) ? 2 : 4;
+    if constexpr (M == 4 && (N == 1 || N == 2)) {
+        // Groups of four, the same rule spelled out: the six comparisons "the lower column is at
+        // least as large" decide every pair (the lower column outranks on >=, the higher one
+        // otherwise), and with exactly N columns kept the slots follow from the keep flags alone.
+        // The flags are wavefront masks combined on the scalar unit; the vector ALU only compares
+        // and selects.
+        const float a0 = fabsf(x[0]), a1 = fabsf(x[1]), a2 = fabsf(x[2]), a3 = fabsf(x[3]);
+        const bool c01 = a0 >= a1, c02 = a0 >= a2, c03 = a0 >= a3, c12 = a1 >= a2, c13 = a1 >= a3, c23 = a2 >= a3;
+        if constexpr (N == 2) {
+            auto under_two = [](bool p, bool q, bool r) { return !((p && q) || (p && r) || (q && r)); };
+            const bool k0 = under_two(!c01, !c02, !c03);       // outranked by fewer than two
+            const bool k1 = under_two(c01, !c12, !c13);
+            const bool k2 = under_two(c02, c12, !c23);
+            const bool k3 = under_two(c03, c13, c23);
+            const float lo = k0 ? x[0] : (k1 ? x[1] : x[2]);   // lowest kept column: 0, else 1, else 2
+            const uint32_t clo = k0 ? 0u : (k1 ? 1u : 2u);
+            const float hi = k3 ? x[3] : (k2 ? x[2] : x[1]);   // highest kept column: 3, else 2, else 1
+            const uint32_t chi = k3 ? 3u : (k2 ? 2u : 1u);
+            const int q0 = quantize<BITS>(lo, s), q1 = quantize<BITS>(hi, s);
+            vbits = ((uint32_t)q0 & ((1u << BITS) - 1u)) | (((uint32_t)q1 & ((1u << BITS) - 1u)) << BITS);
+            mbits = clo | (chi << IB);
+        } else {
+            const bool k0 = c01 && c02 && c03, k1 = !c01 && c12 && c13, k2 = !c02 && !c12 && c23;   // outranked by none
+            const float v = k0 ? x[0] : (k1 ? x[1] : (k2 ? x[2] : x[3]));
+            mbits = k0 ? 0u : (k1 ? 1u : (k2 ? 2u : 3u));
+            vbits = (uint32_t)quantize<BITS>(v, s) & ((1u << BITS) - 1u);
+        }
+        return;
+    }
     const uint32_t mask = keep_mask<N, M>(x);
     vbits = 0;
     mbits = 0;
@@ -140,10 +194,12 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
     constexpr float QMAX = (float)((1 << (BITS - 1)) - 1);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int row_raw = block * RPB + wave / WPR;
+    // the row and the wavefront's place in it are the same in all lanes: said so explicitly, the row's
+    // base addresses stay in scalar registers and every access is base + 32-bit lane offset
+    const int row_raw = __builtin_amdgcn_readfirstlane(block * RPB + wave / WPR);
     const bool live = row_raw < rows;      // rows past the end are computed on the last row and not stored
     const int row = live ? row_raw : rows - 1;
-    const int w = wave % WPR;
+    const int w = __builtin_amdgcn_readfirstlane(wave % WPR);
 
     const float4* __restrict__ w4 = reinterpret_cast<const float4*>(W + (size_t)row * ldw);
     const int groups = cols / M;
@@ -161,7 +217,7 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
             const int g = (w + i * WPR) * 64 + lane;
             if (i < mine && g < groups) {
 #pragma unroll
-                for (int f = 0; f < F4; ++f) x[i * F4 + f] = w4[(size_t)g * F4 + f];
+                for (int f = 0; f < F4; ++f) x[i * F4 + f] = w4[(unsigned)(g * F4 + f)];
             }
         }
 #pragma unroll
@@ -175,7 +231,7 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
             if (g < groups)
 #pragma unroll
                 for (int f = 0; f < F4; ++f) {
-                    float4 v = w4[(size_t)g * F4 + f];
+                    float4 v = w4[(unsigned)(g * F4 + f)];
                     amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
                 }
         }
@@ -189,47 +245,54 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
         for (int k = 1; k < WPR; ++k) amax = fmaxf(amax, part[first + k]);
     }
     // Sec. 3.3.1: largest magnitude over the largest code; an all-zero row keeps scale 1
-    const float s = given ? scales[row] : ((amax == 0.0f) ? 1.0f : amax / QMAX);
+    // (the same value in every lane of the row's wavefronts: kept in a scalar register)
+    const float s = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane(
+        (int)__float_as_uint(given ? scales[row] : ((amax == 0.0f) ? 1.0f : amax / QMAX))));
     if (!given && live && w == 0 && lane == 0) scales[row] = s;
 
     uint32_t* __restrict__ vrow = vals + (size_t)row * vstride_dw;
     uint32_t* __restrict__ mrow = meta + (size_t)row * mstride_dw;
 
-    auto emit = [&](const float (&grp)[M], int g) {
-        uint32_t vb = 0, mb = 0;
-        if (g < groups) encode_group<N, M, BITS>(grp, s, vb, mb);
-        vb = group_or<VL>(vb << ((lane % VL) * VB));
-        mb = group_or<ML>(mb << ((lane % ML) * MB));
-        if (live && g < groups && lane % VL == 0) vrow[g / VL] = vb;
-        if (live && g < groups && lane % ML == 0) mrow[g / ML] = mb;
-    };
-
-    if (resident) {
+    auto encode_row = [&](auto divisor) __attribute__((always_inline)) {
+        auto emit = [&](const float (&grp)[M], int g) __attribute__((always_inline)) {
+            uint32_t vb = 0, mb = 0;
+            if (g < groups) encode_group<N, M, BITS>(grp, divisor, vb, mb);
+            vb = group_or<VL>(vb << ((lane % VL) * VB));
+            mb = group_or<ML>(mb << ((lane % ML) * MB));
+            if (live && g < groups && lane % VL == 0) vrow[(unsigned)g / VL] = vb;
+            if (live && g < groups && lane % ML == 0) mrow[(unsigned)g / ML] = mb;
+        };
+        if (resident) {
 #pragma unroll
-        for (int i = 0; i < RES; ++i) {
-            if (i < mine) {
+            for (int i = 0; i < RES; ++i) {
+                if (i < mine) {
+                    float grp[M];
+#pragma unroll
+                    for (int f = 0; f < F4; ++f) {
+                        const float4 v = x[i * F4 + f];
+                        grp[4 * f + 0] = v.x; grp[4 * f + 1] = v.y; grp[4 * f + 2] = v.z; grp[4 * f + 3] = v.w;
+                    }
+                    emit(grp, (w + i * WPR) * 64 + lane);
+                }
+            }
+        } else {
+            for (int i = 0; i < mine; ++i) {
+                const int g = (w + i * WPR) * 64 + lane;
                 float grp[M];
 #pragma unroll
                 for (int f = 0; f < F4; ++f) {
-                    const float4 v = x[i * F4 + f];
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (g < groups) v = w4[(unsigned)(g * F4 + f)];
                     grp[4 * f + 0] = v.x; grp[4 * f + 1] = v.y; grp[4 * f + 2] = v.z; grp[4 * f + 3] = v.w;
                 }
-                emit(grp, (w + i * WPR) * 64 + lane);
+                emit(grp, g);
             }
         }
-    } else {
-        for (int i = 0; i < mine; ++i) {
-            const int g = (w + i * WPR) * 64 + lane;
-            float grp[M];
-#pragma unroll
-            for (int f = 0; f < F4; ++f) {
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (g < groups) v = w4[(size_t)g * F4 + f];
-                grp[4 * f + 0] = v.x; grp[4 * f + 1] = v.y; grp[4 * f + 2] = v.z; grp[4 * f + 3] = v.w;
-            }
-            emit(grp, g);
-        }
-    }
+    };
+    // One division per row (the reciprocal) instead of one per kept weight wherever the scale is
+    // in the range for which that route is exact; any other scale takes the division operator.
+    if (s >= 0x1p-60f && s <= 0x1p60f) encode_row(Divisor<true>{s, __fdiv_rn(1.0f, s)});
+    else encode_row(Divisor<false>{s, 0.0f});
 }
 
 template <int N, int M, int BITS, int WPR, int RES>

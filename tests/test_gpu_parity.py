@@ -615,3 +615,30 @@ def test_compress_batch_full_size_layer_set_feeds_the_gemm():
     acc_ref = oracle.gemm_sparse(Xq[rows], ref[0], ref[1], g.O, g.N, g.M, g.bits)
     acc = run_gemm(Xq, sx, packed, g.O, g.N, g.M, g.bits, None, want=("acc",))["acc"]
     assert np.array_equal(acc[rows], acc_ref)
+
+
+@pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (2, 4, 4), (1, 4, 8), (2, 8, 4)])
+def test_compress_quotients_next_to_half_way_points(N, M, bits):
+    """Weights placed on and a few units in the last place around (k + 1/2) * scale, for scales
+    with arbitrary significands (all ones and all zeros among them) over the exponent range,
+    including scales outside the range in which the kernel divides by way of the reciprocal: the
+    codes hinge on the correctly rounded quotient, which the oracle takes from the division operator."""
+    say("compress half-way quotients", N, M, bits)
+    rng = np.random.default_rng([N, M, bits, 5])
+    qmax = (1 << (bits - 1)) - 1
+    rows, cols = 96, 64 * M
+    W = np.zeros((rows, cols), np.float32)
+    for r in range(rows):
+        mant = [0, (1 << 23) - 1, 1, (1 << 23) - 2][r % 8] if r % 8 < 4 else int(rng.integers(0, 1 << 23))
+        expo = 127 + [-70, -61, -60, -30, -8, 0, 9, 31, 59, 60, 61, 70][r % 12]
+        amax = np.array([(expo << 23) | mant], np.uint32).view(np.float32)[0]
+        scale = np.float32(amax) / np.float32(qmax)                      # what the row's scale will be
+        k = rng.integers(-qmax, qmax, cols).astype(np.float64) + 0.5
+        w = (k * np.float64(scale)).astype(np.float32)
+        w = (w.view(np.int32) + rng.integers(-2, 3, cols).astype(np.int32)).view(np.float32)
+        w = np.clip(w, -amax, amax)
+        w[int(rng.integers(0, cols))] = amax
+        W[r] = w
+    assert np.isfinite(W).all()
+    packed = gpu_compress(W, N, M, bits)
+    assert_packed_equal(packed, oracle.compress(W, N, M, bits), "half-way quotients")
