@@ -44,6 +44,9 @@ def parse():
                          "int8 / int4 schemes at 4096 tokens (the fifth workload of the task's list); "
                          "single: one 768x768 layer at 128 tokens (the skinny shape, for profiling); "
                          "copy: a plain 256 MiB device copy (calibrates the HBM traffic counters)")
+    ap.add_argument("--tokens", type=int, default=None,
+                    help="token count for the bert_base / bert_large layer sets instead of the workload's own (batch x "
+                         "sequence length of the paper's inference table, e.g. 128 x 384 = 49152): a sweep, not the benchmark")
     ap.add_argument("--only", default=None,
                     help="restrict the bert_base workload to one layer (qkv, attn_out, ffn_up, ffn_down): used by "
                          "the counter passes, which can tell dispatches apart only by kernel name and grid")
@@ -92,6 +95,10 @@ def main():
                          "1:4 i4, 2:8 i4} by a seeded sampler, 32x128=4096 tokens, activation and output buffers shared between layers")
     else:
         gemms = synth.config3() if args.workload == "bert_large" else synth.config2()
+        if args.tokens is not None:
+            import dataclasses
+            assert args.tokens > 0
+            gemms = [dataclasses.replace(g, T=args.tokens) for g in gemms]
         if args.only is not None:
             gemms = [g for g in gemms if g.name == args.only]
             assert gemms, "--only names no layer of the workload"
@@ -99,6 +106,8 @@ def main():
                          "32x384=12288 tokens" if args.workload == "bert_large" else
                          "BERT-base encoder layer linear set (QKV, attn-out, FFN-up, FFN-down), 2:4 int8, "
                          "32x128=4096 tokens")
+        if args.tokens is not None:
+            workload_name = workload_name[:workload_name.rindex(",") + 1] + " %d tokens" % args.tokens
     out_code = NM_OUT_BF16 if args.out_dtype == "bf16" else NM_OUT_F32
     out_torch = {"bf16": torch.bfloat16, "f32": torch.float32, "i8": torch.int8}[args.out_dtype]
     out_bytes = {"bf16": 2, "f32": 4, "i8": 1}[args.out_dtype]
