@@ -621,20 +621,30 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
     constexpr bool PAIR = (4 * U::VBYTES) == 8 || (4 * U::MBYTES) == 8;
     if (PAIR && !k256) return false;
     if (cfg == 0) {
-        const long long n96 = (long long)((a.tokens + 127) / 128) * ((a.O + 95) / 96);
-        const int c192 = (a.O + 191) / 192;
-        const long long n192 = (long long)((a.tokens + 255) / 256) * c192;
-        const bool fits192 = (c192 * 192 - a.O) * 8 <= a.O;      // at most an eighth of the columns computed in vain
-        if (fits192 && n192 >= 176) {                            // wide layers: 256 x 192, a quarter of the LDS fill per MAC
-            cfg = 122;
-            // ... unless its tiles leave most of a last round empty and 192 x 128 tiles (about 1.5
-            // times the cost per multiply-add) divide evenly: 12288 tokens x 1024 columns is 288
-            // of the former (two rounds, the second an eighth full) or 512 of the latter (two full
-            // rounds): 16.4 against 21.4 us at K = 1024, 57.0 against 63.0 us at K = 4096.
-            const long long n128 = (long long)((a.tokens + 191) / 192) * ((a.O + 127) / 128);
-            const long long cost192 = ((n192 + 255) / 256) * (256 * 192) * 2, cost128 = ((n128 + 255) / 256) * (192 * 128) * 3;
-            if (cost128 * 10 < cost192 * 9) cfg = 128;
+        // Cost of a tile shape = rounds over the 256 CUs x tile area x the shape's cost per
+        // multiply-add relative to 256 x 192 (the L2->LDS fill per multiply-add, measured: 256 x 128
+        // 1.35, 192 x 128 1.5, 128 x 128 1.66, 128 x 96 1.45 with its two workgroups per CU).  A
+        // shape whose last column tile would compute more than an eighth of the columns in vain is
+        // out; a later shape must beat an earlier one by 5 %.  BERT-base at 4096 tokens: 256 x 192
+        // for QKV and FFN-up (192 and 256 tiles), 128 x 96 for the 768-wide outputs (256 tiles);
+        // BERT-large at 12288 tokens: 256 x 192 for the wide layers, 192 x 128 for the 1024-wide
+        // ones (512 tiles, two full rounds, against 288 of 256 x 192: 16.4 against 21.4 us at
+        // K = 1024, 57.0 against 63.0 us at K = 4096); at 4096 tokens 128 x 128 for them (256 tiles:
+        // 8.3 against 9.4 us, 23.7 against 26.4 us) and 256 x 128 for FFN-up (512 tiles: 20.2 against 22.4 us).
+        struct Shape { int cfg, bt, bo, cost; };
+        static const Shape shapes[] = {{122, 256, 192, 100}, {121, 256, 128, 135}, {128, 192, 128, 150}, {117, 128, 128, 166}, {0, 128, 96, 145}};
+        long long best = -1;
+        int pick = 0;
+        for (const Shape& sh : shapes) {
+            const long long ct = (a.O + sh.bo - 1) / sh.bo;
+            if (sh.cfg != 0 && (ct * sh.bo - a.O) * 8 > a.O) continue;
+            if (sh.cfg == 121 && a.K > 2048) continue;           // its K loop is no faster per step than that of 256 x 192: only pays while the fixed cost of a tile dominates
+            const long long n = (long long)((a.tokens + sh.bt - 1) / sh.bt) * ct;
+            const long long c = ((n + 255) / 256) * sh.bt * sh.bo * sh.cost;
+            if (best < 0 || c * 105 < best * 100) { best = c; pick = sh.cfg; }
         }
+        const long long n96 = (long long)((a.tokens + 127) / 128) * ((a.O + 95) / 96);
+        if (pick != 0) cfg = pick;
         else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
         else if (n96 <= 256) cfg = (k256 && a.K >= 1536) ? 113 : 115;   // one round: 256-column stages for a long K (fewer, larger requests), else four wavefronts of 64 x 48
         else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
@@ -648,12 +658,12 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
     if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
     if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(a, st);
     if (cfg == 115) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
+    if (cfg == 117) return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
+    if (cfg == 121) return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
     if constexpr (U::IDENTITY) {                                 // further shapes, kept selectable for tuning
         switch (cfg) {
             case 101: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 4, 1>(a, st);
             case 109: return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 6, 1>(a, st);
-            case 117: return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
-            case 121: return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
             default: break;
         }
     }

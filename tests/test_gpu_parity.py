@@ -177,7 +177,7 @@ def _gemm_small(N, M, bits, tile):
         os.environ.pop("NM_GEMM_TILE", None)
 
 
-@pytest.mark.parametrize("tile", ["105", "115", "122", "128"])
+@pytest.mark.parametrize("tile", ["105", "115", "117", "121", "122", "128"])
 @pytest.mark.parametrize("N,M,bits", FAST_SCHEMES[1:])
 def test_gemm_decoded_patterns_on_the_large_tiles(N, M, bits, tile):
     """The patterns that are re-encoded in registers, on the tile shapes the launcher picks for
