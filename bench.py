@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per nm_gemm launch (bf16 output) of the benchmark's four layers, from rocprofv3 FETCH_SIZE and
 # WRITE_SIZE passes scaled by what the same counters read on a plain 256 MiB copy (read counter x2.000, write
 # counter x1.000): profiles/bert_base_2of4_int8_counters.txt.  Not measurable from inside this process.
-MEASURED_HBM_BYTES_BF16 = {"qkv": 31.25e6, "attn_out": 12.67e6, "ffn_up": 40.54e6, "ffn_down": 30.89e6}
+MEASURED_HBM_BYTES_BF16 = {"qkv": 31.27e6, "attn_out": 12.66e6, "ffn_up": 40.56e6, "ffn_down": 30.90e6}
 
 
 def parse():

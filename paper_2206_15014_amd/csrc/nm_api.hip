@@ -117,6 +117,7 @@ int nm_gemm(const int8_t* X_dev, int tokens, int K, int ldx, float act_scale,
     a.vstride = (int)row_bytes(kc, bits);
     a.mstride = (int)row_bytes(kc, M == 4 ? 2 : 4);
     a.store_through = 0;
+    a.k_rotate = 0;
     a.out_scale = 1.0f;
     a.absmax = nullptr;
     return nm::launch_gemm(a, static_cast<hipStream_t>(hip_stream));
@@ -163,6 +164,7 @@ int nm_gemm_q8(const int8_t* X_dev, int tokens, int K, int ldx, float act_scale,
     a.vstride = (int)row_bytes(kc, bits);
     a.mstride = (int)row_bytes(kc, M == 4 ? 2 : 4);
     a.store_through = 0;
+    a.k_rotate = 0;
     a.out_scale = out_scale;
     a.absmax = absmax_dev;
     return nm::launch_gemm(a, static_cast<hipStream_t>(hip_stream));

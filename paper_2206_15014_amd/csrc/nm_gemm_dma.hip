@@ -97,11 +97,15 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     uint32_t voff[PER_WAVE];                   // this lane's byte offset from sbase[p], at the next stage to issue
     const uint8_t* sbase[PER_WAVE];
     uint32_t stepb[PER_WAVE];                  // bytes per stage along the source row
-    // Workgroups walk K in rotated order (stage j of this workgroup is K block (kstart + j) mod ns;
-    // integer sums do not care), so that workgroups sharing rows of X do not all miss on the same
-    // lines at the same moment.
+    // With several rounds of tiles per CU, workgroups walk K in rotated order (stage j of this
+    // workgroup is K block (kstart + j) mod ns; integer sums do not care), so that workgroups
+    // sharing rows of X do not all miss on the same lines at the same moment (8-9 % on the
+    // 12288- to 49152-token layer sets).  With a single round every workgroup starts at the same
+    // instant on inputs that no L2 holds yet, and rotated starts would ask the memory for all of X
+    // and W at once, the first stages queueing behind everybody's later ones: there all start at
+    // block 0 (3.5-4.5 % on the 4096-token layer sets).
     constexpr bool PAIR = G::PAIR_V || G::PAIR_M;        // then stage parity must equal K block parity: even start, even ns
-    const int kstart = (int)(((unsigned)tile * 7u) % (unsigned)ns) & (PAIR ? ~1 : ~0);
+    const int kstart = a.k_rotate ? ((int)(((unsigned)tile * 7u) % (unsigned)ns) & (PAIR ? ~1 : ~0)) : 0;
     uint32_t amask[PER_WAVE];                  // pair arrays: the load address is rounded down to the 16-byte piece
 #pragma unroll
     for (int p = 0; p < PER_WAVE; ++p) {
@@ -600,6 +604,7 @@ bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
     // 12.6 MB, 17 % faster at 18.9 MB, slower below); fp32 always is, in the kernel.
     GemmArgs b = a;
     b.store_through = (long long)a.tokens * a.O * 2 >= (14ll << 20);
+    b.k_rotate = n_tiles > 256;                 // more tiles than CUs: see the kernel
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), lds, st, b, tiles_o, n_tiles);
     return true;
 }

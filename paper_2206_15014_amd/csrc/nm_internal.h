@@ -24,6 +24,7 @@ struct GemmArgs {
     int ldo;
     int vstride, mstride;  // packed row strides in bytes
     int store_through;     // set by a launcher: output stores bypass the L2's write-back (large outputs)
+    int k_rotate;          // set by a launcher: workgroups start their walk along K at different blocks
     float out_scale;       // out_dtype 3: scale of the output codes
     float* absmax;         // out_dtype 3: max |y| is max-combined into it, or null
 };
