@@ -171,9 +171,9 @@ def main():
         items = binding.compress_items([j["W"] for j in js], [(j["vals"], j["meta"], j["scales"]) for j in js])
         batches.append((items, len(js)) + scheme)
 
-    def run_step(st):
+    def run_step(st, mode=None):
         """The launches of one step on stream `st`."""
-        if args.compress == "batched":
+        if (mode or args.compress) == "batched":
             for b in batches:
                 check(lib.nm_compress_batch(*b, st))
             for ga in gargs:
@@ -264,6 +264,25 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # The same work with the other arrangement of the compress calls, timed the same way and reported beside it.
+    other_mode = "per_layer" if args.compress == "batched" else "batched"
+    other_ms = None
+    if graph is not None:
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2, stream=side):
+                for _ in range(steps_per_graph):
+                    run_step(side.cuda_stream, other_mode)
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(3):
+            g2.replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for k in range(args.steps // steps_per_graph):
+            g2.replay()
+        torch.cuda.synchronize()
+        other_ms = (time.perf_counter() - t2) * 1e3 / args.steps
     # Launch duration of the dominant kernel: HIP events around back-to-back (graph-replayed) launches
     # of that same kernel, right after the timed steps; a rocprofv3 kernel trace of this command
     # reports the same kernel about a microsecond shorter (the gap between two launches).
@@ -294,6 +313,8 @@ def main():
                    "tokens": gemms[0].T, "hidden": min(g.K for g in gemms), "pattern": "/".join(sorted({"%d:%d" % (g.N, g.M) for g in gemms})),
                    "weight_bits": "/".join(sorted({str(g.bits) for g in gemms})), "out_dtype": args.out_dtype},
         "pct_of_int8_dense_peak": round(100.0 * value / INT8_DENSE_PEAK_TOPS, 2),
+        "same_work_with_%s_compress" % other_mode: None if other_ms is None else {
+            "ms_per_step": round(other_ms, 5), "value": round(dense_ops / (other_ms * 1e-3) / 1e12, 2)},
         "roofline": {
             "bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_DENSE_PEAK_TOPS, "unit": "TFLOP/s",
             "frac": round(achieved / INT8_DENSE_PEAK_TOPS, 4),
