@@ -174,15 +174,32 @@ __device__ __forceinline__ void encode_group(const float (&x)[M], const Divisor<
 // Requires: N*BITS and N*IB in {2,4,8,16,32}, packed row strides that are multiples of 4 bytes,
 // ldw % 4 == 0 and a 16-byte aligned W.
 // ---------------------------------------------------------------------------------------------
+// The fp32 weights are read once and never again.  A batched call whose matrices exceed what the L2s
+// hold together (32 MB) loads them with the streaming hint, so that they do not push the operands of the
+// GEMMs that follow out of the caches (the 48 matrices of a 12-layer encoder, 340 MB: the GEMMs after
+// them 5 % faster; BERT-large's layer set, 50 MB: 2 %); smaller calls use plain loads (a caller that
+// compresses the same 28 MB again and again finds them in the Infinity Cache).
+constexpr long long STREAM_ABOVE_BYTES = 32ll << 20;
+constexpr int GIVEN_SCALES = 1;                        // bit of the kernels' `flags` argument
+typedef float v4f_t __attribute__((ext_vector_type(4)));
+template <bool ONCE>
+__device__ __forceinline__ float4 load_w(const float4* p)
+{
+    if constexpr (!ONCE) return *p;
+    const v4f_t v = __builtin_nontemporal_load(reinterpret_cast<const v4f_t*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // The rows of one workgroup: `block` is the workgroup's index among those of this matrix, WPR
 // (1, 2 or 4) a compile-time constant in the single-matrix kernel and a per-matrix value in the
 // batched one (uniform over the workgroup, so the barrier below is too).
-template <int N, int M, int BITS, int RES>
+template <int N, int M, int BITS, int RES, bool ONCE>
 __device__ __forceinline__ void
 compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
               uint32_t* __restrict__ vals, uint32_t* __restrict__ meta, float* __restrict__ scales,
-              int vstride_dw, int mstride_dw, int given, const int WPR, const int block, float* part)
+              int vstride_dw, int mstride_dw, int flags, const int WPR, const int block, float* part)
 {
+    const bool given = (flags & GIVEN_SCALES) != 0;
     constexpr int IB = (M == 4) ? 2 : 4;
     constexpr int VB = N * BITS;           // value bits per group
     constexpr int MB = N * IB;             // index bits per group
@@ -217,7 +234,7 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
             const int g = (w + i * WPR) * 64 + lane;
             if (i < mine && g < groups) {
 #pragma unroll
-                for (int f = 0; f < F4; ++f) x[i * F4 + f] = w4[(unsigned)(g * F4 + f)];
+                for (int f = 0; f < F4; ++f) x[i * F4 + f] = load_w<ONCE>(w4 + (unsigned)(g * F4 + f));
             }
         }
 #pragma unroll
@@ -231,7 +248,7 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
             if (g < groups)
 #pragma unroll
                 for (int f = 0; f < F4; ++f) {
-                    float4 v = w4[(unsigned)(g * F4 + f)];
+                    float4 v = load_w<ONCE>(w4 + (unsigned)(g * F4 + f));
                     amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
                 }
         }
@@ -282,7 +299,7 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
 #pragma unroll
                 for (int f = 0; f < F4; ++f) {
                     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (g < groups) v = w4[(unsigned)(g * F4 + f)];
+                    if (g < groups) v = load_w<ONCE>(w4 + (unsigned)(g * F4 + f));
                     grp[4 * f + 0] = v.x; grp[4 * f + 1] = v.y; grp[4 * f + 2] = v.z; grp[4 * f + 3] = v.w;
                 }
                 emit(grp, g);
@@ -299,10 +316,10 @@ template <int N, int M, int BITS, int WPR, int RES>
 __global__ void __launch_bounds__(256)
 compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
                      uint32_t* __restrict__ vals, uint32_t* __restrict__ meta, float* __restrict__ scales,
-                     int vstride_dw, int mstride_dw, int given)      // given != 0: scales[] holds the rows' scales already
+                     int vstride_dw, int mstride_dw, int flags)      // GIVEN_SCALES: scales[] holds the rows' scales already
 {
     __shared__ float part[4];
-    compress_rows<N, M, BITS, RES>(W, rows, cols, ldw, vals, meta, scales, vstride_dw, mstride_dw, given, WPR, blockIdx.x, part);
+    compress_rows<N, M, BITS, RES, false>(W, rows, cols, ldw, vals, meta, scales, vstride_dw, mstride_dw, flags, WPR, blockIdx.x, part);
 }
 
 // Several matrices of one pattern in one launch: the descriptors travel by value in the kernel
@@ -320,9 +337,10 @@ struct BatchItem {
 struct BatchArgs {
     BatchItem it[BATCH_MAX];
     int count;
+    int flags;
 };
 
-template <int N, int M, int BITS, int RES>
+template <int N, int M, int BITS, int RES, bool ONCE>
 __global__ void __launch_bounds__(256)
 compress_batch_kernel(const BatchArgs b)
 {
@@ -331,7 +349,7 @@ compress_batch_kernel(const BatchArgs b)
     for (int k = 1; k < b.count; ++k)
         if ((int)blockIdx.x >= b.it[k].first_block) i = k;     // uniform: scalar loads from the argument segment
     const BatchItem& t = b.it[i];
-    compress_rows<N, M, BITS, RES>(t.W, t.rows, t.cols, t.ldw, t.vals, t.meta, t.scales, t.vstride_dw, t.mstride_dw, 0,
+    compress_rows<N, M, BITS, RES, ONCE>(t.W, t.rows, t.cols, t.ldw, t.vals, t.meta, t.scales, t.vstride_dw, t.mstride_dw, 0,
                                    t.wpr, (int)blockIdx.x - t.first_block, part);
 }
 
@@ -409,11 +427,11 @@ decompress_kernel(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ 
 
 template <int N, int M, int BITS, int WPR, int RES>
 void launch_wave_res(const float* W, int rows, int cols, int ldw, uint32_t* v, uint32_t* m, float* scales,
-                     int vstride, int mstride, int given, hipStream_t st)
+                     int vstride, int mstride, int flags, hipStream_t st)
 {
     constexpr int RPB = 4 / WPR;
     hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, WPR, RES>), dim3((rows + RPB - 1) / RPB), dim3(256), 0, st,
-                       W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4, given);
+                       W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4, flags);
 }
 
 // WPR = wavefronts per row: enough that a wavefront walks at most ~4 passes of 64 groups.  RES =
@@ -422,28 +440,28 @@ void launch_wave_res(const float* W, int rows, int cols, int ldw, uint32_t* v, u
 // nothing); rows too long for the largest size are read twice.
 template <int N, int M, int BITS, int WPR>
 void launch_wave_wpr(const float* W, int rows, int cols, int ldw, uint32_t* v, uint32_t* m, float* scales,
-                     int vstride, int mstride, int given, hipStream_t st)
+                     int vstride, int mstride, int flags, hipStream_t st)
 {
     constexpr int MAXRES = 16 / (M / 4);
     const int passes = (cols / M + 63) / 64;
     const int mine = (passes + WPR - 1) / WPR;                 // of wavefront 0, the longest share
-    if (mine <= 1) launch_wave_res<N, M, BITS, WPR, 1>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
-    else if (mine <= 2) launch_wave_res<N, M, BITS, WPR, 2>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
-    else if (mine <= 3) launch_wave_res<N, M, BITS, WPR, 3>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
-    else if (mine <= 4) launch_wave_res<N, M, BITS, WPR, 4>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
-    else launch_wave_res<N, M, BITS, WPR, MAXRES>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
+    if (mine <= 1) launch_wave_res<N, M, BITS, WPR, 1>(W, rows, cols, ldw, v, m, scales, vstride, mstride, flags, st);
+    else if (mine <= 2) launch_wave_res<N, M, BITS, WPR, 2>(W, rows, cols, ldw, v, m, scales, vstride, mstride, flags, st);
+    else if (mine <= 3) launch_wave_res<N, M, BITS, WPR, 3>(W, rows, cols, ldw, v, m, scales, vstride, mstride, flags, st);
+    else if (mine <= 4) launch_wave_res<N, M, BITS, WPR, 4>(W, rows, cols, ldw, v, m, scales, vstride, mstride, flags, st);
+    else launch_wave_res<N, M, BITS, WPR, MAXRES>(W, rows, cols, ldw, v, m, scales, vstride, mstride, flags, st);
 }
 
 template <int N, int M, int BITS>
 void launch_wave(const float* W, int rows, int cols, int ldw, void* vals, void* meta, float* scales,
-                 int vstride, int mstride, int given, hipStream_t st)
+                 int vstride, int mstride, int flags, hipStream_t st)
 {
     const int passes = (cols / M + 63) / 64;
     uint32_t* v = (uint32_t*)vals;
     uint32_t* m = (uint32_t*)meta;
-    if (passes > 8) launch_wave_wpr<N, M, BITS, 4>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
-    else if (passes > 4) launch_wave_wpr<N, M, BITS, 2>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
-    else launch_wave_wpr<N, M, BITS, 1>(W, rows, cols, ldw, v, m, scales, vstride, mstride, given, st);
+    if (passes > 8) launch_wave_wpr<N, M, BITS, 4>(W, rows, cols, ldw, v, m, scales, vstride, mstride, flags, st);
+    else if (passes > 4) launch_wave_wpr<N, M, BITS, 2>(W, rows, cols, ldw, v, m, scales, vstride, mstride, flags, st);
+    else launch_wave_wpr<N, M, BITS, 1>(W, rows, cols, ldw, v, m, scales, vstride, mstride, flags, st);
 }
 
 }  // namespace
@@ -462,10 +480,11 @@ int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, i
     // One scale per group of rows: the scales are computed first (row maxima, then the groups'),
     // and the kernels below quantise with what they find in scales[].
     const int given = rows_per_scale > 1 ? 1 : 0;
+    const int flags = given ? GIVEN_SCALES : 0;
     if (given) launch_group_scales(W, rows, cols, ldw, rows_per_scale, (float)((1 << (bits - 1)) - 1), scales, st);
     if (aligned) {
         done = true;
-#define NM_CASE(n, m, b) else if (N == n && M == m && bits == b) launch_wave<n, m, b>(W, rows, cols, ldw, vals, meta, scales, vstride, mstride, given, st)
+#define NM_CASE(n, m, b) else if (N == n && M == m && bits == b) launch_wave<n, m, b>(W, rows, cols, ldw, vals, meta, scales, vstride, mstride, flags, st)
         if (false) {}
         NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4);
         NM_CASE(1, 8, 8); NM_CASE(2, 8, 8); NM_CASE(4, 8, 8);
@@ -487,16 +506,23 @@ int wave_wpr(int cols, int M)
     return passes > 8 ? 4 : (passes > 4 ? 2 : 1);
 }
 
-template <int N, int M, int BITS>
-void launch_batch(const BatchArgs& b, int max_mine, int blocks, hipStream_t st)
+template <int N, int M, int BITS, bool ONCE>
+void launch_batch_res(const BatchArgs& b, int max_mine, int blocks, hipStream_t st)
 {
     constexpr int MAXRES = 16 / (M / 4);
     const dim3 grid((unsigned)blocks), wg(256);
-    if (max_mine <= 1) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 1>), grid, wg, 0, st, b);
-    else if (max_mine <= 2) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 2>), grid, wg, 0, st, b);
-    else if (max_mine <= 3) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 3>), grid, wg, 0, st, b);
-    else if (max_mine <= 4) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 4>), grid, wg, 0, st, b);
-    else hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, MAXRES>), grid, wg, 0, st, b);
+    if (max_mine <= 1) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 1, ONCE>), grid, wg, 0, st, b);
+    else if (max_mine <= 2) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 2, ONCE>), grid, wg, 0, st, b);
+    else if (max_mine <= 3) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 3, ONCE>), grid, wg, 0, st, b);
+    else if (max_mine <= 4) hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, 4, ONCE>), grid, wg, 0, st, b);
+    else hipLaunchKernelGGL((compress_batch_kernel<N, M, BITS, MAXRES, ONCE>), grid, wg, 0, st, b);
+}
+
+template <int N, int M, int BITS>
+void launch_batch(const BatchArgs& b, int max_mine, int blocks, hipStream_t st)
+{
+    if (b.flags) launch_batch_res<N, M, BITS, true>(b, max_mine, blocks, st);
+    else launch_batch_res<N, M, BITS, false>(b, max_mine, blocks, st);
 }
 
 }  // namespace
@@ -510,6 +536,9 @@ int launch_compress_batch(const CompressItem* items, int count, int N, int M, in
     begin_launch();
     BatchArgs b;
     b.count = 0;
+    long long bytes = 0;
+    for (int i = 0; i < count; ++i) bytes += (long long)items[i].rows * items[i].cols * 4;
+    b.flags = bytes > STREAM_ABOVE_BYTES ? 1 : 0;           // stream the weights
     int blocks = 0, max_mine = 0;
     auto flush = [&]() {
         if (b.count == 0) return;
