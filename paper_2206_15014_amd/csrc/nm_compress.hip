@@ -143,6 +143,48 @@ __device__ __forceinline__ void encode_group(const float (&x)[M], const Divisor<
         }
         return;
     }
+    if constexpr (M == 8 && (N == 1 || N == 2)) {
+        // Groups of eight, one or two kept: each of the 28 pairs is compared once (ge[d][c], d < c:
+        // the lower column is at least as large, so it outranks the higher one; otherwise the
+        // higher one outranks it), a column's count of outranking entries is the number of
+        // columns above it, plus the pairs it loses to lower columns, minus the pairs it wins
+        // against higher ones; the slots are the first and the last kept column.
+        float a[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) a[c] = fabsf(x[c]);
+        bool keep[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            int outranked = 7 - c;
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                if (d < c) outranked += (a[d] >= a[c]) ? 1 : 0;
+                if (d > c) outranked -= (a[c] >= a[d]) ? 1 : 0;
+            }
+            keep[c] = outranked < N;
+        }
+        float lo = x[7];
+        uint32_t clo = 7u;
+#pragma unroll
+        for (int c = 6; c >= 0; --c) {                  // first kept column
+            lo = keep[c] ? x[c] : lo;
+            clo = keep[c] ? (uint32_t)c : clo;
+        }
+        vbits = (uint32_t)quantize<BITS>(lo, s) & ((1u << BITS) - 1u);
+        mbits = clo;
+        if constexpr (N == 2) {
+            float hi = x[0];
+            uint32_t chi = 0u;
+#pragma unroll
+            for (int c = 1; c < 8; ++c) {               // last kept column
+                hi = keep[c] ? x[c] : hi;
+                chi = keep[c] ? (uint32_t)c : chi;
+            }
+            vbits |= ((uint32_t)quantize<BITS>(hi, s) & ((1u << BITS) - 1u)) << BITS;
+            mbits |= chi << IB;
+        }
+        return;
+    }
     const uint32_t mask = keep_mask<N, M>(x);
     vbits = 0;
     mbits = 0;
