@@ -126,13 +126,52 @@ project_kernel(const float* __restrict__ W, const float* U, int rows, int cols, 
         }
         v[4 * f + 0] = x.x; v[4 * f + 1] = x.y; v[4 * f + 2] = x.z; v[4 * f + 3] = x.w;
     }
+    const float s = bits ? scales[row] : 1.0f;
+    const float qmax = (float)((1 << (bits ? bits - 1 : 7)) - 1);
+    // Eq. 5 (offset 0), then Eq. 4: the value the integer code stands for (an integer code: its zero has no sign)
+    auto requantised = [&](float x) {
+        const int q = (int)fminf(fmaxf(rintf(__fdiv_rn(x, s)), -qmax), qmax);
+        return __fmul_rn(s, (float)q);
+    };
+    if constexpr (M == 4) {
+        if (N <= 2) {
+            // Groups of four with one or two kept: the six pairwise comparisons decide every pair
+            // (the lower column outranks on >=, the higher one otherwise), the keep flags follow
+            // from them, and only the kept entries (the lowest and the highest kept column) are
+            // quantised.
+            const float a0 = fabsf(v[0]), a1 = fabsf(v[1]), a2 = fabsf(v[2]), a3 = fabsf(v[3]);
+            const bool c01 = a0 >= a1, c02 = a0 >= a2, c03 = a0 >= a3, c12 = a1 >= a2, c13 = a1 >= a3, c23 = a2 >= a3;
+            float z0, z1, z2, z3;
+            if (N == 2) {
+                auto under_two = [](bool p, bool q, bool r) { return !((p && q) || (p && r) || (q && r)); };
+                const bool k0 = under_two(!c01, !c02, !c03), k1 = under_two(c01, !c12, !c13);
+                const bool k2 = under_two(c02, c12, !c23), k3 = under_two(c03, c13, c23);
+                float lo = k0 ? v[0] : (k1 ? v[1] : v[2]);
+                float hi = k3 ? v[3] : (k2 ? v[2] : v[1]);
+                if (bits) { lo = requantised(lo); hi = requantised(hi); }
+                z0 = k0 ? lo : 0.0f;
+                z1 = k1 ? (k0 ? hi : lo) : 0.0f;
+                z2 = k2 ? (k3 ? lo : hi) : 0.0f;
+                z3 = k3 ? hi : 0.0f;
+            } else {
+                const bool k0 = c01 && c02 && c03, k1 = !c01 && c12 && c13, k2 = !c02 && !c12 && c23;
+                const bool k3 = !(k0 || k1 || k2);
+                float kept = k0 ? v[0] : (k1 ? v[1] : (k2 ? v[2] : v[3]));
+                if (bits) kept = requantised(kept);
+                z0 = k0 ? kept : 0.0f; z1 = k1 ? kept : 0.0f; z2 = k2 ? kept : 0.0f; z3 = k3 ? kept : 0.0f;
+            }
+            *reinterpret_cast<float4*>(Z + out_at) = make_float4(z0, z1, z2, z3);
+            if (U_out)
+                *reinterpret_cast<float4*>(U_out + out_at) =
+                    make_float4(__fsub_rn(v[0], z0), __fsub_rn(v[1], z1), __fsub_rn(v[2], z2), __fsub_rn(v[3], z3));
+            return;
+        }
+    }
     // Eq. 3: an entry is kept when fewer than N entries outrank it; a larger magnitude outranks a
     // smaller one and, between equal magnitudes, the lower column the higher.
     float a[M];
 #pragma unroll
     for (int c = 0; c < M; ++c) a[c] = fabsf(v[c]);
-    const float s = bits ? scales[row] : 1.0f;
-    const float qmax = (float)((1 << (bits ? bits - 1 : 7)) - 1);
     float z[M];
 #pragma unroll
     for (int c = 0; c < M; ++c) {
@@ -143,10 +182,7 @@ project_kernel(const float* __restrict__ W, const float* U, int rows, int cols, 
             outranked += (d < c) ? (a[d] >= a[c]) : (a[d] > a[c]);
         }
         float kept_value = v[c];
-        if (bits) {                            // Eq. 5 (offset 0), then Eq. 4: the value the integer code stands for
-            const int q = (int)fminf(fmaxf(rintf(__fdiv_rn(v[c], s)), -qmax), qmax);   // an integer code: its zero has no sign
-            kept_value = __fmul_rn(s, (float)q);
-        }
+        if (bits) kept_value = requantised(v[c]);
         z[c] = (outranked < N) ? kept_value : 0.0f;
     }
 #pragma unroll
