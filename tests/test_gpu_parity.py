@@ -642,3 +642,44 @@ def test_compress_quotients_next_to_half_way_points(N, M, bits):
     assert np.isfinite(W).all()
     packed = gpu_compress(W, N, M, bits)
     assert_packed_equal(packed, oracle.compress(W, N, M, bits), "half-way quotients")
+
+
+def test_compress_batch_and_gemm_replayed_from_a_graph():
+    """The launches as bench.py issues them: nm_compress_batch and nm_gemm captured once in a HIP
+    graph and replayed, the weights changed in place between the replays (and eager work and
+    synchronisations in between); every replay must give what the oracle gives for the weights
+    of that moment."""
+    say("graph replay: compress batch + gemm")
+    N, M, bits = 2, 4, 8
+    rng = np.random.default_rng(99)
+    shapes = [(96, 256), (40, 768)]
+    Ws = [(rng.standard_normal(sh) * 0.02).astype(np.float32) for sh in shapes]
+    Wd = [torch.from_numpy(W).to(DEV) for W in Ws]
+    outs = nm.nm_compress_batch(Wd, N, M, bits)             # allocates the packed buffers (and warms up)
+    T, K, O = 200, 256, 96
+    Xq, sx = synth.quantize_activations(rng.standard_normal((T, K)).astype(np.float32))
+    X = torch.from_numpy(Xq).to(DEV)
+    acc = torch.empty((T, O), dtype=torch.int32, device=DEV)
+    y = torch.empty((T, O), dtype=torch.float32, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        nm.nm_gemm(X, float(sx), *outs[0], O, N, M, bits, acc=acc, out=y, out_dtype=NM_OUT_F32, stream=side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            nm.nm_compress_batch(Wd, N, M, bits, outs=outs, stream=side)
+            nm.nm_gemm(X, float(sx), *outs[0], O, N, M, bits, acc=acc, out=y, out_dtype=NM_OUT_F32, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        for W, d in zip(Ws, Wd):                            # new weights in the same buffers
+            W[...] = (rng.standard_normal(W.shape) * 0.02 * (rep + 1)).astype(np.float32)
+            d.copy_(torch.from_numpy(W))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for W, packed in zip(Ws, outs):
+            assert_packed_equal(packed, oracle.compress(W, N, M, bits), "replay %d" % rep)
+        ref = oracle.compress(Ws[0], N, M, bits)
+        acc_ref = oracle.gemm_sparse(Xq, ref[0], ref[1], O, N, M, bits)
+        check_outputs(acc_ref, sx, ref[2], None, acc.cpu().numpy(), y.cpu().numpy(), None, what="replay %d" % rep)
