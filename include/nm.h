@@ -102,9 +102,10 @@ int nm_compress_grouped(const float *W_dev, int rows, int cols, int ldw,
  * scales_dev) gives, byte for byte; the matrices that meet nm_compress's alignment share launches
  * (the fixed cost of a launch is several times the time their bytes take), the others go one by
  * one.  `items` is HOST memory, read during the call and not kept; the device buffers of
- * different items must not overlap; count <= 0 is an error, as is any item nm_compress would
- * refuse (then nothing is enqueued).
+ * different items must not overlap; count <= 0 or count > NM_COMPRESS_BATCH_MAX_ITEMS is an error
+ * (NM_ERR_DIM), as is any item nm_compress would refuse (then nothing is enqueued).
  */
+#define NM_COMPRESS_BATCH_MAX_ITEMS 65536
 typedef struct nm_compress_item {
     const float *W_dev;   /* [rows][ldw] float                        */
     int rows, cols, ldw;

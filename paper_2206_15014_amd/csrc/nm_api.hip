@@ -63,7 +63,7 @@ int nm_compress_grouped(const float* W_dev, int rows, int cols, int ldw, int N, 
 
 int nm_compress_batch(const nm_compress_item* items, int count, int N, int M, int bits, void* hip_stream)
 {
-    if (count <= 0) return NM_ERR_DIM;
+    if (count <= 0 || count > NM_COMPRESS_BATCH_MAX_ITEMS) return NM_ERR_DIM;
     if (!items) return NM_ERR_NULL;
     std::vector<nm::CompressItem> v((size_t)count);
     for (int i = 0; i < count; ++i) {

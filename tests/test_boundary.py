@@ -52,6 +52,7 @@ def test_entry_points_validate_before_launch():
     items = (Item * 2)(Item(P, 8, 8, 8, P, P, P), Item(P, 8, 16, 16, P, P, P))
     assert lib.nm_compress_batch(items, 0, 2, 4, 8, None) == -2               # no items
     assert lib.nm_compress_batch(None, 2, 2, 4, 8, None) == -1
+    assert lib.nm_compress_batch(items, 65537, 2, 4, 8, None) == -2           # more items than a call takes
     assert lib.nm_compress_batch(items, 2, 2, 4, 7, None) == -4
     for bad, code in [(Item(None, 8, 8, 8, P, P, P), -1), (Item(P, 8, 8, 8, P, None, P), -1), (Item(P, 8, 8, 4, P, P, P), -2),
                       (Item(P, 0, 8, 8, P, P, P), -2), (Item(P, 8, 10, 12, P, P, P), -3), (Item(P + 2, 8, 8, 8, P, P, P), -6)]:
