@@ -41,6 +41,10 @@ def _load():
         _lib.nmo_row_scale.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int]
         _lib.nmo_quantize_one.restype = ctypes.c_int
         _lib.nmo_quantize_one.argtypes = [ctypes.c_float, ctypes.c_float, ctypes.c_int]
+        _lib.nmo_tiled_bytes.restype = ctypes.c_size_t
+        _lib.nmo_tiled_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_size_t]
+        _lib.nmo_to_tiled.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p]
+        _lib.nmo_from_tiled.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p]
     return _lib
 
 
@@ -56,7 +60,7 @@ def _check(rc: int):
 
 
 def _p(a):
-    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+    return None if a is None or a.size == 0 else ctypes.c_void_p(a.ctypes.data)
 
 
 def num_threads() -> int:
@@ -75,6 +79,42 @@ def packed_sizes(rows, cols, N, M, bits):
     _check(_load().nmo_packed_sizes(rows, cols, N, M, bits,
                                     ctypes.byref(v), ctypes.byref(m), ctypes.byref(s)))
     return v.value, m.value, s.value
+
+
+def unit_bytes(N, M, bits):
+    """(value bytes, index bytes) of the packed entries covering 32 input columns of one row."""
+    epu = 32 // M * N
+    ib = 0 if N >= M else (2 if M == 4 else 4)
+    return epu * bits // 8, epu * ib // 8
+
+
+def to_tiled(vals, meta, cols, N, M, bits):
+    """Row layout -> tiled layout (both arrays; flat uint8).  A dense matrix has no metadata."""
+    vals = np.ascontiguousarray(vals, dtype=np.uint8)
+    meta = np.ascontiguousarray(meta, dtype=np.uint8)
+    rows = vals.shape[0]
+    out = []
+    for a, ub in zip((vals, meta), unit_bytes(N, M, bits)):
+        if ub == 0:
+            out.append(np.zeros(0, dtype=np.uint8))
+            continue
+        t = np.zeros(_load().nmo_tiled_bytes(rows, cols, ub), dtype=np.uint8)
+        _check(_load().nmo_to_tiled(_p(a), rows, cols, ub, _p(t)))
+        out.append(t)
+    return out[0], out[1]
+
+
+def from_tiled(vals_t, meta_t, rows, cols, N, M, bits):
+    """Tiled layout -> row layout: (vals [rows, vstride], meta [rows, mstride])."""
+    out = []
+    for a, ub in zip((vals_t, meta_t), unit_bytes(N, M, bits)):
+        r = np.zeros((rows, cols // 32 * ub), dtype=np.uint8)
+        if ub:
+            a = np.ascontiguousarray(a, dtype=np.uint8)
+            assert a.size == _load().nmo_tiled_bytes(rows, cols, ub)
+            _check(_load().nmo_from_tiled(_p(a), rows, cols, ub, _p(r)))
+        out.append(r)
+    return out[0], out[1]
 
 
 def project(W, N, M):

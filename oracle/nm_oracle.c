@@ -43,13 +43,14 @@
  *     qmax = 2^(b-1) - 1.
  *   - packed format: see nmo_packed_sizes.
  *   - the dequantized value is formed in double and rounded once.
- *   - requantised output: the paper fixes neither where the activation scale
- *     comes from nor the arithmetic; here the caller supplies the scale, and,
- *     because a rounding decides an integer, the value is formed in fp32 in a
- *     fixed order (see nmo_requant) that the GPU path follows bit for bit; the
- *     division of Eq. 5 is applied to each column's multiplier and offset, not
- *     to each output (a per-output division costs more than the whole rest of
- *     the epilogue and changes a result by at most an fp32 rounding).
+ *   - requantised output: the paper does not say where the activation scale
+ *     comes from; here the caller supplies it.  The value quantised is the
+ *     dequantised output of Eq. 4 exactly as nmo_dequant forms it (double,
+ *     rounded once to float), and the quantiser is Eq. 5 as for the weights:
+ *     one fp32 division per output, round half to even, clamp to +-127.
+ *   - dense matrices (N = M, the "Q4" / "Q8" components of Sec. 5.4): every
+ *     entry is kept, no index metadata is stored.
+ *   - tiled layout: a byte permutation of the packed rows, see nmo_to_tiled.
  *
  * Build: gcc -O2 -std=c11 -fno-fast-math -ffp-contract=off -fopenmp -shared -fPIC
  *
@@ -57,8 +58,10 @@
  * supports, N=1 == argmax, idempotence, max-survives-pruning invariant,
  * quantiser closed forms and half-way cases, an independent numpy decoder of
  * the byte format, numpy int64 matmul on the decompressed matrix, dequant
- * special cases; requantisation against exact rational arithmetic with each
- * fp32 rounding applied explicitly, half-way and saturation cases.  The tie-break rule and the byte format are this build's own
+ * special cases; requantisation against exact rational arithmetic, half-way
+ * and saturation cases, and the weight quantiser applied to the dequantised
+ * value; the tiled layout against a numpy transposition of the row layout and
+ * a hand-placed case.  The tie-break rule and the byte format are this build's own
  * choices (the paper fixes neither): pinned by the written format description
  * and the independent decoder, not by the paper.
  */
@@ -76,13 +79,14 @@ enum {
     NMO_ERR_NONFINITE = -5
 };
 
-static int index_bits(int M) { return M == 4 ? 2 : 4; }
+/* Bits of index metadata per kept entry: none for a dense matrix (N = M). */
+static int index_bits(int N, int M) { return N >= M ? 0 : (M == 4 ? 2 : 4); }
 
 static int check_pattern(int rows, int cols, int N, int M, int bits)
 {
     if (rows <= 0 || cols <= 0) return NMO_ERR_DIM;
     if (M != 4 && M != 8) return NMO_ERR_PATTERN;
-    if (N < 1 || N >= M) return NMO_ERR_PATTERN;
+    if (N < 1 || N > M) return NMO_ERR_PATTERN;
     if (cols % M != 0) return NMO_ERR_PATTERN;
     if (bits != 4 && bits != 8) return NMO_ERR_BITS;
     return NMO_OK;
@@ -100,7 +104,8 @@ static int check_pattern(int rows, int cols, int N, int M, int bits)
  *            Entry e's column offset inside its group sits in ib bits starting
  *            at bit e*ib of the row, counted LSB-first through the bytes.
  *   scales : one float per row.
- * Unused trailing bits of a row are zero.
+ * Unused trailing bits of a row are zero.  A dense matrix (N = M) keeps every
+ * entry, so entry e is column e and there is no metadata (meta_bytes = 0).
  */
 int nmo_packed_sizes(int rows, int cols, int N, int M, int bits,
                      size_t *vals_bytes, size_t *meta_bytes, size_t *scales_bytes)
@@ -109,7 +114,7 @@ int nmo_packed_sizes(int rows, int cols, int N, int M, int bits,
     if (rc) return rc;
     size_t kc = (size_t)cols / M * N;
     if (vals_bytes) *vals_bytes = (size_t)rows * ((kc * bits + 7) / 8);
-    if (meta_bytes) *meta_bytes = (size_t)rows * ((kc * index_bits(M) + 7) / 8);
+    if (meta_bytes) *meta_bytes = (size_t)rows * ((kc * index_bits(N, M) + 7) / 8);
     if (scales_bytes) *scales_bytes = (size_t)rows * sizeof(float);
     return NMO_OK;
 }
@@ -198,6 +203,13 @@ static unsigned get_bits(const uint8_t *row, size_t bit_offset, int nbits)
     return v;
 }
 
+/* Column offset inside its group of kept entry e of a packed row (dense: nothing stored, entry j is column j). */
+static unsigned kept_offset(const uint8_t *mrow, size_t e, int N, int M)
+{
+    int ib = index_bits(N, M);
+    return ib ? get_bits(mrow, e * ib, ib) : (unsigned)(e % (size_t)N);
+}
+
 /*
  * project (Eq. 3), then scale and quantise the kept entries (Eq. 5), then pack.
  * One scale per group of rows_per_scale consecutive rows (Sec. 4: the paper's
@@ -210,7 +222,7 @@ int nmo_compress_grouped(const float *W, int rows, int cols, int ldw, int N, int
 {
     int rc = check_pattern(rows, cols, N, M, bits);
     if (rc) return rc;
-    if (!W || !vals || !meta || !scales) return NMO_ERR_NULL;
+    if (!W || !vals || (!meta && N < M) || !scales) return NMO_ERR_NULL;
     if (ldw < cols || rows_per_scale < 1) return NMO_ERR_DIM;
     for (int r0 = 0; r0 < rows; r0 += rows_per_scale) {
         int r1 = r0 + rows_per_scale < rows ? r0 + rows_per_scale : rows;
@@ -244,10 +256,10 @@ static int nmo_compress_given(const float *W, int rows, int cols, int ldw, int N
 {
     int rc = check_pattern(rows, cols, N, M, bits);
     if (rc) return rc;
-    if (!W || !vals || !meta || !scales) return NMO_ERR_NULL;
+    if (!W || !vals || (!meta && N < M) || !scales) return NMO_ERR_NULL;
     if (ldw < cols) return NMO_ERR_DIM;
     int groups = cols / M;
-    int ib = index_bits(M);
+    int ib = index_bits(N, M);
     size_t kc = (size_t)groups * N;
     size_t vstride = (kc * bits + 7) / 8;
     size_t mstride = (kc * ib + 7) / 8;
@@ -256,7 +268,7 @@ static int nmo_compress_given(const float *W, int rows, int cols, int ldw, int N
     for (int r = 0; r < rows; ++r) {
         const float *w = W + (size_t)r * ldw;
         uint8_t *vrow = vals + (size_t)r * vstride;
-        uint8_t *mrow = meta + (size_t)r * mstride;
+        uint8_t *mrow = ib ? meta + (size_t)r * mstride : NULL;
         int finite = 1;
         for (int c = 0; c < cols; ++c)
             if (!isfinite(w[c])) finite = 0;
@@ -266,7 +278,7 @@ static int nmo_compress_given(const float *W, int rows, int cols, int ldw, int N
             continue;
         }
         memset(vrow, 0, vstride);
-        memset(mrow, 0, mstride);
+        if (ib) memset(mrow, 0, mstride);
         float s = scales[r];
         for (int g = 0; g < groups; ++g) {
             uint8_t kept[8];
@@ -275,7 +287,7 @@ static int nmo_compress_given(const float *W, int rows, int cols, int ldw, int N
                 size_t e = (size_t)g * N + j;
                 int q = nmo_quantize_one(w[(size_t)g * M + kept[j]], s, bits);
                 put_bits(vrow, e * bits, bits, (unsigned)q & ((1u << bits) - 1u));
-                put_bits(mrow, e * ib, ib, kept[j]);
+                if (ib) put_bits(mrow, e * ib, ib, kept[j]);
             }
         }
     }
@@ -294,9 +306,9 @@ int nmo_decompress(const uint8_t *vals, const uint8_t *meta, int rows, int cols,
 {
     int rc = check_pattern(rows, cols, N, M, bits);
     if (rc) return rc;
-    if (!vals || !meta || !Wq) return NMO_ERR_NULL;
+    if (!vals || (!meta && N < M) || !Wq) return NMO_ERR_NULL;
     int groups = cols / M;
-    int ib = index_bits(M);
+    int ib = index_bits(N, M);
     size_t kc = (size_t)groups * N;
     size_t vstride = (kc * bits + 7) / 8;
     size_t mstride = (kc * ib + 7) / 8;
@@ -304,7 +316,7 @@ int nmo_decompress(const uint8_t *vals, const uint8_t *meta, int rows, int cols,
     for (int r = 0; r < rows; ++r)
         for (size_t e = 0; e < kc; ++e) {
             int q = sign_extend(get_bits(vals + (size_t)r * vstride, e * bits, bits), bits);
-            unsigned off = get_bits(meta + (size_t)r * mstride, e * ib, ib);
+            unsigned off = kept_offset(ib ? meta + (size_t)r * mstride : NULL, e, N, M);
             size_t col = (e / N) * M + off;
             Wq[(size_t)r * cols + col] = (int8_t)q;
         }
@@ -321,22 +333,22 @@ int nmo_gemm_sparse(const int8_t *X, int tokens, int K, int ldx,
 {
     int rc = check_pattern(O, K, N, M, bits);
     if (rc) return rc;
-    if (!X || !vals || !meta || !acc) return NMO_ERR_NULL;
+    if (!X || !vals || (!meta && N < M) || !acc) return NMO_ERR_NULL;
     if (tokens <= 0 || ldx < K || ldacc < O) return NMO_ERR_DIM;
-    int ib = index_bits(M);
+    int ib = index_bits(N, M);
     size_t kc = (size_t)K / M * N;
     size_t vstride = (kc * bits + 7) / 8;
     size_t mstride = (kc * ib + 7) / 8;
 #pragma omp parallel for schedule(static)
     for (int o = 0; o < O; ++o) {
         const uint8_t *vrow = vals + (size_t)o * vstride;
-        const uint8_t *mrow = meta + (size_t)o * mstride;
+        const uint8_t *mrow = ib ? meta + (size_t)o * mstride : NULL;
         for (int t = 0; t < tokens; ++t) {
             const int8_t *x = X + (size_t)t * ldx;
             int32_t sum = 0;
             for (size_t e = 0; e < kc; ++e) {
                 int q = sign_extend(get_bits(vrow, e * bits, bits), bits);
-                size_t col = (e / N) * M + get_bits(mrow, e * ib, ib);
+                size_t col = (e / N) * M + kept_offset(mrow, e, N, M);
                 sum += (int32_t)x[col] * (int32_t)q;
             }
             acc[(size_t)t * ldacc + o] = sum;
@@ -396,19 +408,12 @@ int nmo_dequant(const int32_t *acc, int tokens, int O, int ldacc, float act_scal
 }
 
 /*
- * Layer output as 8-bit activations for the next layer: Eq. 4 (o = 0) followed
- * by Eq. 5 (o = 0, 8 bits) with the caller's scale.  The division by the scale
- * is taken once per output column (folded into the column's multiplier and
- * offset) instead of once per output; every step is one fp32 operation, in this
- * order:
- *   g[o] = (act_scale * s_w[o]) / out_scale     (multiplication, then division)
- *   h[o] = bias[o] / out_scale, or 0            (division)
- *   z    = fma((float)acc, g[o], h[o])          (int32 -> float conversion rounds
- *                                                to nearest even, then one fused
- *                                                multiply-add)
- *   q    = clamp(rne(z), -127, 127)             (round half to even)
- * absmax, when given, receives (max |z|) * out_scale: max |y| up to rounding,
- * the statistic a caller needs to choose the next out_scale.
+ * Layer output as 8-bit activations for the next layer (Sec. 5.3): the
+ * dequantised value of Eq. 4 (o = 0), formed as in nmo_dequant (double, rounded
+ * once to float), then the quantiser of Eq. 5 (o = 0, 8 bits) with the caller's
+ * scale, exactly as it is applied to the weights: one fp32 division, round half
+ * to even, clamp to [-127, 127].  absmax, when given, receives max |y| over all
+ * outputs, the statistic from which a caller chooses the next out_scale.
  */
 int nmo_requant(const int32_t *acc, int tokens, int O, int ldacc, float act_scale,
                 const float *scales, const float *bias, float out_scale,
@@ -417,24 +422,81 @@ int nmo_requant(const int32_t *acc, int tokens, int O, int ldacc, float act_scal
     if (!acc || !scales || !out) return NMO_ERR_NULL;
     if (tokens <= 0 || O <= 0 || ldacc < O || ldo < O) return NMO_ERR_DIM;
     if (!(out_scale > 0.0f) || !isfinite(out_scale)) return NMO_ERR_NONFINITE;
-    float zmax = 0.0f;
-    for (int o = 0; o < O; ++o) {
-        volatile float p = act_scale * scales[o];
-        volatile float g = p / out_scale;
-        volatile float h = bias ? bias[o] / out_scale : 0.0f;
-        for (int t = 0; t < tokens; ++t) {
-            volatile float z = fmaf((float)acc[(size_t)t * ldacc + o], g, h);
-            if (fabsf(z) > zmax) zmax = fabsf(z);
-            float r = nearbyintf(z);
-            if (r > 127.0f) r = 127.0f;
-            if (r < -127.0f) r = -127.0f;
-            out[(size_t)t * ldo + o] = (int8_t)r;
+    float ymax = 0.0f;
+    for (int t = 0; t < tokens; ++t)
+        for (int o = 0; o < O; ++o) {
+            double y = (double)acc[(size_t)t * ldacc + o] * (double)act_scale * (double)scales[o];
+            if (bias) y += (double)bias[o];
+            float yf = (float)y;
+            if (fabsf(yf) > ymax) ymax = fabsf(yf);
+            out[(size_t)t * ldo + o] = (int8_t)nmo_quantize_one(yf, out_scale, 8);
         }
-    }
-    if (absmax) {
-        volatile float m = zmax * out_scale;
-        *absmax = m;
-    }
+    if (absmax) *absmax = ymax;
+    return NMO_OK;
+}
+
+/*
+ * Tiled layout of the packed values and of the index metadata: a permutation of
+ * the bytes of the row layout above, chosen so that what one matrix-core
+ * fragment consumes (16 rows x 128 input columns) is one contiguous run of
+ * memory.  Defined for cols % 128 == 0.
+ *   unit    = the packed bytes of one row that cover 32 consecutive input
+ *             columns: unit u of row r is bytes [u*UB, (u+1)*UB) of row r in the
+ *             row layout, UB = (32/M)*N*bits/8 for values and (32/M)*N*ib/8
+ *             for metadata.
+ *   block   = the 64 units of 16 consecutive rows (row block rb = r / 16) and
+ *             one 128-column slice (s = u / 4); block (rb, s) starts at byte
+ *             (rb * (cols/128) + s) * 64 * UB.  Rows are padded with zero bytes
+ *             up to a multiple of 16.
+ *   in a block, unit number j = (u % 4) * 16 + (r % 16); a unit is cut into
+ *             pieces of PB bytes, PB the largest power of two <= 16 dividing UB,
+ *             and piece p of unit j lies at byte (p * 64 + j) * PB of the block.
+ * nmo_to_tiled converts one array (values or metadata, told apart only by UB);
+ * nmo_from_tiled is its inverse.
+ */
+static size_t tiled_piece_bytes(size_t ub)
+{
+    size_t pb = 16;
+    while (ub % pb) pb >>= 1;
+    return pb;
+}
+
+static size_t tiled_offset(size_t r, size_t byte_in_row, size_t ub, size_t slices)
+{
+    size_t u = byte_in_row / ub, i = byte_in_row % ub;
+    size_t pb = tiled_piece_bytes(ub);
+    size_t block = (r / 16) * slices + u / 4;
+    size_t j = (u % 4) * 16 + r % 16;
+    return block * 64 * ub + ((i / pb) * 64 + j) * pb + i % pb;
+}
+
+size_t nmo_tiled_bytes(int rows, int cols, size_t unit_bytes)
+{
+    return (size_t)((rows + 15) / 16) * 16 * (size_t)(cols / 32) * unit_bytes;
+}
+
+int nmo_to_tiled(const uint8_t *rowmajor, int rows, int cols, size_t unit_bytes, uint8_t *tiled)
+{
+    if (!rowmajor || !tiled) return NMO_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || unit_bytes == 0) return NMO_ERR_DIM;
+    if (cols % 128 != 0) return NMO_ERR_PATTERN;
+    size_t stride = (size_t)(cols / 32) * unit_bytes;
+    memset(tiled, 0, nmo_tiled_bytes(rows, cols, unit_bytes));
+    for (int r = 0; r < rows; ++r)
+        for (size_t b = 0; b < stride; ++b)
+            tiled[tiled_offset((size_t)r, b, unit_bytes, (size_t)cols / 128)] = rowmajor[(size_t)r * stride + b];
+    return NMO_OK;
+}
+
+int nmo_from_tiled(const uint8_t *tiled, int rows, int cols, size_t unit_bytes, uint8_t *rowmajor)
+{
+    if (!rowmajor || !tiled) return NMO_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || unit_bytes == 0) return NMO_ERR_DIM;
+    if (cols % 128 != 0) return NMO_ERR_PATTERN;
+    size_t stride = (size_t)(cols / 32) * unit_bytes;
+    for (int r = 0; r < rows; ++r)
+        for (size_t b = 0; b < stride; ++b)
+            rowmajor[(size_t)r * stride + b] = tiled[tiled_offset((size_t)r, b, unit_bytes, (size_t)cols / 128)];
     return NMO_OK;
 }
 

@@ -116,7 +116,7 @@ def test_zero_group_and_errors():
     with pytest.raises(oracle.OracleError):
         oracle.admm_project(W, None, 2, 4, 8, 0)
     with pytest.raises(oracle.OracleError):
-        oracle.admm_project(W, None, 4, 4, 8, 1)
+        oracle.admm_project(W, None, 5, 4, 8, 1)
     bad = W.copy()
     bad[0, 0] = np.inf
     with pytest.raises(oracle.OracleError):

@@ -1,7 +1,9 @@
 """Pins for the oracle's requantised layer output (Eq. 4 then Eq. 5 with o = 0, 8-bit activations
-of Sec. 5.3): the same chain of operations in exact rational arithmetic with every fp32 rounding
-applied explicitly (a different mechanism from the C code's float arithmetic), half-way and
-saturation cases, the int32 -> fp32 conversion, and the single rounding of the fused multiply-add."""
+of Sec. 5.3): the definition in exact rational arithmetic (the value of Eq. 4 rounded once to
+fp32, the quotient of Eq. 5 rounded once to fp32, then to the nearest integer, ties to even - a
+different mechanism from the C code's floating-point operations), half-way and saturation cases,
+the single rounding of the dequantised value, and agreement with the separately pinned weight
+quantiser and dequantiser."""
 from fractions import Fraction
 
 import numpy as np
@@ -18,8 +20,9 @@ def round_half_even(x: Fraction) -> int:
     return f
 
 
-def rn32(x: Fraction) -> Fraction:
-    """x rounded to the nearest fp32 number, ties to even (normal range, which is all these tests use)."""
+def rn(x: Fraction, sig: int) -> Fraction:
+    """x rounded to the nearest binary floating-point number with a `sig`-bit significand, ties to
+    even (normal range, which is all these tests use)."""
     if x == 0:
         return Fraction(0)
     sign = -1 if x < 0 else 1
@@ -32,8 +35,12 @@ def rn32(x: Fraction) -> Fraction:
         x *= 2
         e -= 1
     assert -126 <= e <= 127
-    m = round_half_even(x * (1 << 23))          # 24-bit significand
-    return sign * Fraction(m, 1 << 23) * (Fraction(2) ** e)
+    m = round_half_even(x * (1 << (sig - 1)))
+    return sign * Fraction(m, 1 << (sig - 1)) * (Fraction(2) ** e)
+
+
+def rn32(x: Fraction) -> Fraction:
+    return rn(x, 24)
 
 
 def F(v) -> Fraction:
@@ -41,19 +48,20 @@ def F(v) -> Fraction:
 
 
 def expected(acc, act_scale, scales, bias, out_scale):
-    """The definition, step by step, in exact arithmetic with explicit fp32 roundings."""
+    """Eq. 4, then Eq. 5, in exact arithmetic.  The dequantised value is rounded to fp32 once;
+    on the way the oracle holds it in double, whose own roundings (53 bits) are applied too, so
+    that a value next to an fp32 rounding boundary is decided as the C code decides it."""
     q = np.zeros(acc.shape, np.int64)
-    zmax = Fraction(0)
-    for o in range(acc.shape[1]):
-        p = rn32(F(act_scale) * F(scales[o]))
-        g = rn32(p / F(out_scale))
-        h = rn32(F(bias[o]) / F(out_scale)) if bias is not None else Fraction(0)
-        for t in range(acc.shape[0]):
-            a = rn32(Fraction(int(acc[t, o])))              # int32 -> fp32
-            z = rn32(a * g + h)                             # fused: one rounding
-            zmax = max(zmax, abs(z))
-            q[t, o] = min(127, max(-127, round_half_even(z)))
-    return q, float(rn32(zmax * F(out_scale)))
+    ymax = Fraction(0)
+    for t in range(acc.shape[0]):
+        for o in range(acc.shape[1]):
+            y = rn(rn(Fraction(int(acc[t, o])) * F(act_scale), 53) * F(scales[o]), 53)
+            if bias is not None:
+                y = rn(y + F(bias[o]), 53)
+            y = rn32(y)
+            ymax = max(ymax, abs(y))
+            q[t, o] = min(127, max(-127, round_half_even(rn32(y / F(out_scale)))))
+    return q, float(ymax)
 
 
 def test_random_cases_against_exact_arithmetic_with_explicit_roundings():
@@ -107,11 +115,11 @@ def test_int32_to_fp32_conversion_rounds_to_nearest_even():
     assert amax == float((1 << 24) + 4)
 
 
-def test_multiply_add_is_fused_one_rounding():
-    # acc * g = 4097 * (1 + 2^-12) = 4098 + 2^-12 exactly, which fp32 cannot hold (25 bits); a
-    # separately rounded product is 4098 (or 4098 + 2^-11) and the sum with -4098 then 0 (or 2^-11).
-    # Fused, the sum is 2^-12 exactly.  With out_scale 2^-13 (a power of two: g and h scale exactly)
-    # that is code 2; the unfused results would be 0 or 4.
+def test_product_and_bias_are_summed_before_the_single_rounding():
+    # acc * s = 4097 * (1 + 2^-12) = 4098 + 2^-12 exactly, which fp32 cannot hold (25 bits); a
+    # product rounded to fp32 on its own is 4098 (or 4098 + 2^-11) and the sum with -4098 then 0
+    # (or 2^-11).  Formed in double and rounded once, the sum is 2^-12 exactly.  With out_scale
+    # 2^-13 that is code 2; the separately rounded results would be 0 or 4.
     p = np.float32(1.0 + 2.0 ** -12)
     q, amax = oracle.requant(np.array([[4097]], np.int32), 1.0, np.array([p], np.float32), 2.0 ** -13,
                              np.array([-4098.0], np.float32))
@@ -119,10 +127,10 @@ def test_multiply_add_is_fused_one_rounding():
     assert amax == 2.0 ** -12
 
 
-def test_close_to_the_weight_quantiser_on_the_dequantised_value():
-    # Eq. 5 is one function: the codes must be those the (separately pinned) weight quantiser gives
-    # for the dequantised value and the same scale at 8 bits, up to the one-step difference that
-    # folding the division into the column constants can make next to a half-way point.
+def test_is_the_weight_quantiser_applied_to_the_dequantised_value():
+    # Eq. 5 is one function: the codes are those the (separately pinned) weight quantiser gives for
+    # the (separately pinned) dequantised value and the same scale at 8 bits, entry by entry, and
+    # the statistic is the largest magnitude of that dequantised value.
     rng = np.random.default_rng(11)
     acc = rng.integers(-3_000_000, 3_000_000, size=(4, 33)).astype(np.int32)
     scales = (rng.random(33) * 1e-4 + 2e-5).astype(np.float32)
@@ -130,15 +138,11 @@ def test_close_to_the_weight_quantiser_on_the_dequantised_value():
     sx, so = np.float32(0.0123), np.float32(0.0371)
     q, amax = oracle.requant(acc, sx, scales, so, bias)
     f32, _ = oracle.dequant(acc, sx, scales, bias)
-    differ = 0
     for t in range(4):
         for o in range(33):
-            want = oracle.quantize_one(float(f32[t, o]), float(so), 8)
-            assert abs(int(q[t, o]) - want) <= 1
-            differ += int(q[t, o]) != want
-    assert differ <= 2
+            assert int(q[t, o]) == oracle.quantize_one(float(f32[t, o]), float(so), 8)
     assert np.count_nonzero(np.abs(q.astype(int)) < 127) > 60      # most codes inside the range: the comparison means something
-    assert abs(amax - np.abs(f32).max()) <= np.abs(f32).max() * 2.0 ** -21
+    assert amax == float(np.abs(f32).max())
 
 
 def test_rejects_bad_scale():
