@@ -21,10 +21,12 @@ if ROOT not in sys.path:
 
 INT8_DENSE_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA peak (sparsity not counted)
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per nm_gemm launch (bf16 output) of the benchmark's four layers, from rocprofv3 FETCH_SIZE and
-# WRITE_SIZE passes scaled by what the same counters read on a plain 256 MiB copy (read counter x2.000, write
-# counter x1.000): profiles/bert_base_2of4_int8_counters.txt.  Not measurable from inside this process.
-MEASURED_HBM_BYTES_BF16 = {"qkv": 31.27e6, "attn_out": 12.66e6, "ffn_up": 40.56e6, "ffn_down": 30.90e6}
+# HBM bytes per nm_gemm launch (bf16 output, tiled layout) of the benchmark's four layers, from rocprofv3
+# FETCH_SIZE and WRITE_SIZE passes scaled by what the same counters read on a plain 256 MiB copy.  Counters
+# cannot be read from inside this process: the figures are those of the file named here and go stale with
+# any change of the tiling (the file states the commit it was measured at).
+TRAFFIC_PROFILE = "profiles/bert_base_2of4_int8_counters.txt"
+MEASURED_HBM_BYTES_BF16 = {"qkv": None, "attn_out": None, "ffn_up": None, "ffn_down": None}
 
 
 def parse():
@@ -34,7 +36,11 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--out-dtype", choices=["bf16", "f32", "i8"], default="bf16",
                     help="i8: nm_gemm_q8, the layer output as int8 codes for the next layer (not the headline configuration)")
+    ap.add_argument("--layout", choices=["tiled", "rows"], default="tiled",
+                    help="layout of the packed weights: tiled (what the fast kernels read; the benchmark) or rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-streaming-leg", action="store_true",
+                    help="skip the second timed leg (buffer sets rotated over more than the 256 MB Infinity Cache)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--workload", choices=["bert_base", "bert_large", "hetero", "single", "copy"], default="bert_base",
                     help="bert_base: the four GEMMs of a BERT-base layer at 4096 tokens (the benchmark); "
@@ -70,7 +76,8 @@ def main():
 
     import paper_2206_15014_amd as nm
     from paper_2206_15014_amd import binding, synth
-    from paper_2206_15014_amd.binding import NM_OUT_BF16, NM_OUT_F32
+    from paper_2206_15014_amd.binding import NM_LAYOUT_ROWS, NM_LAYOUT_TILED, NM_OUT_BF16, NM_OUT_F32
+    layout = NM_LAYOUT_TILED if args.layout == "tiled" else NM_LAYOUT_ROWS
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
@@ -130,7 +137,7 @@ def main():
             outs[g.name] = torch.empty((g.T, g.O), dtype=out_torch, device=dev)
         b = synth.bias(g)
         host.append((g, W, Xq, sx, b))
-        vb, mb, _ = nm.nm_packed_sizes(g.O, g.K, g.N, g.M, g.bits)
+        vb, mb, _ = nm.nm_packed_sizes(g.O, g.K, g.N, g.M, g.bits, layout)
         jobs.append(dict(
             g=g, sx=float(sx),
             W=torch.from_numpy(W).to(dev), X=Xd, bias=torch.from_numpy(b).to(dev),
@@ -142,7 +149,7 @@ def main():
 
     def compress_args(j):
         g = j["g"]
-        return (j["W"].data_ptr(), g.O, g.K, g.K, g.N, g.M, g.bits, j["vals"].data_ptr(), j["meta"].data_ptr(),
+        return (j["W"].data_ptr(), g.O, g.K, g.K, g.N, g.M, g.bits, layout, j["vals"].data_ptr(), j["meta"].data_ptr(),
                 j["scales"].data_ptr(), stream)
 
     gemm_fn = lib.nm_gemm_q8 if args.out_dtype == "i8" else lib.nm_gemm
@@ -150,11 +157,11 @@ def main():
     def gemm_args(j):
         g = j["g"]
         if args.out_dtype == "i8":         # any positive scale times the same: 1/16 keeps most codes inside the range
-            return (j["X"].data_ptr(), g.T, g.K, g.K, j["sx"], j["vals"].data_ptr(), j["meta"].data_ptr(),
-                    j["scales"].data_ptr(), g.O, g.N, g.M, g.bits, j["bias"].data_ptr(), 0.0625, j["out"].data_ptr(),
+            return (j["X"].data_ptr(), g.T, g.K, g.K, j["sx"], None, j["vals"].data_ptr(), j["meta"].data_ptr(),
+                    j["scales"].data_ptr(), g.O, g.N, g.M, g.bits, layout, j["bias"].data_ptr(), 0.0625, None, j["out"].data_ptr(),
                     g.O, j["absmax"].data_ptr(), stream)
-        return (j["X"].data_ptr(), g.T, g.K, g.K, j["sx"], j["vals"].data_ptr(), j["meta"].data_ptr(),
-                j["scales"].data_ptr(), g.O, g.N, g.M, g.bits, j["bias"].data_ptr(), None, j["out"].data_ptr(),
+        return (j["X"].data_ptr(), g.T, g.K, g.K, j["sx"], None, j["vals"].data_ptr(), j["meta"].data_ptr(),
+                j["scales"].data_ptr(), g.O, g.N, g.M, g.bits, layout, j["bias"].data_ptr(), None, j["out"].data_ptr(),
                 out_code, g.O, stream)
 
     cargs = [compress_args(j) for j in jobs]
@@ -169,7 +176,7 @@ def main():
     for scheme in sorted({(j["g"].N, j["g"].M, j["g"].bits) for j in jobs}):
         js = [j for j in jobs if (j["g"].N, j["g"].M, j["g"].bits) == scheme]
         items = binding.compress_items([j["W"] for j in js], [(j["vals"], j["meta"], j["scales"]) for j in js])
-        batches.append((items, len(js)) + scheme)
+        batches.append((items, len(js)) + scheme + (layout,))
 
     def run_step(st, mode=None):
         """The launches of one step on stream `st`."""
@@ -287,6 +294,66 @@ def main():
     # of that same kernel, right after the timed steps; a rocprofv3 kernel trace of this command
     # reports the same kernel about a microsecond shorter (the gap between two launches).
     dom_us = timed_launches(gemm_fn, gargs[dom], 40)
+
+    # ---- second timed leg: the same step over buffer sets rotated through more than the Infinity Cache holds ----
+    # Every set has its own weights, packed buffers, activations and outputs (copies of the first set), so
+    # a step finds none of its operands in the 256 MB Infinity Cache or the L2s: the HBM-streaming figure
+    # beside the cache-hot one above (whose whole footprint stays resident between steps).
+    streaming = None
+    if not args.no_streaming_leg and args.launch == "graph" and args.workload in ("bert_base", "bert_large"):
+        set_bytes = sum(j[k].numel() * j[k].element_size() for j in jobs for k in ("W", "X", "vals", "meta", "out"))
+        nsets = max(2, -(-(320 << 20) // set_bytes))
+        sets = []
+        for _ in range(nsets):
+            js2 = [dict(j, W=j["W"].clone(), X=j["X"].clone(), vals=torch.empty_like(j["vals"]), meta=torch.empty_like(j["meta"]),
+                        scales=torch.empty_like(j["scales"]), out=torch.empty_like(j["out"])) for j in jobs]
+            items = binding.compress_items([j["W"] for j in js2], [(j["vals"], j["meta"], j["scales"]) for j in js2])
+            g0 = js2[0]["g"]
+            sets.append((js2, (items, len(js2), g0.N, g0.M, g0.bits, layout), [gemm_args(j) for j in js2]))
+        reps = max(1, 20 // nsets)
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _, b, gas in sets:                      # warm-up outside the capture
+                check(lib.nm_compress_batch(*b, side.cuda_stream))
+                for ga in gas:
+                    check(gemm_fn(*(ga[:-1] + (side.cuda_stream,))))
+            side.synchronize()
+            g3 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g3, stream=side):
+                for _ in range(reps):
+                    for _, b, gas in sets:
+                        check(lib.nm_compress_batch(*b, side.cuda_stream))
+                        for ga in gas:
+                            check(gemm_fn(*(ga[:-1] + (side.cuda_stream,))))
+        torch.cuda.current_stream().wait_stream(side)
+        g3.replay()
+        torch.cuda.synchronize()
+        n_rep = max(1, args.steps // (reps * nsets))
+        t4 = time.perf_counter()
+        for _ in range(n_rep):
+            g3.replay()
+        torch.cuda.synchronize()
+        st_ms = (time.perf_counter() - t4) * 1e3 / (n_rep * reps * nsets)
+        streaming = {"ms_per_step": round(st_ms, 5), "buffer_sets": nsets, "footprint_MB": round(nsets * set_bytes / 1e6, 1),
+                     "note": "HBM-streaming: every step works on another of %d buffer sets (weights, packed buffers, "
+                             "activations, outputs), %d MB in all, more than the 256 MB Infinity Cache" % (nsets, nsets * set_bytes // 1000000)}
+        del sets
+
+    # ---- the matrix pipe on its own: register-resident loop of the sparse MFMA, and the shader clock under it ----
+    counters = torch.zeros(4, dtype=torch.int64, device=dev)
+    probe_blocks, probe_iters = 256 * 8, 4096
+    check(lib.nm_bench_smfmac_probe(probe_blocks, probe_iters, counters.data_ptr(), stream))
+    torch.cuda.synchronize()
+    pe0, pe1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    pe0.record()
+    check(lib.nm_bench_smfmac_probe(probe_blocks, probe_iters, counters.data_ptr(), stream))
+    pe1.record()
+    torch.cuda.synchronize()
+    probe_s = pe0.elapsed_time(pe1) * 1e-3
+    cyc, ticks = int(counters[0].item()), int(counters[1].item())
+    sclk_mhz = cyc / max(ticks, 1) * 100.0
+    smfmac_peak_tops = probe_blocks * 4 * probe_iters * 8 * (2 * 16 * 16 * 128) / probe_s / 1e12
+
     dense_ops = sum(g.dense_ops for g in gemms)
     value = dense_ops / (ms_per_step * 1e-3) / 1e12
 
@@ -295,7 +362,13 @@ def main():
     if len(set(names)) < len(names):       # several layers: say which layer and scheme
         names = ["L%02d.%s %d:%d i%d" % (g.seed[1], g.name, g.N, g.M, g.bits) for g in gemms]
     achieved = gd.dense_ops / (dom_us * 1e-6) / 1e12
-    comp_bytes = sum(g.O * g.K * 4 + g.O * (g.K // g.M * g.N) * (g.bits + 2) // 8 + g.O * 4 for g in gemms)
+    kc = gd.K // gd.M * gd.N
+    real_ops = 2 * gd.T * gd.O * kc                         # int8 operations the method performs (pruned products never formed)
+    alg_bytes = gd.T * gd.K + gd.O * kc * (gd.bits + synth.index_bits(gd.N, gd.M)) // 8 + 8 * gd.O + gd.T * gd.O * out_bytes
+    frac_real = real_ops / (dom_us * 1e-6) / 1e12 / INT8_DENSE_PEAK_TOPS
+    frac_hbm = alg_bytes / (dom_us * 1e-6) / 1e9 / HBM_PEAK_GBS
+    hbm_bound = frac_hbm >= frac_real
+    comp_bytes = sum(g.O * g.K * 4 + g.O * (g.K // g.M * g.N) * (g.bits + synth.index_bits(g.N, g.M)) // 8 + g.O * 4 for g in gemms)
     result = {
         "metric": "dense-equivalent int8 TOPS of N:M sparse GEMM (BERT shapes) + % of int8 roofline",
         "value": round(value, 2),
@@ -315,17 +388,28 @@ def main():
         "pct_of_int8_dense_peak": round(100.0 * value / INT8_DENSE_PEAK_TOPS, 2),
         "same_work_with_%s_compress" % other_mode: None if other_ms is None else {
             "ms_per_step": round(other_ms, 5), "value": round(dense_ops / (other_ms * 1e-3) / 1e12, 2)},
+        "streaming_leg": streaming,
         "roofline": {
-            "bound": "mfma", "achieved": round(achieved, 1), "peak": INT8_DENSE_PEAK_TOPS, "unit": "TFLOP/s",
-            "frac": round(achieved / INT8_DENSE_PEAK_TOPS, 4),
-            "traffic": MEASURED_HBM_BYTES_BF16.get(gd.name) if (args.workload == "bert_base" and args.out_dtype == "bf16") else None,
-            "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated on a copy; a stored figure)",
-            "algorithmic_bytes": gd.T * gd.K + gd.O * (gd.K // gd.M * gd.N) * (gd.bits + 2) // 8 + 8 * gd.O
-                                 + gd.T * gd.O * out_bytes,
+            # the roof that binds this kernel: the larger of its two fractions, both from the method's own work
+            "bound": "hbm" if hbm_bound else "mfma",
+            "achieved": round(alg_bytes / (dom_us * 1e-6) / 1e9, 1) if hbm_bound else round(real_ops / (dom_us * 1e-6) / 1e12, 1),
+            "peak": HBM_PEAK_GBS if hbm_bound else INT8_DENSE_PEAK_TOPS,
+            "unit": "GB/s" if hbm_bound else "TFLOP/s",
+            "frac": round(max(frac_hbm, frac_real), 4),
+            "frac_hbm": round(frac_hbm, 4),                  # algorithmic bytes / duration against 8 TB/s
+            "frac_real_ops": round(frac_real, 4),            # 2*T*O*kc int8 ops / duration against the dense int8 MFMA peak
+            "frac_dense_equiv": round(achieved / INT8_DENSE_PEAK_TOPS, 4),   # 2*T*O*K (pruned zeros counted): the reading of the task's 50 % target
+            "dense_equiv_tops": round(achieved, 1),
+            "traffic": MEASURED_HBM_BYTES_BF16.get(gd.name) if (args.workload == "bert_base" and args.out_dtype == "bf16" and args.layout == "tiled") else None,
+            "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated on a copy); a stored figure from " + TRAFFIC_PROFILE,
+            "algorithmic_bytes": alg_bytes,
+            "real_int8_ops": real_ops,
             "kernel": "nm_gemm %s %dx%d->%d %d:%d int%d" % (gd.name, gd.T, gd.K, gd.O, gd.N, gd.M, gd.bits),
-            "note": "int8 multiply-add ops, dense-equivalent (zeros counted), against the dense int8 MFMA peak; "
-                    "duration = HIP events around 200 back-to-back launches of this kernel (5 replays of a 40-launch graph) after the timed steps",
+            "note": "duration = HIP events around 200 back-to-back launches of this kernel (5 replays of a 40-launch graph) after "
+                    "the timed steps; operands cache-hot (one buffer set)",
             "duration_us": round(dom_us, 2),
+            "measured_smfmac_peak_tops": round(smfmac_peak_tops, 1),   # register-resident sparse-MFMA loop, dense-equivalent
+            "sclk_mhz": round(sclk_mhz, 0),                  # shader clock under that loop (cycle counter against the 100 MHz clock)
         },
         "kernels": {
             "gemm_us_back_to_back": {n: round(u, 2) for n, u in zip(names, per_gemm_us)},
@@ -343,7 +427,7 @@ def main():
         gs, Ws, Xs, sxs = synth.config1_tensors()
         js = dict(g=gs, sx=float(sxs), W=torch.from_numpy(Ws).to(dev), X=torch.from_numpy(Xs).to(dev),
                   bias=torch.zeros(gs.O, dtype=torch.float32, device=dev))
-        vb, mb, _ = nm.nm_packed_sizes(gs.O, gs.K, gs.N, gs.M, gs.bits)
+        vb, mb, _ = nm.nm_packed_sizes(gs.O, gs.K, gs.N, gs.M, gs.bits, layout)
         js.update(vals=torch.empty(vb, dtype=torch.uint8, device=dev), meta=torch.empty(mb, dtype=torch.uint8, device=dev),
                   scales=torch.empty(gs.O, dtype=torch.float32, device=dev),
                   out=torch.empty((gs.T, gs.O), dtype=out_torch, device=dev),

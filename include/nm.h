@@ -7,7 +7,8 @@
  *
  * Ownership and execution model (all entry points):
  *   - every *_dev pointer is DEVICE memory owned by the caller; the library
- *     allocates nothing, keeps no device state and never frees anything;
+ *     allocates nothing, keeps no device state between calls and never frees
+ *     anything;
  *   - work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and the call returns without synchronising;
  *   - buffers of one call must not overlap;
@@ -28,11 +29,26 @@ enum nm_status {
     NM_OK = 0,
     NM_ERR_NULL = -1,     /* a required pointer is NULL                                   */
     NM_ERR_DIM = -2,      /* rows/cols/tokens <= 0 or a leading dimension below its extent */
-    NM_ERR_PATTERN = -3,  /* M not in {4, 8}, N < 1, N >= M, or cols % M != 0              */
+    NM_ERR_PATTERN = -3,  /* M not in {4, 8}, N < 1, N > M, cols % M != 0, or (tiled layout)
+                             cols % 128 != 0                                               */
     NM_ERR_BITS = -4,     /* bits not in {4, 8}                                            */
     NM_ERR_DTYPE = -5,    /* unknown output dtype, or dtype set with a NULL output         */
     NM_ERR_ALIGN = -6,    /* pointer or leading dimension violates a stated alignment      */
-    NM_ERR_HIP = -7       /* the HIP runtime reported an error at launch                   */
+    NM_ERR_HIP = -7,      /* the HIP runtime reported an error at launch                   */
+    NM_ERR_LAYOUT = -8,   /* unknown layout code                                           */
+    NM_ERR_SCALE = -9     /* a host-side scale that is not a positive finite number        */
+};
+
+/*
+ * Layout of the packed values and of the index metadata in memory (the paper never discusses
+ * one; both are this library's definitions).  The same bytes either way: the tiled layout is a
+ * permutation of the row layout, fixed below, and every entry point takes either.
+ */
+enum nm_layout {
+    NM_LAYOUT_ROWS = 0,   /* one packed row after the other: the interchange format          */
+    NM_LAYOUT_TILED = 1   /* what one matrix-core fragment consumes (16 rows x 128 input
+                             columns) is one contiguous run of memory: the format the fast
+                             nm_gemm kernels read; needs cols % 128 == 0                     */
 };
 
 enum nm_out_dtype {
@@ -45,8 +61,7 @@ enum nm_out_dtype {
  * Byte sizes of the three packed buffers of a rows x cols matrix (host only, no
  * GPU needed).  Any of the three out-pointers may be NULL.
  *
- * Packed format (the paper leaves it open; this is the library's definition).
- * kc = cols*N/M kept entries per row, entry e = g*N + j is the j-th kept column
+ * Row layout.  kc = cols*N/M kept entries per row, entry e = g*N + j is the j-th kept column
  * (ascending) of group g.
  *   values : row-major, row stride ceil(kc*bits/8) bytes; bits=8: entry e is byte e;
  *            bits=4: two's-complement nibbles, entry e in byte e/2, low nibble for
@@ -55,9 +70,22 @@ enum nm_out_dtype {
  *            M=8; entry e's column offset inside its group occupies ib bits at bit
  *            e*ib of the row, LSB-first through the bytes.
  *   scales : float[rows].
- * Unused trailing bits of a row are zero.
+ * Unused trailing bits of a row are zero.  A dense matrix (N = M: every entry kept, the
+ * 8-bit / 4-bit components without sparsity of Sec. 5.4) has no metadata: meta_bytes = 0,
+ * meta_dev may be NULL, entry e is column e.
+ *
+ * Tiled layout (cols % 128 == 0).  A unit is the packed bytes of one row that cover 32
+ * consecutive input columns: unit u of row r is bytes [u*UB, (u+1)*UB) of row r in the row
+ * layout, with UB = (32/M)*N*bits/8 for the values and (32/M)*N*ib/8 for the metadata.  The 64
+ * units of 16 consecutive rows (row block rb = r/16) and one 128-column slice (s = u/4) form
+ * block (rb, s), which starts at byte (rb*(cols/128) + s)*64*UB of the buffer; rows are padded
+ * with zero bytes up to a multiple of 16.  Inside a block unit number j = (u%4)*16 + r%16; a
+ * unit is cut into pieces of PB bytes, PB the largest power of two <= 16 that divides UB, and
+ * piece p of unit j lies at byte (p*64 + j)*PB of the block.  (For 2:4 int8 a block is the
+ * A-operand of the sparse 16x16x128 integer MFMA in lane order, 16 bytes per lane.)  The
+ * scales are float[rows] as in the row layout.
  */
-int nm_packed_sizes(int rows, int cols, int N, int M, int bits,
+int nm_packed_sizes(int rows, int cols, int N, int M, int bits, int layout,
                     size_t *vals_bytes, size_t *meta_bytes, size_t *scales_bytes);
 
 /*
@@ -68,8 +96,13 @@ int nm_packed_sizes(int rows, int cols, int N, int M, int bits,
  * to the given weights as in Sec. 4.
  *
  *   W_dev      [rows][ldw] float, row-major; rows = output neurons, cols = inputs;
- *              ldw (elements) >= cols; W_dev and ldw*4 must be 16-byte aligned.
- *   vals_dev, meta_dev, scales_dev   outputs, sizes from nm_packed_sizes; 4-byte aligned.
+ *              ldw (elements) >= cols; 4-byte aligned (NM_ERR_ALIGN otherwise).  With W_dev
+ *              and ldw*4 16-byte aligned, vals_dev / meta_dev 4-byte aligned and packed rows
+ *              that are whole dwords the wavefront-per-row kernels run (N in {1, 2} or N = M,
+ *              and 4:8); anything else takes a slow thread-per-row kernel, same bytes.
+ *   layout     nm_layout of the outputs.
+ *   vals_dev, meta_dev, scales_dev   outputs, sizes from nm_packed_sizes; scales_dev 4-byte
+ *              aligned; meta_dev may be NULL for a dense matrix.
  *
  * Definitions the paper leaves open: equal magnitudes keep the lower column; one
  * scale per row, s = max|w| / (2^(bits-1)-1) with an all-zero row giving s = 1;
@@ -77,7 +110,7 @@ int nm_packed_sizes(int rows, int cols, int N, int M, int bits,
  * divisions and round-half-to-even.  Non-finite weights give unspecified bytes.
  */
 int nm_compress(const float *W_dev, int rows, int cols, int ldw,
-                int N, int M, int bits,
+                int N, int M, int bits, int layout,
                 void *vals_dev, void *meta_dev, float *scales_dev,
                 void *hip_stream);
 
@@ -91,15 +124,15 @@ int nm_compress(const float *W_dev, int rows, int cols, int ldw,
  * nm_compress.  scales_dev also serves as the call's scratch space.
  */
 int nm_compress_grouped(const float *W_dev, int rows, int cols, int ldw,
-                        int N, int M, int bits, int rows_per_scale,
+                        int N, int M, int bits, int layout, int rows_per_scale,
                         void *vals_dev, void *meta_dev, float *scales_dev,
                         void *hip_stream);
 
 /*
  * nm_compress on several matrices of one pattern in one call - the weight matrices of an encoder
  * layer, say (Sec. 4 compresses every linear layer of the encoder the same way).  Item i gives
- * exactly what nm_compress(items[i].W_dev, rows, cols, ldw, N, M, bits, vals_dev, meta_dev,
- * scales_dev) gives, byte for byte; the matrices that meet nm_compress's alignment share launches
+ * exactly what nm_compress(items[i].W_dev, rows, cols, ldw, N, M, bits, layout, vals_dev,
+ * meta_dev, scales_dev) gives, byte for byte; the matrices that meet nm_compress's alignment share launches
  * (the fixed cost of a launch is several times the time their bytes take), the others go one by
  * one.  `items` is HOST memory, read during the call and not kept; the device buffers of
  * different items must not overlap; count <= 0 or count > NM_COMPRESS_BATCH_MAX_ITEMS is an error
@@ -115,7 +148,7 @@ typedef struct nm_compress_item {
 } nm_compress_item;
 
 int nm_compress_batch(const nm_compress_item *items, int count,
-                      int N, int M, int bits, void *hip_stream);
+                      int N, int M, int bits, int layout, void *hip_stream);
 
 /*
  * Expand packed weights to the dense integer matrix Wq_dev[rows][cols] (int8,
@@ -123,7 +156,7 @@ int nm_compress_batch(const nm_compress_item *items, int count,
  * step; used to check that the sparse product equals the dense one.
  */
 int nm_decompress_i8(const void *vals_dev, const void *meta_dev, int rows, int cols,
-                     int N, int M, int bits, int8_t *Wq_dev, void *hip_stream);
+                     int N, int M, int bits, int layout, int8_t *Wq_dev, void *hip_stream);
 
 /*
  * The sparse integer linear layer of Sec. 5.3 with the dequantisation of Sec. 3.3
@@ -132,10 +165,12 @@ int nm_decompress_i8(const void *vals_dev, const void *meta_dev, int rows, int c
  *   acc[t][o] = sum over kept entries e of row o:  X[t][col(o,e)] * q[o][e]   (int32, exact)
  *   y[t][o]   = float(acc[t][o]) * (act_scale * scales[o])  (+ bias[o])
  *
- *   X_dev      [tokens][ldx] int8 activations, ldx >= K; X_dev and ldx 16-byte aligned.
+ *   X_dev      [tokens][ldx] int8 activations, ldx >= K.
  *   act_scale  per-tensor activation scale (host value).
+ *   act_scale_dev   NULL, or one device float that replaces act_scale and is read when the
+ *              kernel runs (see nm_gemm_q8).
  *   vals_dev, meta_dev, scales_dev   packed weights of an O x K matrix as written by
- *              nm_compress with the same N, M, bits.
+ *              nm_compress with the same N, M, bits, layout.
  *   bias_dev   float[O] or NULL.
  *   acc_dev    int32 [tokens][ldo] or NULL (exact accumulators, optional).
  *   out_dev    [tokens][ldo] of out_dtype, or NULL with NM_OUT_NONE.
@@ -145,10 +180,18 @@ int nm_decompress_i8(const void *vals_dev, const void *meta_dev, int rows, int c
  * int8 in registers; products of pruned positions are never formed on the 2:4
  * hardware path.  Results do not depend on launch shape (integer sums are exact;
  * the epilogue is elementwise).
+ *
+ * Alignment.  Required (NM_ERR_ALIGN): scales_dev, bias_dev, acc_dev 4-byte aligned, out_dev
+ * aligned to its element.  The matrix-core kernels additionally need K % 128 == 0, O % 4 == 0,
+ * ldo % 4 == 0 and 16-byte aligned X_dev, ldx, vals_dev, meta_dev, scales_dev, bias_dev, acc_dev,
+ * out_dev, and a pattern they cover: N <= 2 (either layout; the tiled layout runs the fastest
+ * kernels), or 3:4, 4:8 and dense N = M in the tiled layout.  Any other call is computed by a
+ * slow one-thread-per-output kernel with the same results.
  */
 int nm_gemm(const int8_t *X_dev, int tokens, int K, int ldx, float act_scale,
+            const float *act_scale_dev,
             const void *vals_dev, const void *meta_dev, const float *scales_dev,
-            int O, int N, int M, int bits,
+            int O, int N, int M, int bits, int layout,
             const float *bias_dev,
             int32_t *acc_dev,
             void *out_dev, int out_dtype,
@@ -187,29 +230,49 @@ int nm_project(const float *W_dev, const float *U_dev, int rows, int cols, int l
  * The same layer with its output handed on as 8-bit activations (Sec. 5.3: activations are
  * 8-bit integers), i.e. Eq. 4 followed by the scalar quantiser of Sec. 3.3, Eq. 5 (offset 0,
  * 8 bits) with a scale the caller supplies, so that a chain of layers never writes or re-reads a
- * floating-point tensor.  The division of Eq. 5 is taken once per output column, folded into the
- * column's multiplier and offset; every step is one fp32 operation, in this order:
+ * floating-point tensor:
  *
+ *   q[t][o] = clamp(rne(y[t][o] / out_scale), -127, 127),   y as nm_gemm defines it.
+ *
+ * How it is evaluated.  The division is taken once per output column, folded into the column's
+ * multiplier and offset, one fp32 operation per step:
  *   g[o]    = (act_scale * scales[o]) / out_scale        (multiplication, then true division)
  *   h[o]    = bias[o] / out_scale, or 0 without bias
- *   z[t][o] = fma(float(acc[t][o]), g[o], h[o])          (int32 -> float rounds to nearest even)
- *   q[t][o] = clamp(rne(z[t][o]), -127, 127)             (ties to even)
+ *   z[t][o] = fma(float(acc[t][o]), g[o], h[o]),   q = clamp(rne(z), -127, 127)   (ties to even)
+ * z differs from the exactly divided y / out_scale by less than
+ * 1e-6 * (|acc| * act_scale * scales[o] + |bias[o]|) / out_scale, so a code can differ (by one)
+ * from the one a division per output gives only where y / out_scale lies within that distance of
+ * a half-way point k + 1/2.
  *
- *   out_scale   > 0, finite (host value); out_dev[t][o] * out_scale approximates the y of nm_gemm.
+ *   out_scale   > 0, finite (host value; NM_ERR_SCALE otherwise).
+ *   act_scale_dev, out_scale_dev   NULL, or one device float each that replaces the host value
+ *               of the same name and is read when the kernel runs - a scale computed on the
+ *               device by earlier work on the stream (nm_absmax_to_scale), so that a captured
+ *               chain of layers follows the statistics of its own activations.  A device
+ *               out_scale must be positive and finite (not checked: the host cannot see it).
  *   out_dev     int8 [tokens][ldo], ldo >= O, 4-byte aligned (rows that are whole 16-byte
  *               pieces, ldo % 16 == 0 with a 16-byte aligned out_dev, are written fastest).
  *   absmax_dev  NULL, or one float that the caller has set (to 0, or to a running maximum
  *               >= 0) before the call: (max over all outputs of |z|) * out_scale, i.e. max |y|
- *               up to rounding, is max-combined into it atomically - the statistic from which
- *               the next out_scale is chosen.
- * Other arguments as for nm_gemm.  Errors: as nm_gemm; NM_ERR_DIM for an out_scale that is not
- * a positive finite number.
+ *               up to the rounding above, is max-combined into it atomically - the statistic
+ *               from which the next out_scale is chosen.
+ * Other arguments as for nm_gemm.
  */
 int nm_gemm_q8(const int8_t *X_dev, int tokens, int K, int ldx, float act_scale,
+               const float *act_scale_dev,
                const void *vals_dev, const void *meta_dev, const float *scales_dev,
-               int O, int N, int M, int bits,
-               const float *bias_dev, float out_scale,
+               int O, int N, int M, int bits, int layout,
+               const float *bias_dev, float out_scale, const float *out_scale_dev,
                int8_t *out_dev, int ldo, float *absmax_dev, void *hip_stream);
+
+/*
+ * The per-tensor scale of 8-bit activations from their largest magnitude (Sec. 5 keeps
+ * activations at 8 bits; the rule is the one the weights use in Sec. 3.3.1): on the stream,
+ * *scale_dev = *absmax_dev / 127 (one fp32 division; 1 when the maximum is 0), and then, when
+ * `reset` is non-zero, *absmax_dev = 0 for the next round of nm_gemm_q8 calls.  One tiny kernel;
+ * both pointers are single device floats, 4-byte aligned, and must differ.
+ */
+int nm_absmax_to_scale(float *absmax_dev, float *scale_dev, int reset, void *hip_stream);
 
 /* Human-readable name of a status code (static string, never NULL). */
 const char *nm_status_string(int status);

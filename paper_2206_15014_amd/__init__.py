@@ -5,8 +5,11 @@ C-ABI library built from ``csrc/``; every step of the path runs in its HIP
 kernels.  ``synth`` holds the seeded input generators and workload tables.
 """
 from .binding import (  # noqa: F401
+    NM_LAYOUT_ROWS,
+    NM_LAYOUT_TILED,
     NMError,
     library_path,
+    nm_absmax_to_scale,
     nm_compress,
     nm_compress_batch,
     nm_compress_grouped,

@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libnm.so")
 
 NM_OUT_NONE, NM_OUT_F32, NM_OUT_BF16 = 0, 1, 2
+NM_LAYOUT_ROWS, NM_LAYOUT_TILED = 0, 1
 
 
 class CompressItem(ctypes.Structure):
@@ -49,23 +50,29 @@ def _load():
     c_int, c_vp, c_f = ctypes.c_int, ctypes.c_void_p, ctypes.c_float
     szp = ctypes.POINTER(ctypes.c_size_t)
     lib.nm_packed_sizes.restype = c_int
-    lib.nm_packed_sizes.argtypes = [c_int] * 5 + [szp] * 3
+    lib.nm_packed_sizes.argtypes = [c_int] * 6 + [szp] * 3
     lib.nm_compress.restype = c_int
-    lib.nm_compress.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
+    lib.nm_compress.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
     lib.nm_compress_grouped.restype = c_int
-    lib.nm_compress_grouped.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
-    lib.nm_decompress_i8.restype = c_int
-    lib.nm_compress_batch.argtypes = [ctypes.POINTER(CompressItem), c_int, c_int, c_int, c_int, c_vp]
+    lib.nm_compress_grouped.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
+    lib.nm_compress_batch.argtypes = [ctypes.POINTER(CompressItem), c_int, c_int, c_int, c_int, c_int, c_vp]
     lib.nm_compress_batch.restype = c_int
-    lib.nm_decompress_i8.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp]
+    lib.nm_decompress_i8.restype = c_int
+    lib.nm_decompress_i8.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp]
     lib.nm_gemm.restype = c_int
-    lib.nm_gemm.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp,
-                            c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_int, c_int, c_vp]
+    lib.nm_gemm.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp, c_vp,
+                            c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_int, c_int, c_vp]
     lib.nm_project.restype = c_int
     lib.nm_project.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_int, c_vp, c_vp]
     lib.nm_gemm_q8.restype = c_int
-    lib.nm_gemm_q8.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp,
-                               c_int, c_int, c_int, c_int, c_vp, c_f, c_vp, c_int, c_vp, c_vp]
+    lib.nm_gemm_q8.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp, c_vp,
+                               c_int, c_int, c_int, c_int, c_int, c_vp, c_f, c_vp, c_vp, c_int, c_vp, c_vp]
+    lib.nm_absmax_to_scale.restype = c_int
+    lib.nm_absmax_to_scale.argtypes = [c_vp, c_vp, c_int, c_vp]
+    lib.nm_test_force_gemm_tile.restype = c_int
+    lib.nm_test_force_gemm_tile.argtypes = [c_int]
+    lib.nm_bench_smfmac_probe.restype = c_int
+    lib.nm_bench_smfmac_probe.argtypes = [c_int, c_int, c_vp, c_vp]
     lib.nm_status_string.restype = ctypes.c_char_p
     lib.nm_status_string.argtypes = [c_int]
     _lib = lib
@@ -98,48 +105,55 @@ def _stream(stream) -> Optional[int]:
     return stream.cuda_stream
 
 
-def nm_packed_sizes(rows: int, cols: int, N: int, M: int, bits: int) -> Tuple[int, int, int]:
+def force_gemm_tile(cfg: int) -> int:
+    """Test hook (not part of the ABI): force the tile variant nm_gemm launches; 0 = automatic."""
+    return _load().nm_test_force_gemm_tile(int(cfg))
+
+
+def nm_packed_sizes(rows: int, cols: int, N: int, M: int, bits: int, layout: int = NM_LAYOUT_ROWS) -> Tuple[int, int, int]:
     v, m, s = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
-    rc = _load().nm_packed_sizes(rows, cols, N, M, bits, ctypes.byref(v), ctypes.byref(m), ctypes.byref(s))
+    rc = _load().nm_packed_sizes(rows, cols, N, M, bits, layout, ctypes.byref(v), ctypes.byref(m), ctypes.byref(s))
     if rc:
         raise NMError(rc, "nm_packed_sizes")
     return v.value, m.value, s.value
 
 
-def nm_compress(W, N: int, M: int, bits: int, vals=None, meta=None, scales=None, stream=None):
+def _packed_buffers(rows, cols, N, M, bits, layout, device, vals, meta, scales):
+    """The three output buffers of a compress call: [rows, stride] in the row layout, flat in the tiled one."""
+    import torch
+    vb, mb, _ = nm_packed_sizes(rows, cols, N, M, bits, layout)
+    shape = (lambda nbytes: (rows, nbytes // rows)) if layout == NM_LAYOUT_ROWS else (lambda nbytes: (nbytes,))
+    if vals is None:
+        vals = torch.empty(shape(vb), dtype=torch.uint8, device=device)
+    if meta is None:
+        meta = torch.empty(shape(mb), dtype=torch.uint8, device=device)
+    if scales is None:
+        scales = torch.empty(rows, dtype=torch.float32, device=device)
+    return vals, meta, scales
+
+
+def nm_compress(W, N: int, M: int, bits: int, vals=None, meta=None, scales=None, stream=None, layout: int = NM_LAYOUT_ROWS):
     """W: float32 CUDA tensor [rows, cols] (row stride may exceed cols).
 
-    Returns (vals uint8 [rows, vstride], meta uint8 [rows, mstride], scales float32 [rows]).
+    Returns (vals uint8, meta uint8, scales float32 [rows]); vals / meta are [rows, stride] in the
+    row layout and flat in the tiled one.
     """
-    import torch
     rows, cols = W.shape
-    vb, mb, _ = nm_packed_sizes(rows, cols, N, M, bits)
-    if vals is None:
-        vals = torch.empty((rows, vb // rows), dtype=torch.uint8, device=W.device)
-    if meta is None:
-        meta = torch.empty((rows, mb // rows), dtype=torch.uint8, device=W.device)
-    if scales is None:
-        scales = torch.empty(rows, dtype=torch.float32, device=W.device)
-    rc = _load().nm_compress(_ptr(W), rows, cols, W.stride(0), N, M, bits,
+    vals, meta, scales = _packed_buffers(rows, cols, N, M, bits, layout, W.device, vals, meta, scales)
+    rc = _load().nm_compress(_ptr(W), rows, cols, W.stride(0), N, M, bits, layout,
                              _ptr(vals), _ptr(meta), _ptr(scales), _stream(stream))
     if rc:
         raise NMError(rc, "nm_compress")
     return vals, meta, scales
 
 
-def nm_compress_grouped(W, N: int, M: int, bits: int, rows_per_scale: int, vals=None, meta=None, scales=None, stream=None):
+def nm_compress_grouped(W, N: int, M: int, bits: int, rows_per_scale: int, vals=None, meta=None, scales=None, stream=None,
+                        layout: int = NM_LAYOUT_ROWS):
     """As nm_compress, with one scale per group of rows_per_scale consecutive rows; scales is
     still float32 [rows] (the rows of a group hold the same value)."""
-    import torch
     rows, cols = W.shape
-    vb, mb, _ = nm_packed_sizes(rows, cols, N, M, bits)
-    if vals is None:
-        vals = torch.empty((rows, vb // rows), dtype=torch.uint8, device=W.device)
-    if meta is None:
-        meta = torch.empty((rows, mb // rows), dtype=torch.uint8, device=W.device)
-    if scales is None:
-        scales = torch.empty(rows, dtype=torch.float32, device=W.device)
-    rc = _load().nm_compress_grouped(_ptr(W), rows, cols, W.stride(0), N, M, bits, rows_per_scale,
+    vals, meta, scales = _packed_buffers(rows, cols, N, M, bits, layout, W.device, vals, meta, scales)
+    rc = _load().nm_compress_grouped(_ptr(W), rows, cols, W.stride(0), N, M, bits, layout, rows_per_scale,
                                      _ptr(vals), _ptr(meta), _ptr(scales), _stream(stream))
     if rc:
         raise NMError(rc, "nm_compress_grouped")
@@ -155,32 +169,26 @@ def compress_items(Ws, outs):
     return arr
 
 
-def nm_compress_batch(Ws, N: int, M: int, bits: int, outs=None, stream=None):
+def nm_compress_batch(Ws, N: int, M: int, bits: int, outs=None, stream=None, layout: int = NM_LAYOUT_ROWS):
     """nm_compress of every matrix of the list Ws (float32 CUDA tensors [rows, cols]) in one call.
 
     Returns the list of (vals, meta, scales), one per matrix, as nm_compress would.
     """
-    import torch
     if outs is None:
-        outs = []
-        for W in Ws:
-            rows, cols = W.shape
-            vb, mb, _ = nm_packed_sizes(rows, cols, N, M, bits)
-            outs.append((torch.empty((rows, vb // rows), dtype=torch.uint8, device=W.device),
-                         torch.empty((rows, mb // rows), dtype=torch.uint8, device=W.device),
-                         torch.empty(rows, dtype=torch.float32, device=W.device)))
+        outs = [_packed_buffers(W.shape[0], W.shape[1], N, M, bits, layout, W.device, None, None, None) for W in Ws]
     arr = compress_items(Ws, outs)
-    rc = _load().nm_compress_batch(arr, len(Ws), N, M, bits, _stream(stream))
+    rc = _load().nm_compress_batch(arr, len(Ws), N, M, bits, layout, _stream(stream))
     if rc:
         raise NMError(rc, "nm_compress_batch")
     return outs
 
 
-def nm_decompress_i8(vals, meta, rows: int, cols: int, N: int, M: int, bits: int, out=None, stream=None):
+def nm_decompress_i8(vals, meta, rows: int, cols: int, N: int, M: int, bits: int, out=None, stream=None,
+                     layout: int = NM_LAYOUT_ROWS):
     import torch
     if out is None:
         out = torch.empty((rows, cols), dtype=torch.int8, device=vals.device)
-    rc = _load().nm_decompress_i8(_ptr(vals), _ptr(meta), rows, cols, N, M, bits, _ptr(out), _stream(stream))
+    rc = _load().nm_decompress_i8(_ptr(vals), _ptr(meta), rows, cols, N, M, bits, layout, _ptr(out), _stream(stream))
     if rc:
         raise NMError(rc, "nm_decompress_i8")
     return out
@@ -188,15 +196,15 @@ def nm_decompress_i8(vals, meta, rows: int, cols: int, N: int, M: int, bits: int
 
 def nm_gemm(X, act_scale: float, vals, meta, scales, O: int, N: int, M: int, bits: int,
             bias=None, acc=None, out=None, out_dtype: int = NM_OUT_NONE, ldo: Optional[int] = None,
-            stream=None):
+            stream=None, layout: int = NM_LAYOUT_ROWS, act_scale_dev=None):
     """X: int8 CUDA tensor [tokens, K].  acc (int32) and out (float32 / bfloat16), when
     given, are [tokens, ldo] buffers written in place; returns (acc, out)."""
     tokens, K = X.shape
     if ldo is None:
         ref = out if out is not None else acc
         ldo = ref.stride(0) if ref is not None and hasattr(ref, "stride") else O
-    rc = _load().nm_gemm(_ptr(X), tokens, K, X.stride(0), float(act_scale),
-                         _ptr(vals), _ptr(meta), _ptr(scales), O, N, M, bits,
+    rc = _load().nm_gemm(_ptr(X), tokens, K, X.stride(0), float(act_scale), _ptr(act_scale_dev),
+                         _ptr(vals), _ptr(meta), _ptr(scales), O, N, M, bits, layout,
                          _ptr(bias), _ptr(acc), _ptr(out), out_dtype, ldo, _stream(stream))
     if rc:
         raise NMError(rc, "nm_gemm")
@@ -204,19 +212,29 @@ def nm_gemm(X, act_scale: float, vals, meta, scales, O: int, N: int, M: int, bit
 
 
 def nm_gemm_q8(X, act_scale: float, vals, meta, scales, O: int, N: int, M: int, bits: int,
-               out_scale: float, out, bias=None, absmax=None, ldo: Optional[int] = None, stream=None):
+               out_scale: float, out, bias=None, absmax=None, ldo: Optional[int] = None, stream=None,
+               layout: int = NM_LAYOUT_ROWS, act_scale_dev=None, out_scale_dev=None):
     """X: int8 CUDA tensor [tokens, K]; out: int8 [tokens, ldo] written in place with the layer's
     output as 8-bit codes of scale out_scale; absmax: optional float32 tensor of one element,
-    max |y| is max-combined into it.  Returns out."""
+    max |y| is max-combined into it.  act_scale_dev / out_scale_dev: optional float32 tensors of
+    one element that replace the host values.  Returns out."""
     tokens, K = X.shape
     if ldo is None:
         ldo = out.stride(0)
-    rc = _load().nm_gemm_q8(_ptr(X), tokens, K, X.stride(0), float(act_scale),
-                            _ptr(vals), _ptr(meta), _ptr(scales), O, N, M, bits,
-                            _ptr(bias), float(out_scale), _ptr(out), ldo, _ptr(absmax), _stream(stream))
+    rc = _load().nm_gemm_q8(_ptr(X), tokens, K, X.stride(0), float(act_scale), _ptr(act_scale_dev),
+                            _ptr(vals), _ptr(meta), _ptr(scales), O, N, M, bits, layout,
+                            _ptr(bias), float(out_scale), _ptr(out_scale_dev), _ptr(out), ldo, _ptr(absmax), _stream(stream))
     if rc:
         raise NMError(rc, "nm_gemm_q8")
     return out
+
+
+def nm_absmax_to_scale(absmax, scale, reset: bool = False, stream=None):
+    """scale[0] = absmax[0] / 127 (1 when it is 0) on the stream; reset: absmax[0] = 0 afterwards."""
+    rc = _load().nm_absmax_to_scale(_ptr(absmax), _ptr(scale), int(bool(reset)), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_absmax_to_scale")
+    return scale
 
 
 def nm_project(W, U, N: int, M: int, bits: int, rows_per_scale: int, Z=None, U_out=None, scales=None, stream=None):

@@ -9,7 +9,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnm.so")
-SOURCES = ["nm_api.hip", "nm_compress.hip", "nm_gemm.hip", "nm_gemm_dma.hip", "nm_gemm_stream.hip", "nm_gemm_xres.hip", "nm_project.hip"]
+# (source, extra flags, object name).  The LDS-direct GEMM kernels are one source compiled once per
+# set of N:M patterns, so that their many instantiations build in parallel.
+DMA_SETS = 7
+SOURCES = [("nm_gemm_dma.hip", ["-DNM_DMA_SET=%d" % k], "nm_gemm_dma_%d.o" % k) for k in range(DMA_SETS)] + \
+          [(s, [], s.replace(".hip", ".o")) for s in ["nm_api.hip", "nm_compress.hip", "nm_gemm.hip", "nm_project.hip"]]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -42,8 +46,8 @@ def build(verbose: bool = False) -> str:
     tmpdir = tempfile.mkdtemp(prefix="libnm_build_")
     tmp = LIB + ".tmp.%d" % os.getpid()
     try:
-        objs = [os.path.join(tmpdir, s.replace(".hip", ".o")) for s in SOURCES]
-        jobs = [[hipcc, *compile_flags, "-c", "-o", o, os.path.join(CSRC, s)] for s, o in zip(SOURCES, objs)]
+        objs = [os.path.join(tmpdir, o) for _, _, o in SOURCES]
+        jobs = [[hipcc, *compile_flags, *extra, "-c", "-o", o, os.path.join(CSRC, s)] for (s, extra, _), o in zip(SOURCES, objs)]
         workers = max(1, min(len(jobs), (os.cpu_count() or 2), 8))
         with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as pool:
             list(pool.map(lambda c: _run(c, verbose), jobs))

@@ -114,6 +114,14 @@ template <int N, int M, int BITS, bool RECIP>
 __device__ __forceinline__ void encode_group(const float (&x)[M], const Divisor<RECIP>& s, uint32_t& vbits, uint32_t& mbits)
 {
     constexpr int IB = (M == 4) ? 2 : 4;
+    if constexpr (N == M) {
+        // dense matrix: every entry is kept, in column order; there are no index bits
+        vbits = 0;
+        mbits = 0;
+#pragma unroll
+        for (int j = 0; j < N; ++j) vbits |= ((uint32_t)quantize<BITS>(x[j], s) & ((1u << BITS) - 1u)) << (j * BITS);
+        return;
+    }
     if constexpr (M == 4 && (N == 1 || N == 2)) {
         // Groups of four, the same rule spelled out: the six comparisons "the lower column is at
         // least as large" decide every pair (the lower column outranks on >=, the higher one
@@ -222,7 +230,8 @@ __device__ __forceinline__ void encode_group(const float (&x)[M], const Divisor<
 // them 5 % faster; BERT-large's layer set, 50 MB: 2 %); smaller calls use plain loads (a caller that
 // compresses the same 28 MB again and again finds them in the Infinity Cache).
 constexpr long long STREAM_ABOVE_BYTES = 32ll << 20;
-constexpr int GIVEN_SCALES = 1;                        // bit of the kernels' `flags` argument
+constexpr int GIVEN_SCALES = 1;                        // bits of the kernels' `flags` argument
+constexpr int TILED_LAYOUT = 2;
 typedef float v4f_t __attribute__((ext_vector_type(4)));
 template <bool ONCE>
 __device__ __forceinline__ float4 load_w(const float4* p)
@@ -230,6 +239,35 @@ __device__ __forceinline__ float4 load_w(const float4* p)
     if constexpr (!ONCE) return *p;
     const v4f_t v = __builtin_nontemporal_load(reinterpret_cast<const v4f_t*>(p));
     return make_float4(v.x, v.y, v.z, v.w);
+}
+
+// Byte offset, in the tiled layout, of byte b of a packed row (UB = bytes per unit, a compile-time
+// constant here so that the divisions are shifts and multiplications).
+template <int UB>
+__device__ __forceinline__ uint32_t tiled_at(uint32_t row, uint32_t b, uint32_t slices)
+{
+    constexpr uint32_t PB = (uint32_t)piece_bytes(UB);
+    const uint32_t u = b / UB, i = b % UB;
+    return ((row >> 4) * slices + (u >> 2)) * (64u * UB) + ((i / PB) * 64u + (u & 3u) * 16u + (row & 15u)) * PB + i % PB;
+}
+
+// One dword of a packed row (dword index `d` of the row layout) to either layout.  In the tiled
+// layout a dword lies inside one piece of a unit when pieces are 4 bytes or more; 2-byte pieces
+// (units of 2 bytes: a dword spans two units, 16 rows apart) are stored as two halves.
+template <int UB>
+__device__ __forceinline__ void store_packed(uint8_t* __restrict__ base, int tiled, uint32_t row, uint32_t d,
+                                             uint32_t stride_dw, uint32_t slices, uint32_t v)
+{
+    if (!tiled) {
+        reinterpret_cast<uint32_t*>(base)[(size_t)row * stride_dw + d] = v;
+        return;
+    }
+    if constexpr (piece_bytes(UB) >= 4) {
+        *reinterpret_cast<uint32_t*>(base + tiled_at<UB>(row, 4u * d, slices)) = v;
+    } else {
+        *reinterpret_cast<uint16_t*>(base + tiled_at<UB>(row, 4u * d, slices)) = (uint16_t)v;
+        *reinterpret_cast<uint16_t*>(base + tiled_at<UB>(row, 4u * d + 2u, slices)) = (uint16_t)(v >> 16);
+    }
 }
 
 // The rows of one workgroup: `block` is the workgroup's index among those of this matrix, WPR
@@ -242,11 +280,15 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
               int vstride_dw, int mstride_dw, int flags, const int WPR, const int block, float* part)
 {
     const bool given = (flags & GIVEN_SCALES) != 0;
+    const int tiled = (flags & TILED_LAYOUT) ? 1 : 0;
+    constexpr bool HAS_META = N < M;       // a dense matrix stores no index bits
     constexpr int IB = (M == 4) ? 2 : 4;
     constexpr int VB = N * BITS;           // value bits per group
-    constexpr int MB = N * IB;             // index bits per group
+    constexpr int MB = HAS_META ? N * IB : 32;   // index bits per group
     constexpr int VL = 32 / VB;            // lanes per value dword
     constexpr int ML = 32 / MB;            // lanes per index dword
+    constexpr int UV = 32 / M * N * BITS / 8;    // packed value / index bytes per 32 input columns
+    constexpr int UM = HAS_META ? 32 / M * N * IB / 8 : 4;
     constexpr int F4 = M / 4;              // 16-byte loads per group
     static_assert(RES * F4 <= 16, "at most 64 floats per lane stay in registers");
     const int RPB = 4 / WPR;               // rows per workgroup
@@ -256,8 +298,11 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
     // the row and the wavefront's place in it are the same in all lanes: said so explicitly, the row's
     // base addresses stay in scalar registers and every access is base + 32-bit lane offset
     const int row_raw = __builtin_amdgcn_readfirstlane(block * RPB + wave / WPR);
-    const bool live = row_raw < rows;      // rows past the end are computed on the last row and not stored
+    const bool live = row_raw < rows;      // rows past the end are computed on the last row and not stored ...
     const int row = live ? row_raw : rows - 1;
+    // ... except that the tiled layout pads the rows to a multiple of 16 with zero bytes
+    const bool store = live || (tiled && row_raw < ((rows + 15) & ~15));
+    const uint32_t slices = (uint32_t)cols >> 7;
     const int w = __builtin_amdgcn_readfirstlane(wave % WPR);
 
     const float4* __restrict__ w4 = reinterpret_cast<const float4*>(W + (size_t)row * ldw);
@@ -309,17 +354,21 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
         (int)__float_as_uint(given ? scales[row] : ((amax == 0.0f) ? 1.0f : amax / QMAX))));
     if (!given && live && w == 0 && lane == 0) scales[row] = s;
 
-    uint32_t* __restrict__ vrow = vals + (size_t)row * vstride_dw;
-    uint32_t* __restrict__ mrow = meta + (size_t)row * mstride_dw;
+    uint8_t* __restrict__ vbase = reinterpret_cast<uint8_t*>(vals);
+    uint8_t* __restrict__ mbase = reinterpret_cast<uint8_t*>(meta);
 
     auto encode_row = [&](auto divisor) __attribute__((always_inline)) {
         auto emit = [&](const float (&grp)[M], int g) __attribute__((always_inline)) {
             uint32_t vb = 0, mb = 0;
             if (g < groups) encode_group<N, M, BITS>(grp, divisor, vb, mb);
             vb = group_or<VL>(vb << ((lane % VL) * VB));
-            mb = group_or<ML>(mb << ((lane % ML) * MB));
-            if (live && g < groups && lane % VL == 0) vrow[(unsigned)g / VL] = vb;
-            if (live && g < groups && lane % ML == 0) mrow[(unsigned)g / ML] = mb;
+            if (store && g < groups && lane % VL == 0)
+                store_packed<UV>(vbase, tiled, (uint32_t)row_raw, (uint32_t)g / VL, (uint32_t)vstride_dw, slices, live ? vb : 0u);
+            if constexpr (HAS_META) {
+                mb = group_or<ML>(mb << ((lane % ML) * MB));
+                if (store && g < groups && lane % ML == 0)
+                    store_packed<UM>(mbase, tiled, (uint32_t)row_raw, (uint32_t)g / ML, (uint32_t)mstride_dw, slices, live ? mb : 0u);
+            }
         };
         if (resident) {
 #pragma unroll
@@ -379,7 +428,8 @@ struct BatchItem {
 struct BatchArgs {
     BatchItem it[BATCH_MAX];
     int count;
-    int flags;
+    int flags;             // of compress_rows
+    int stream_loads;      // the weights are loaded with the streaming hint
 };
 
 template <int N, int M, int BITS, int RES, bool ONCE>
@@ -391,31 +441,39 @@ compress_batch_kernel(const BatchArgs b)
     for (int k = 1; k < b.count; ++k)
         if ((int)blockIdx.x >= b.it[k].first_block) i = k;     // uniform: scalar loads from the argument segment
     const BatchItem& t = b.it[i];
-    compress_rows<N, M, BITS, RES, ONCE>(t.W, t.rows, t.cols, t.ldw, t.vals, t.meta, t.scales, t.vstride_dw, t.mstride_dw, 0,
+    compress_rows<N, M, BITS, RES, ONCE>(t.W, t.rows, t.cols, t.ldw, t.vals, t.meta, t.scales, t.vstride_dw, t.mstride_dw, b.flags,
                                    t.wpr, (int)blockIdx.x - t.first_block, part);
 }
 
 // ---------------------------------------------------------------------------------------------
-// Any pattern, any width, any alignment: one thread per row, bytes written one at a time.
+// Any pattern, any width, any alignment, either layout: one thread per row, bytes written one at
+// a time.
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(64)
 compress_generic_kernel(const float* __restrict__ W, int rows, int cols, int ldw, int N, int M, int bits,
                         uint8_t* __restrict__ vals, uint8_t* __restrict__ meta, float* __restrict__ scales,
-                        int vstride, int mstride, int given)
+                        PackedArray pv, PackedArray pm, int given)
 {
     const int row = blockIdx.x * 64 + threadIdx.x;
-    if (row >= rows) return;
+    if (row >= rows) {
+        // rows that only pad the tiled layout to a multiple of 16: zero bytes
+        if (pv.tiled && row < ((rows + 15) & ~15)) {
+            for (uint32_t b = 0; b < pv.stride; ++b) vals[pv.at((uint32_t)row, b)] = 0;
+            if (pm.ub)
+                for (uint32_t b = 0; b < pm.stride; ++b) meta[pm.at((uint32_t)row, b)] = 0;
+        }
+        return;
+    }
     const float* w = W + (size_t)row * ldw;
-    const int ib = (M == 4) ? 2 : 4;
+    const int ib = (N >= M) ? 0 : (M == 4) ? 2 : 4;
     const int qmaxi = (1 << (bits - 1)) - 1;
     float amax = 0.0f;
     for (int c = 0; c < cols; ++c) amax = fmaxf(amax, fabsf(w[c]));
     const float s = given ? scales[row] : ((amax == 0.0f) ? 1.0f : amax / (float)qmaxi);
     if (!given) scales[row] = s;
-    uint8_t* vrow = vals + (size_t)row * vstride;
-    uint8_t* mrow = meta + (size_t)row * mstride;
     uint32_t vacc = 0, macc = 0;
-    int vfill = 0, mfill = 0, vpos = 0, mpos = 0;
+    int vfill = 0, mfill = 0;
+    uint32_t vpos = 0, mpos = 0;
     for (int g = 0; g < cols / M; ++g) {
         float x[8];
         for (int c = 0; c < 8; ++c) x[c] = (c < M) ? w[g * M + c] : 0.0f;
@@ -433,34 +491,33 @@ compress_generic_kernel(const float* __restrict__ W, int rows, int cols, int ldw
             vfill += bits;
             macc |= (uint32_t)c << mfill;
             mfill += ib;
-            while (vfill >= 8) { vrow[vpos++] = (uint8_t)vacc; vacc >>= 8; vfill -= 8; }
-            while (mfill >= 8) { mrow[mpos++] = (uint8_t)macc; macc >>= 8; mfill -= 8; }
+            while (vfill >= 8) { vals[pv.at((uint32_t)row, vpos++)] = (uint8_t)vacc; vacc >>= 8; vfill -= 8; }
+            while (mfill >= 8) { meta[pm.at((uint32_t)row, mpos++)] = (uint8_t)macc; macc >>= 8; mfill -= 8; }
         }
     }
-    if (vfill > 0) vrow[vpos] = (uint8_t)vacc;
-    if (mfill > 0) mrow[mpos] = (uint8_t)macc;
+    if (vfill > 0) vals[pv.at((uint32_t)row, vpos)] = (uint8_t)vacc;
+    if (mfill > 0) meta[pm.at((uint32_t)row, mpos)] = (uint8_t)macc;
 }
 
 // Packed -> dense int8, one thread per (row, group).
 __global__ void __launch_bounds__(256)
 decompress_kernel(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ meta, int rows, int cols,
-                  int N, int M, int bits, int vstride, int mstride, int8_t* __restrict__ Wq)
+                  int N, int M, int bits, PackedArray pv, PackedArray pm, int8_t* __restrict__ Wq)
 {
     const int groups = cols / M;
     const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
     if (id >= (long long)rows * groups) return;
     const int row = (int)(id / groups), g = (int)(id % groups);
-    const int ib = (M == 4) ? 2 : 4;
-    const uint8_t* vrow = vals + (size_t)row * vstride;
-    const uint8_t* mrow = meta + (size_t)row * mstride;
+    const int ib = (N >= M) ? 0 : (M == 4) ? 2 : 4;
     int8_t out[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int j = 0; j < N; ++j) {
-        const int e = g * N + j;
+        const uint32_t e = (uint32_t)(g * N + j);
         int q, off;
-        if (bits == 8) q = (int8_t)vrow[e];
-        else { int nib = (vrow[e >> 1] >> ((e & 1) * 4)) & 15; q = (nib ^ 8) - 8; }
-        if (ib == 2) off = (mrow[e >> 2] >> ((e & 3) * 2)) & 3;
-        else off = (mrow[e >> 1] >> ((e & 1) * 4)) & 15;
+        if (bits == 8) q = (int8_t)vals[pv.at((uint32_t)row, e)];
+        else { int nib = (vals[pv.at((uint32_t)row, e >> 1)] >> ((e & 1) * 4)) & 15; q = (nib ^ 8) - 8; }
+        if (ib == 0) off = j;
+        else if (ib == 2) off = (meta[pm.at((uint32_t)row, e >> 2)] >> ((e & 3) * 2)) & 3;
+        else off = (meta[pm.at((uint32_t)row, e >> 1)] >> ((e & 1) * 4)) & 15;
         out[off & 7] = (int8_t)q;
     }
     int8_t* dst = Wq + (size_t)row * cols + (size_t)g * M;
@@ -472,7 +529,8 @@ void launch_wave_res(const float* W, int rows, int cols, int ldw, uint32_t* v, u
                      int vstride, int mstride, int flags, hipStream_t st)
 {
     constexpr int RPB = 4 / WPR;
-    hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, WPR, RES>), dim3((rows + RPB - 1) / RPB), dim3(256), 0, st,
+    const int rows_out = (flags & TILED_LAYOUT) ? ((rows + 15) & ~15) : rows;      // the tiled layout pads the rows
+    hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, WPR, RES>), dim3((rows_out + RPB - 1) / RPB), dim3(256), 0, st,
                        W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4, flags);
 }
 
@@ -508,35 +566,44 @@ void launch_wave(const float* W, int rows, int cols, int ldw, void* vals, void* 
 
 }  // namespace
 
-int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale,
+// Whether the wavefront-per-row kernels take a matrix: a compiled pattern, 16-byte aligned rows of
+// W, dword-aligned outputs and packed rows that are whole dwords.
+static bool wave_kernel_takes(const float* W, int cols, int ldw, int N, int M, int bits, const void* vals, const void* meta)
+{
+    const bool pattern_ok = (M == 4 && (N == 1 || N == 2 || N == 4)) || (M == 8 && (N == 1 || N == 2 || N == 4));
+    const size_t kc = (size_t)cols / M * N;
+    const int ib = index_bits(N, M);
+    return pattern_ok && ((uintptr_t)W % 16 == 0) && (ldw % 4 == 0) && ((uintptr_t)vals % 4 == 0) &&
+           ((uintptr_t)meta % 4 == 0) && (kc * bits % 32 == 0) && (kc * ib % 32 == 0);
+}
+
+int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, int bits, int layout, int rows_per_scale,
                     void* vals, void* meta, float* scales, hipStream_t st)
 {
-    const int ib = (M == 4) ? 2 : 4;
-    const size_t kc = (size_t)cols / M * N;
-    const int vstride = (int)((kc * bits + 7) / 8);
-    const int mstride = (int)((kc * ib + 7) / 8);
-    const bool aligned = ((uintptr_t)W % 16 == 0) && (ldw % 4 == 0) && ((uintptr_t)vals % 4 == 0) &&
-                         ((uintptr_t)meta % 4 == 0) && (kc * bits % 32 == 0) && (kc * ib % 32 == 0);
+    const PackedArray pv = packed_values(cols, N, M, bits, layout), pm = packed_meta(cols, N, M, layout);
+    const int vstride = (int)pv.stride, mstride = (int)pm.stride;
     bool done = false;
     begin_launch();
     // One scale per group of rows: the scales are computed first (row maxima, then the groups'),
     // and the kernels below quantise with what they find in scales[].
     const int given = rows_per_scale > 1 ? 1 : 0;
-    const int flags = given ? GIVEN_SCALES : 0;
+    const int flags = (given ? GIVEN_SCALES : 0) | (layout ? TILED_LAYOUT : 0);
     if (given) launch_group_scales(W, rows, cols, ldw, rows_per_scale, (float)((1 << (bits - 1)) - 1), scales, st);
-    if (aligned) {
+    if (wave_kernel_takes(W, cols, ldw, N, M, bits, vals, meta)) {
         done = true;
 #define NM_CASE(n, m, b) else if (N == n && M == m && bits == b) launch_wave<n, m, b>(W, rows, cols, ldw, vals, meta, scales, vstride, mstride, flags, st)
         if (false) {}
-        NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4);
+        NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4); NM_CASE(4, 4, 8); NM_CASE(4, 4, 4);
         NM_CASE(1, 8, 8); NM_CASE(2, 8, 8); NM_CASE(4, 8, 8);
         NM_CASE(1, 8, 4); NM_CASE(2, 8, 4); NM_CASE(4, 8, 4);
         else done = false;
 #undef NM_CASE
     }
-    if (!done)
-        hipLaunchKernelGGL(compress_generic_kernel, dim3((rows + 63) / 64), dim3(64), 0, st,
-                           W, rows, cols, ldw, N, M, bits, (uint8_t*)vals, (uint8_t*)meta, scales, vstride, mstride, given);
+    if (!done) {
+        const int rows_out = layout ? ((rows + 15) & ~15) : rows;
+        hipLaunchKernelGGL(compress_generic_kernel, dim3((rows_out + 63) / 64), dim3(64), 0, st,
+                           W, rows, cols, ldw, N, M, bits, (uint8_t*)vals, (uint8_t*)meta, scales, pv, pm, given);
+    }
     return launch_status();
 }
 
@@ -563,7 +630,7 @@ void launch_batch_res(const BatchArgs& b, int max_mine, int blocks, hipStream_t 
 template <int N, int M, int BITS>
 void launch_batch(const BatchArgs& b, int max_mine, int blocks, hipStream_t st)
 {
-    if (b.flags) launch_batch_res<N, M, BITS, true>(b, max_mine, blocks, st);
+    if (b.stream_loads) launch_batch_res<N, M, BITS, true>(b, max_mine, blocks, st);
     else launch_batch_res<N, M, BITS, false>(b, max_mine, blocks, st);
 }
 
@@ -571,22 +638,21 @@ void launch_batch(const BatchArgs& b, int max_mine, int blocks, hipStream_t st)
 
 // Matrices that the wavefront kernel takes (alignment, whole dwords per packed row) go out in
 // launches of up to BATCH_MAX; the others one by one through launch_compress.
-int launch_compress_batch(const CompressItem* items, int count, int N, int M, int bits, hipStream_t st)
+int launch_compress_batch(const CompressItem* items, int count, int N, int M, int bits, int layout, hipStream_t st)
 {
-    const int ib = (M == 4) ? 2 : 4;
-    const bool pattern_ok = (M == 4 && (N == 1 || N == 2)) || (M == 8 && (N == 1 || N == 2 || N == 4));
     begin_launch();
     BatchArgs b;
     b.count = 0;
     long long bytes = 0;
     for (int i = 0; i < count; ++i) bytes += (long long)items[i].rows * items[i].cols * 4;
-    b.flags = bytes > STREAM_ABOVE_BYTES ? 1 : 0;           // stream the weights
+    b.stream_loads = bytes > STREAM_ABOVE_BYTES ? 1 : 0;
+    b.flags = layout ? TILED_LAYOUT : 0;
     int blocks = 0, max_mine = 0;
     auto flush = [&]() {
         if (b.count == 0) return;
 #define NM_CASE(n, m, bt) else if (N == n && M == m && bits == bt) launch_batch<n, m, bt>(b, max_mine, blocks, st)
         if (false) {}
-        NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4);
+        NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4); NM_CASE(4, 4, 8); NM_CASE(4, 4, 4);
         NM_CASE(1, 8, 8); NM_CASE(2, 8, 8); NM_CASE(4, 8, 8);
         NM_CASE(1, 8, 4); NM_CASE(2, 8, 4); NM_CASE(4, 8, 4);
 #undef NM_CASE
@@ -594,13 +660,10 @@ int launch_compress_batch(const CompressItem* items, int count, int N, int M, in
     };
     for (int i = 0; i < count; ++i) {
         const CompressItem& c = items[i];
-        const size_t kc = (size_t)c.cols / M * N;
-        const int vstride = (int)((kc * bits + 7) / 8), mstride = (int)((kc * ib + 7) / 8);
-        const bool aligned = ((uintptr_t)c.W % 16 == 0) && (c.ldw % 4 == 0) && ((uintptr_t)c.vals % 4 == 0) &&
-                             ((uintptr_t)c.meta % 4 == 0) && (kc * bits % 32 == 0) && (kc * ib % 32 == 0);
-        if (!pattern_ok || !aligned) {
+        const PackedArray pv = packed_values(c.cols, N, M, bits, layout), pm = packed_meta(c.cols, N, M, layout);
+        if (!wave_kernel_takes(c.W, c.cols, c.ldw, N, M, bits, c.vals, c.meta)) {
             int rc = launch_status();              // of the batches launched so far: the call below starts a bracket of its own
-            if (rc == 0) rc = launch_compress(c.W, c.rows, c.cols, c.ldw, N, M, bits, 1, c.vals, c.meta, c.scales, st);
+            if (rc == 0) rc = launch_compress(c.W, c.rows, c.cols, c.ldw, N, M, bits, layout, 1, c.vals, c.meta, c.scales, st);
             if (rc) return rc;
             continue;
         }
@@ -608,9 +671,10 @@ int launch_compress_batch(const CompressItem* items, int count, int N, int M, in
         const int passes = (c.cols / M + 63) / 64, mine = (passes + wpr - 1) / wpr, rpb = 4 / wpr;
         BatchItem& t = b.it[b.count++];
         t.W = c.W; t.vals = (uint32_t*)c.vals; t.meta = (uint32_t*)c.meta; t.scales = c.scales;
-        t.rows = c.rows; t.cols = c.cols; t.ldw = c.ldw; t.vstride_dw = vstride / 4; t.mstride_dw = mstride / 4;
+        t.rows = c.rows; t.cols = c.cols; t.ldw = c.ldw; t.vstride_dw = (int)pv.stride / 4; t.mstride_dw = (int)pm.stride / 4;
         t.wpr = wpr; t.first_block = blocks; t.pad = 0;
-        blocks += (c.rows + rpb - 1) / rpb;
+        const int rows_out = layout ? ((c.rows + 15) & ~15) : c.rows;     // the tiled layout pads the rows
+        blocks += (rows_out + rpb - 1) / rpb;
         max_mine = mine > max_mine ? mine : max_mine;
         if (b.count == BATCH_MAX) flush();
     }
@@ -618,17 +682,14 @@ int launch_compress_batch(const CompressItem* items, int count, int N, int M, in
     return launch_status();
 }
 
-int launch_decompress(const void* vals, const void* meta, int rows, int cols, int N, int M, int bits,
+int launch_decompress(const void* vals, const void* meta, int rows, int cols, int N, int M, int bits, int layout,
                       int8_t* Wq, hipStream_t st)
 {
-    const int ib = (M == 4) ? 2 : 4;
-    const size_t kc = (size_t)cols / M * N;
-    const int vstride = (int)((kc * bits + 7) / 8);
-    const int mstride = (int)((kc * ib + 7) / 8);
     const long long total = (long long)rows * (cols / M);
     begin_launch();
     hipLaunchKernelGGL(decompress_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       (const uint8_t*)vals, (const uint8_t*)meta, rows, cols, N, M, bits, vstride, mstride, Wq);
+                       (const uint8_t*)vals, (const uint8_t*)meta, rows, cols, N, M, bits,
+                       packed_values(cols, N, M, bits, layout), packed_meta(cols, N, M, layout), Wq);
     return launch_status();
 }
 

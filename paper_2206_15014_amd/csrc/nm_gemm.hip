@@ -22,6 +22,8 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include <type_traits>
 
 #include "nm_internal.h"
@@ -48,6 +50,7 @@ namespace {
 //
 // Workgroups are numbered so that those sharing an XCD (blockIdx % 8) cover a contiguous token
 // range: each XCD's L2 then holds one slice of X plus the (small) packed weight matrix.
+// Serves the row layout of the packed weights (the LDS-direct kernels read the tiled one).
 // Requires K % 128 == 0, O % 4 == 0, 16-byte aligned X / ldx / values, ldo % 4 == 0.
 // ---------------------------------------------------------------------------------------------
 template <int BT, int BO>
@@ -99,8 +102,8 @@ gemm_smfmac_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     for (int r = 0; r < WU; ++r) {
         const int u = min(tid + NT * r, BO * 4 - 1);
         const int row = min(o0 + (u >> 2), a.O - 1);
-        wvsrc[r] = a.vals + (size_t)row * a.vstride + (u & 3) * U::VBYTES;
-        wmsrc[r] = a.meta + (size_t)row * a.mstride + (u & 3) * U::MBYTES;
+        wvsrc[r] = a.vals + (size_t)row * a.pv.stride + (u & 3) * U::VBYTES;
+        wmsrc[r] = a.meta + (size_t)row * a.pm.stride + (u & 3) * U::MBYTES;
     }
     v4i xr[DEPTH][XCH];
     typename U::Raw wr[DEPTH][WU];
@@ -203,7 +206,8 @@ gemm_smfmac_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Any pattern, any shape, any alignment: one thread per output element, walking the metadata.
+// Any pattern, any shape, any alignment, either layout: one thread per output element, walking
+// the metadata.
 // ---------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 gemm_generic_kernel(const GemmArgs a)
@@ -213,37 +217,72 @@ gemm_generic_kernel(const GemmArgs a)
     const bool live = id_raw < total;          // threads past the end recompute the last output and store nothing
     const long long id = live ? id_raw : total - 1;
     const int t = (int)(id / a.O), o = (int)(id % a.O);
-    const int ib = (a.M == 4) ? 2 : 4;
+    const int ib = (a.N >= a.M) ? 0 : (a.M == 4) ? 2 : 4;
     const int kc = a.K / a.M * a.N;
-    const uint8_t* vrow = a.vals + (size_t)o * a.vstride;
-    const uint8_t* mrow = a.meta + (size_t)o * a.mstride;
     const int8_t* x = a.X + (size_t)t * a.ldx;
     int sum = 0;
     for (int e = 0; e < kc; ++e) {
         int q, off;
-        if (a.bits == 8) q = (int8_t)vrow[e];
-        else { int nib = (vrow[e >> 1] >> ((e & 1) * 4)) & 15; q = (nib ^ 8) - 8; }
-        if (ib == 2) off = (mrow[e >> 2] >> ((e & 3) * 2)) & 3;
-        else off = (mrow[e >> 1] >> ((e & 1) * 4)) & 15;
+        if (a.bits == 8) q = (int8_t)a.vals[a.pv.at((uint32_t)o, (uint32_t)e)];
+        else { int nib = (a.vals[a.pv.at((uint32_t)o, (uint32_t)e >> 1)] >> ((e & 1) * 4)) & 15; q = (nib ^ 8) - 8; }
+        if (ib == 0) off = e % a.N;
+        else if (ib == 2) off = (a.meta[a.pm.at((uint32_t)o, (uint32_t)e >> 2)] >> ((e & 3) * 2)) & 3;
+        else off = (a.meta[a.pm.at((uint32_t)o, (uint32_t)e >> 1)] >> ((e & 1) * 4)) & 15;
         sum += (int)x[(e / a.N) * a.M + off] * q;
     }
     const size_t at = (size_t)t * a.ldo + o;
+    const float s_act = act_scale_of(a);
     if (a.out_dtype == 3) {                    // requantised output: every lane takes part in the reduction of max |y|
+        const float s_out = out_scale_of(a);
         float g[4] = {0.f, 0.f, 0.f, 0.f}, h[4] = {0.f, 0.f, 0.f, 0.f};
-        requant_column(a.act_scale, a.scales[o], a.bias ? a.bias[o] : 0.0f, a.out_scale, g[0], h[0]);
+        requant_column(s_act, a.scales[o], a.bias ? a.bias[o] : 0.0f, s_out, g[0], h[0]);
         float m = 0.0f;
         const uint32_t q = requant4(v4i{sum, 0, 0, 0}, g, h, m);
         if (live) reinterpret_cast<uint8_t*>(a.out)[at] = (uint8_t)q;
-        absmax_commit(m, a.out_scale, a.absmax);
+        absmax_commit(m, s_out, a.absmax);
         return;
     }
     if (!live) return;
     if (a.acc) a.acc[at] = sum;
     if (a.out_dtype != 0) {
-        float y = (float)sum * (a.act_scale * a.scales[o]) + (a.bias ? a.bias[o] : 0.0f);
+        float y = (float)sum * (s_act * a.scales[o]) + (a.bias ? a.bias[o] : 0.0f);
         if (a.out_dtype == 1) reinterpret_cast<float*>(a.out)[at] = y;
         else reinterpret_cast<uint16_t*>(a.out)[at] = (uint16_t)pack_bf16x2(y, 0.0f);
     }
+}
+
+// Register-resident loop of the sparse MFMA (measurement hook, see nm_test_hooks.h).
+__global__ void __launch_bounds__(256)
+smfmac_probe_kernel(int iters, unsigned long long* counters)
+{
+    const int lane = threadIdx.x & 63;
+    v4i a = v4i{lane, lane + 1, lane + 2, lane + 3};
+    v8i b = v8i{lane, 1, 2, 3, 4, 5, 6, lane};
+    v4i acc[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] = v4i{k, 0, 0, 0};
+    const long long c0 = clock64(), w0 = wall_clock64();
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(a, b, acc[k], 0x44444444, 0, 0);
+    }
+    const long long c1 = clock64(), w1 = wall_clock64();
+    int sum = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) sum += acc[k][0] + acc[k][1] + acc[k][2] + acc[k][3];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        counters[0] = (unsigned long long)(c1 - c0);
+        counters[1] = (unsigned long long)(w1 - w0);
+    }
+    if (sum == 0x7fffffff) counters[2] = (unsigned long long)sum;     // keeps the loop alive; never true in practice
+}
+
+// Scale of 8-bit activations from their largest magnitude (the rule of Sec. 3.3.1 at 8 bits).
+__global__ void absmax_to_scale_kernel(float* absmax, float* scale, int reset)
+{
+    const float m = *absmax;
+    *scale = (m == 0.0f) ? 1.0f : __fdiv_rn(m, 127.0f);
+    if (reset) *absmax = 0.0f;
 }
 
 template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int DEPTH, int STAGES>
@@ -261,11 +300,10 @@ void launch_tile(const GemmArgs& a, hipStream_t st)
     const size_t lds = STAGES * (size_t)TileGeom<BT, BO>::STAGE;
     auto kern = gemm_smfmac_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O, DEPTH, STAGES>;
     if (lds > 64 * 1024) {
-        static bool raised = false;             // per instantiation; the attribute is sticky
-        if (!raised) {
+        static std::once_flag raised;           // per instantiation; the attribute is sticky
+        std::call_once(raised, [&]() {
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            raised = true;
-        }
+        });
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WAVES_T * WAVES_O), lds, st, a, tiles_o, n_tiles);
 }
@@ -287,64 +325,66 @@ void launch_pattern(const GemmArgs& a, hipStream_t st, int tile_cfg)
     // Enough workgroups to cover the 256 CUs decides the tile: big tiles reuse operands best,
     // small ones keep narrow layers (few output rows) from leaving CUs idle.
     const long long big = (long long)((a.tokens + 127) / 128) * ((a.O + 127) / 128);
-    if (tile_cfg == 0) tile_cfg = (big >= 384) ? 1 : 2;
+    if (tile_cfg < 1 || tile_cfg > 3) tile_cfg = (big >= 384) ? 1 : 2;
     switch (tile_cfg) {
         case 1: launch_depth<N, M, BITS, 128, 128, 2, 2, 2>(a, st); break;
         case 2: launch_depth<N, M, BITS, 128, 64, 2, 2, 2>(a, st); break;
-        case 3: launch_depth<N, M, BITS, 64, 64, 2, 2, 2>(a, st); break;
-        default:
-            if constexpr (N == 2 && M == 4 && BITS == 8) {
-                switch (tile_cfg) {
-                    case 4: launch_tile<N, M, BITS, 128, 128, 2, 2, 1, 2>(a, st); break;
-                    case 5: launch_depth<N, M, BITS, 128, 128, 2, 2, 3>(a, st); break;
-                    case 6: launch_tile<N, M, BITS, 128, 128, 2, 2, 6, 2>(a, st); break;
-                    case 7: launch_tile<N, M, BITS, 128, 128, 2, 2, 2, 2>(a, st); break;
-                    case 8: launch_depth<N, M, BITS, 128, 96, 2, 2, 3>(a, st); break;
-                    case 9: launch_depth<N, M, BITS, 128, 96, 2, 2, 2>(a, st); break;
-                    case 10: launch_depth<N, M, BITS, 64, 96, 2, 2, 3>(a, st); break;
-                    case 11: launch_depth<N, M, BITS, 64, 96, 2, 2, 2>(a, st); break;
-                    case 12: launch_depth<N, M, BITS, 128, 192, 2, 2, 2>(a, st); break;
-                    case 13: launch_depth<N, M, BITS, 128, 192, 2, 4, 2>(a, st); break;
-                    case 14: launch_depth<N, M, BITS, 256, 128, 4, 2, 2>(a, st); break;
-                    case 15: launch_depth<N, M, BITS, 128, 128, 2, 4, 3>(a, st); break;
-                    case 16: launch_depth<N, M, BITS, 64, 64, 2, 2, 3>(a, st); break;
-                    case 17: launch_depth<N, M, BITS, 64, 128, 2, 2, 3>(a, st); break;
-                    default: launch_depth<N, M, BITS, 128, 128, 2, 2, 2>(a, st); break;
-                }
-            } else {
-                launch_depth<N, M, BITS, 128, 128, 2, 2, 2>(a, st);
-            }
+        default: launch_depth<N, M, BITS, 64, 64, 2, 2, 2>(a, st); break;
     }
 }
 
 }  // namespace
 
+bool launch_gemm_dma_set0(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set1(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set2(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set3(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set4(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set5(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set6(const GemmArgs& a, hipStream_t st, int cfg);
+
+bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg)
+{
+    return launch_gemm_dma_set0(a, st, cfg) || launch_gemm_dma_set1(a, st, cfg) || launch_gemm_dma_set2(a, st, cfg) ||
+           launch_gemm_dma_set3(a, st, cfg) || launch_gemm_dma_set4(a, st, cfg) || launch_gemm_dma_set5(a, st, cfg) ||
+           launch_gemm_dma_set6(a, st, cfg);
+}
+
+int launch_smfmac_probe(int blocks, int iters, unsigned long long* counters, hipStream_t st)
+{
+    begin_launch();
+    hipLaunchKernelGGL(smfmac_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, st, iters, counters);
+    return launch_status();
+}
+
+int launch_absmax_to_scale(float* absmax, float* scale, int reset, hipStream_t st)
+{
+    begin_launch();
+    hipLaunchKernelGGL(absmax_to_scale_kernel, dim3(1), dim3(1), 0, st, absmax, scale, reset);
+    return launch_status();
+}
+
 int launch_gemm(const GemmArgs& a, hipStream_t st)
 {
     const bool out_ok = a.out_dtype == 0 || (uintptr_t)a.out % 16 == 0;   // (int8 codes: rows are then whole dwords, ldo % 4 == 0)
-    const bool fast = a.N <= 2 && a.K % 128 == 0 && a.O % 4 == 0 && a.ldx % 16 == 0 && a.ldo % 4 == 0 &&
-                      (uintptr_t)a.X % 16 == 0 && (uintptr_t)a.vals % 16 == 0 && (uintptr_t)a.meta % 4 == 0 &&
+    const bool fast = a.K % 128 == 0 && a.O % 4 == 0 && a.ldx % 16 == 0 && a.ldo % 4 == 0 &&
+                      (uintptr_t)a.X % 16 == 0 && (uintptr_t)a.vals % 16 == 0 && (uintptr_t)a.meta % 16 == 0 &&
                       (uintptr_t)a.scales % 16 == 0 && (uintptr_t)a.bias % 16 == 0 && (uintptr_t)a.acc % 16 == 0 && out_ok;
     begin_launch();
-    if (fast) {
-        const char* env = getenv("NM_GEMM_TILE");   // tuning / test override of the tile choice
-        int tile_cfg = env ? atoi(env) : 0;
-        // LDS-direct kernel first (tile_cfg 0 = its own choice, >= 100 = forced variant);
-        // 1..99 force the register-staged kernel below.
-        if (tile_cfg >= 300 && launch_gemm_xres(a, st, tile_cfg)) return launch_status();
-        if (tile_cfg >= 200 && tile_cfg < 300 && launch_gemm_stream(a, st, tile_cfg)) return launch_status();
-        if ((tile_cfg == 0 || tile_cfg >= 100) && (uintptr_t)a.meta % 16 == 0 && launch_gemm_dma(a, st, tile_cfg))
-            return launch_status();
-        if (tile_cfg >= 100) tile_cfg = 0;
+    const int tile_cfg = forced_gemm_tile();    // 0 unless a test forces a variant
+    // Tiled layout: the LDS-direct kernels (tile_cfg 0 = their own choice, >= 100 = a forced variant).
+    if (fast && a.pv.tiled && launch_gemm_dma(a, st, tile_cfg >= 100 ? tile_cfg : 0)) return launch_status();
+    // Row layout, at most two kept per group: the register-staged kernel (tile_cfg 1 .. 3 force its shapes).
+    if (fast && !a.pv.tiled && a.N <= 2) {
 #define NM_CASE(n, m, b) else if (a.N == n && a.M == m && a.bits == b) launch_pattern<n, m, b>(a, st, tile_cfg)
         if (false) {}
         NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4);
         NM_CASE(1, 8, 8); NM_CASE(2, 8, 8); NM_CASE(1, 8, 4); NM_CASE(2, 8, 4);
 #undef NM_CASE
-    } else {
-        const long long total = (long long)a.tokens * a.O;
-        hipLaunchKernelGGL(gemm_generic_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
+        return launch_status();
     }
+    const long long total = (long long)a.tokens * a.O;
+    hipLaunchKernelGGL(gemm_generic_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
     return launch_status();
 }
 

@@ -8,6 +8,8 @@
 
 #include <type_traits>
 
+#include "nm_internal.h"
+
 namespace nm {
 namespace {
 
@@ -28,19 +30,25 @@ __device__ __forceinline__ uint32_t sext4x4(uint32_t nib)
 
 template <int N, int M, int BITS>
 struct Unit {
-    static constexpr int IB = (M == 4) ? 2 : 4;
+    static constexpr int IB = (N >= M) ? 0 : (M == 4) ? 2 : 4;
     static constexpr int EPU = 32 / M * N;          // kept entries per unit
-    static constexpr int VBYTES = EPU * BITS / 8;   // packed value bytes per unit (2, 4, 8 or 16)
-    static constexpr int MBYTES = EPU * IB / 8;     // packed index bytes per unit (2 or 4)
+    static constexpr int VBYTES = EPU * BITS / 8;   // packed value bytes per unit (2 .. 32)
+    static constexpr int MBYTES = EPU * IB / 8;     // packed index bytes per unit (0 for a dense matrix)
     static constexpr bool IDENTITY = (N == 2 && M == 4 && BITS == 8);
+    // More than two kept entries can fall into one aligned subgroup of four columns: the unit is
+    // then split into two legal operands of the sparse MFMA (see decode2).
+    static constexpr bool DUAL = (N > 2);
+    static constexpr int VD = (VBYTES + 3) / 4, MD = (MBYTES + 3) / 4 > 0 ? (MBYTES + 3) / 4 : 1;
 
     struct Raw {
-        uint32_t v[(VBYTES + 3) / 4];
-        uint32_t m;
+        uint32_t v[VD];
+        uint32_t m[MD];
     };
 
+    // Row layout: unit `unit` of the packed row at vrow / mrow (patterns with whole power-of-two units).
     static __device__ __forceinline__ Raw load(const uint8_t* __restrict__ vrow, const uint8_t* __restrict__ mrow, int unit)
     {
+        static_assert(!DUAL, "row-layout loads serve the patterns with at most two kept per group");
         Raw r;
         const uint8_t* pv = vrow + (size_t)unit * VBYTES;
         if constexpr (VBYTES == 16) {
@@ -55,14 +63,51 @@ struct Unit {
             r.v[0] = *reinterpret_cast<const uint16_t*>(pv);
         }
         const uint8_t* pm = mrow + (size_t)unit * MBYTES;
-        if constexpr (MBYTES == 4) r.m = *reinterpret_cast<const uint32_t*>(pm);
-        else r.m = *reinterpret_cast<const uint16_t*>(pm);
+        if constexpr (MBYTES == 4) r.m[0] = *reinterpret_cast<const uint32_t*>(pm);
+        else r.m[0] = *reinterpret_cast<const uint16_t*>(pm);
+        return r;
+    }
+
+    // Tiled layout: `vblock` / `mblock` point at the block (16 rows x 128 columns) in LDS, `lane`
+    // = 16 * (unit of the slice) + (row of the block) is this lane's unit.  Piece p of a unit of
+    // UB bytes lies at (p * 64 + lane) * PB: every read is lane-contiguous, free of bank conflicts.
+    template <int UB, int WORDS>
+    static __device__ __forceinline__ void load_pieces(const uint8_t* __restrict__ block, int lane, uint32_t (&dst)[WORDS])
+    {
+        constexpr int PB = piece_bytes(UB), P = UB / PB;
+#pragma unroll
+        for (int w = 0; w < WORDS; ++w) dst[w] = 0u;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const uint8_t* q = block + (p * 64 + lane) * PB;
+            if constexpr (PB == 16) {
+                const uint4 t = *reinterpret_cast<const uint4*>(q);
+                dst[4 * p] = t.x; dst[4 * p + 1] = t.y; dst[4 * p + 2] = t.z; dst[4 * p + 3] = t.w;
+            } else if constexpr (PB == 8) {
+                const uint2 t = *reinterpret_cast<const uint2*>(q);
+                dst[2 * p] = t.x; dst[2 * p + 1] = t.y;
+            } else if constexpr (PB == 4) {
+                dst[p] = *reinterpret_cast<const uint32_t*>(q);
+            } else {
+                static_assert(PB == 2, "units are an even number of bytes");
+                dst[p / 2] |= (uint32_t)*reinterpret_cast<const uint16_t*>(q) << (16 * (p & 1));
+            }
+        }
+    }
+    static __device__ __forceinline__ Raw load_tiled(const uint8_t* __restrict__ vblock, const uint8_t* __restrict__ mblock, int lane)
+    {
+        Raw r;
+        load_pieces<VBYTES>(vblock, lane, r.v);
+        if constexpr (MBYTES > 0) load_pieces<MBYTES>(mblock, lane, r.m);
+        else r.m[0] = 0u;
         return r;
     }
 
     // Packed unit -> MFMA operand: 16 int8 codes (zero where nothing is kept) and 16 2-bit positions.
-    static __device__ __forceinline__ void decode(const Raw& r, v4i& codes, int& pos)
+    static __device__ __forceinline__ void decode(const Raw& r_in, v4i& codes, int& pos)
     {
+        static_assert(!DUAL, "one operand holds at most two entries per subgroup of four");
+        struct { const uint32_t* v; uint32_t m; } r = {r_in.v, r_in.m[0]};
         if constexpr (IDENTITY) {
             codes = v4i{(int)r.v[0], (int)r.v[1], (int)r.v[2], (int)r.v[3]};
             pos = (int)r.m;
@@ -170,38 +215,105 @@ struct Unit {
             pos = (int)hp;
         }
     }
+
+    // Patterns that can keep more than two entries in an aligned subgroup of four columns (3:4,
+    // 4:8, dense): the unit becomes TWO legal operands of the sparse MFMA, multiplied one after the
+    // other against the same activations.  Of the (up to four) entries a subgroup keeps, operand
+    // 1 takes the first two and operand 2 the rest, zero where there is none.  The sparse
+    // instruction at twice its issue count does the work of the dense one at the same rate, and
+    // the whole staging path stays as it is.
+    static __device__ __forceinline__ void decode2(const Raw& r, v4i& c1, int& p1, v4i& c2, int& p2)
+    {
+        static_assert(DUAL, "patterns with more than two kept entries per group");
+        // the codes as bytes, in entry order
+        uint32_t w[EPU / 4];
+        if constexpr (BITS == 8) {
+#pragma unroll
+            for (int d = 0; d < EPU / 4; ++d) w[d] = r.v[d];
+        } else {
+#pragma unroll
+            for (int d = 0; d < EPU / 8; ++d) {
+                const uint32_t x = r.v[d];
+                const uint32_t lo = sext4x4(x & 0x0F0F0F0Fu);          // entries 0, 2, 4, 6 of this dword
+                const uint32_t hi = sext4x4((x >> 4) & 0x0F0F0F0Fu);   // entries 1, 3, 5, 7
+                w[2 * d] = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+                w[2 * d + 1] = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+            }
+        }
+        if constexpr (N == M) {
+            // dense: dword d of w is subgroup d (columns 4d .. 4d+3); operand dword h covers subgroups
+            // 2h and 2h+1: columns 0, 1 of each go to operand 1 (positions 0, 1), columns 2, 3 to operand 2
+            c1 = v4i{(int)__builtin_amdgcn_perm(w[1], w[0], 0x05040100u), (int)__builtin_amdgcn_perm(w[3], w[2], 0x05040100u),
+                     (int)__builtin_amdgcn_perm(w[5], w[4], 0x05040100u), (int)__builtin_amdgcn_perm(w[7], w[6], 0x05040100u)};
+            c2 = v4i{(int)__builtin_amdgcn_perm(w[1], w[0], 0x07060302u), (int)__builtin_amdgcn_perm(w[3], w[2], 0x07060302u),
+                     (int)__builtin_amdgcn_perm(w[5], w[4], 0x07060302u), (int)__builtin_amdgcn_perm(w[7], w[6], 0x07060302u)};
+            p1 = 0x44444444;                                   // slot 0 at position 0, slot 1 at position 1
+            p2 = (int)0xEEEEEEEEu;                             // slot 0 at position 2, slot 1 at position 3
+        } else if constexpr (N == 3 && M == 4) {
+            // subgroup g keeps entries 3g, 3g+1, 3g+2: the first two to operand 1, the third to slot 0
+            // of operand 2, whose slot 1 is zero.  Operand dword h = subgroups 2h, 2h+1 = bytes 6h ...
+            c1 = v4i{(int)__builtin_amdgcn_perm(w[1], w[0], 0x04030100u), (int)__builtin_amdgcn_perm(w[2], w[1], 0x06050302u),
+                     (int)__builtin_amdgcn_perm(w[4], w[3], 0x04030100u), (int)__builtin_amdgcn_perm(w[5], w[4], 0x06050302u)};
+            c2 = v4i{(int)__builtin_amdgcn_perm(w[1], w[0], 0x0c050c02u), (int)__builtin_amdgcn_perm(w[2], w[1], 0x0c070c04u),
+                     (int)__builtin_amdgcn_perm(w[4], w[3], 0x0c050c02u), (int)__builtin_amdgcn_perm(w[5], w[4], 0x0c070c04u)};
+            // index bits: 6 per subgroup (o0 | o1 << 2 | o2 << 4), 48 in all
+            const uint64_t m = (uint64_t)r.m[0] | ((uint64_t)r.m[1] << 32);
+            uint32_t q1 = 0u, q2 = 0u;
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                q1 |= (uint32_t)((m >> (6 * g)) & 0xFu) << (4 * g);
+                q2 |= (uint32_t)((m >> (6 * g + 4)) & 0x3u) << (4 * g);
+            }
+            p1 = (int)q1;
+            p2 = (int)(q2 | 0xCCCCCCCCu);                      // the empty slot points at column 3 (its code is zero)
+        } else {
+            static_assert(N == 4 && M == 8, "dual operands: 3:4, 4:8 and dense");
+            // group g (8 columns) keeps 4 entries, dword g of w, offsets 4 bits each: the codes are
+            // scattered to their columns (zeros elsewhere) and the 8 columns then split as a dense group
+            uint32_t a1[4], a2[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const uint32_t m16 = (r.m[g / 2] >> (16 * (g & 1))) & 0xFFFFu;
+                uint64_t d = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t code = (w[g] >> (8 * j)) & 0xFFu;
+                    const uint32_t sh = ((m16 >> (4 * j)) & 7u) * 8u;
+                    d |= (uint64_t)code << sh;
+                }
+                const uint32_t lo = (uint32_t)d, hi = (uint32_t)(d >> 32);
+                a1[g] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                a2[g] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+            }
+            c1 = v4i{(int)a1[0], (int)a1[1], (int)a1[2], (int)a1[3]};
+            c2 = v4i{(int)a2[0], (int)a2[1], (int)a2[2], (int)a2[3]};
+            p1 = 0x44444444;
+            p2 = (int)0xEEEEEEEEu;
+        }
+    }
 };
 
 // ---------------------------------------------------------------------------------------------
 // LDS-direct operand staging (global_load_lds_dwordx4): geometry of one ring stage and the load /
 // wait primitives.  A direct load writes 64 lanes x 16 bytes to 1 KB of consecutive LDS in lane
 // order, so every staged array is a sequence of 1 KB blocks and the layout inside a block is
-// chosen by which global chunk each lane fetches.
+// chosen by which global chunk each lane fetches.  The packed weights are staged as copies of the
+// tiled layout's blocks (16 rows x 128 columns each): [slice of the stage][row block of the tile].
 // ---------------------------------------------------------------------------------------------
 template <int N, int M, int BITS, int BT, int BO, int KU>
 struct DmaGeom {
     using U = Unit<N, M, BITS>;
-    static constexpr int RVS = 4 * U::VBYTES * KU;           // packed value bytes per row per stage, in memory
-    static constexpr int RMS = 4 * U::MBYTES * KU;           // packed index bytes per row per stage, in memory
-    // A direct load moves 16-byte pieces.  An array with only 8 bytes per row and stage is staged
-    // as the 16-byte piece that holds two consecutive stages ("pair"): every stage loads the piece
-    // its K block lies in and reads its own half.
-    static constexpr bool PAIR_V = (RVS == 8), PAIR_M = (RMS == 8);
-    static constexpr int RV = PAIR_V ? 16 : RVS;             // bytes per row in the LDS stage
-    static constexpr int RM = PAIR_M ? 16 : RMS;
-    static_assert(RV % 16 == 0 && RM % 16 == 0, "rows must be whole 16-byte chunks");
-    static constexpr bool V_SWIZZLE = (RV == 128);           // 8 chunks per row: same XOR as the X rows
-    // XOR term for the 16-byte chunk index of a codes row, so that the 16 rows one fragment read
-    // touches spread over all banks: rows 256 bytes apart would otherwise meet in the same banks
-    // (every 2nd row of 128 bytes, every 4th of 64, every 8th of 32).
-    __host__ __device__ static constexpr int v_xor(int row)
-    {
-        return RV == 128 ? ((row >> 1) & 7) : RV == 64 ? ((row >> 2) & 3) : RV == 32 ? ((row >> 3) & 1) : 0;
-    }
+    static constexpr int FB = BO / 16;                       // row blocks (weight fragments) per tile
+    static constexpr int VBLK = 64 * U::VBYTES;              // bytes of one block of the tiled layout: codes ...
+    static constexpr int MBLK = 64 * U::MBYTES;              // ... and index bits (0: dense matrix)
+    static constexpr int MBLK_ = MBLK > 0 ? MBLK : 1;        // as a divisor
+    static constexpr int V_BYTES = KU * FB * VBLK;           // per stage
+    static constexpr int M_BYTES = KU * FB * MBLK;
+    static_assert(VBLK % 16 == 0 && MBLK % 16 == 0, "blocks are whole 16-byte pieces");
     static constexpr int X_SUB = BT * 128;                   // bytes of one 128-column slice of X
     static constexpr int X_BLOCKS = KU * BT * 128 / 1024;
-    static constexpr int V_BLOCKS = (BO * RV + 1023) / 1024;
-    static constexpr int M_BLOCKS = (BO * RM + 1023) / 1024;
+    static constexpr int V_BLOCKS = (V_BYTES + 1023) / 1024;
+    static constexpr int M_BLOCKS = (M_BYTES + 1023) / 1024;
     static constexpr int X_OFF = 0;
     static constexpr int V_OFF = X_BLOCKS * 1024;
     static constexpr int M_OFF = V_OFF + V_BLOCKS * 1024;
@@ -322,6 +434,19 @@ __device__ __forceinline__ void absmax_commit(float m, float out_scale, float* d
     }
 }
 
+// The activation scale and the scale of the output codes: the host value, or the device float that
+// replaces it (a scale that earlier work on the stream has computed).
+template <class Args>
+__device__ __forceinline__ float act_scale_of(const Args& a)
+{
+    return a.act_scale_dev ? *a.act_scale_dev : a.act_scale;
+}
+template <class Args>
+__device__ __forceinline__ float out_scale_of(const Args& a)
+{
+    return a.out_scale_dev ? *a.out_scale_dev : a.out_scale;
+}
+
 // Epilogue shared by the MFMA kernels: Eq. 4 with offset 0 applied to the product of two quantised
 // operands.  acc[fo][ft] is the 16x16 accumulator fragment of weight rows o_base + fo*16 .. and
 // tokens t_base + ft*16 ..; lane (li, lg) holds rows 4*lg .. 4*lg+3 of token li.
@@ -329,13 +454,14 @@ template <int FO, int FT, class Args>
 __device__ __forceinline__ void store_tile(const Args& a, const v4i (&acc)[FO][FT], int o_base, int t_base, int li, int lg)
 {
     float m = 0.0f;                            // max |y| of this lane (requantised output only)
+    const float s_act = act_scale_of(a), s_out = out_scale_of(a);
 #pragma unroll
     for (int fo = 0; fo < FO; ++fo) {
         const int o = o_base + fo * 16 + 4 * lg;
         if (o >= a.O) continue;
         const float4 sw = *reinterpret_cast<const float4*>(a.scales + o);
         const float sws[4] = {sw.x, sw.y, sw.z, sw.w};
-        const float sc[4] = {a.act_scale * sw.x, a.act_scale * sw.y, a.act_scale * sw.z, a.act_scale * sw.w};
+        const float sc[4] = {s_act * sw.x, s_act * sw.y, s_act * sw.z, s_act * sw.w};
         float bs[4] = {0.f, 0.f, 0.f, 0.f};
         if (a.bias) {
             const float4 b = *reinterpret_cast<const float4*>(a.bias + o);
@@ -362,13 +488,13 @@ __device__ __forceinline__ void store_tile(const Args& a, const v4i (&acc)[FO][F
                 } else {
                     float g[4], h[4];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) requant_column(a.act_scale, sws[r], bs[r], a.out_scale, g[r], h[r]);
+                    for (int r = 0; r < 4; ++r) requant_column(s_act, sws[r], bs[r], s_out, g[r], h[r]);
                     *reinterpret_cast<uint32_t*>(reinterpret_cast<uint8_t*>(a.out) + at) = requant4(c, g, h, m);
                 }
             }
         }
     }
-    if (a.out_dtype == 3) absmax_commit(m, a.out_scale, a.absmax);
+    if (a.out_dtype == 3) absmax_commit(m, s_out, a.absmax);
 }
 
 // Same, with the row scales and biases already in registers (sw[fo], bw[fo] hold rows
@@ -379,11 +505,12 @@ __device__ __forceinline__ void store_tile_pre(const Args& a, const v4i (&acc)[F
                                                int o_base, int t_base, int li, int lg)
 {
     float m = 0.0f;                            // max |y| of this lane (requantised output only)
+    const float s_act = act_scale_of(a);
 #pragma unroll
     for (int fo = 0; fo < FO; ++fo) {
         const int o = o_base + fo * 16 + 4 * lg;
         if (o >= a.O) continue;
-        const float sc[4] = {a.act_scale * sw[fo].x, a.act_scale * sw[fo].y, a.act_scale * sw[fo].z, a.act_scale * sw[fo].w};
+        const float sc[4] = {s_act * sw[fo].x, s_act * sw[fo].y, s_act * sw[fo].z, s_act * sw[fo].w};
         const float bs[4] = {bw[fo].x, bw[fo].y, bw[fo].z, bw[fo].w};
 #pragma unroll
         for (int ft = 0; ft < FT; ++ft) {
@@ -410,7 +537,7 @@ __device__ __forceinline__ void store_tile_pre(const Args& a, const v4i (&acc)[F
             }
         }
     }
-    if (a.out_dtype == 3) absmax_commit(m, a.out_scale, a.absmax);
+    if (a.out_dtype == 3) absmax_commit(m, out_scale_of(a), a.absmax);
 }
 
 }  // namespace

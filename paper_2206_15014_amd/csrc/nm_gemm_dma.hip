@@ -9,20 +9,28 @@
 // for; the packed weight bytes travel in their compact form and are widened / re-encoded to the
 // MFMA operand in registers (Sec. 5.3: low-bit weights are widened for the ALUs).
 //
-// Stage layout (one 128-column K step).  A direct load writes 64 lanes x 16 bytes to 1 KB of
+// The packed weights are read in the tiled layout of include/nm.h: what one 16-row x 128-column
+// fragment consumes is one contiguous run of memory, so a direct load asks the L2 for eight whole
+// 128-byte lines (in the row layout it gathered 16 or 64 pieces of as many different lines, and
+// the L2 -> LDS fill is bound by the number of line requests, not by bytes), and the fragment
+// reads from LDS are lane-contiguous.
+//
+// Stage layout (KU 128-column K steps).  A direct load writes 64 lanes x 16 bytes to 1 KB of
 // consecutive LDS in lane order, so every array is a sequence of 1 KB blocks and the layout
 // inside a block is chosen by which global chunk each lane fetches:
 //   X      [BT rows][128 B]; 16-byte chunk c of row r sits in slot c ^ ((r >> 1) & 7): eight
 //          consecutive lanes fetch one full 128-byte line, and the MFMA B-fragment reads
 //          (16 rows x one slot) spread over all banks;
-//   codes  [BO rows][RV B], RV = 4 units x packed value bytes per unit (64 B for 2:4 int8);
-//   index  [BO rows][16 B]  (patterns whose index bits fill 4 bytes per unit: N = 2).
+//   codes  [KU slices][BO / 16 row blocks][64 units], a copy of the tiled layout's blocks;
+//   index  the same with the units' index bytes (absent for a dense matrix).
 // Synchronisation per step: wait until this wavefront's own loads of the next step have landed
 // (s_waitcnt vmcnt with the count of younger loads), barrier (everyone's have, and everyone has
 // consumed the stage about to be refilled), issue the loads STAGES-1 steps ahead, read the next
 // step's fragments into registers, multiply the current one.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <mutex>
 
 #include "nm_internal.h"
 #include "nm_gemm_common.h"
@@ -40,6 +48,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
 {
     using U = Unit<N, M, BITS>;
     using G = DmaGeom<N, M, BITS, BT, BO, KU>;
+    static_assert(BO % (16 * WAVES_O) == 0, "wave tiles are whole row blocks");
     constexpr int NW = WAVES_T * WAVES_O;
     constexpr int WT = BT / WAVES_T, WO = BO / WAVES_O;
     constexpr int FT = WT / 16, FO = WO / 16;
@@ -104,12 +113,10 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     // instant on inputs that no L2 holds yet, and rotated starts would ask the memory for all of X
     // and W at once, the first stages queueing behind everybody's later ones: there all start at
     // block 0 (3.5-4.5 % on the 4096-token layer sets).
-    constexpr bool PAIR = G::PAIR_V || G::PAIR_M;        // then stage parity must equal K block parity: even start, even ns
-    const int kstart = a.k_rotate ? ((int)(((unsigned)tile * 7u) % (unsigned)ns) & (PAIR ? ~1 : ~0)) : 0;
-    uint32_t amask[PER_WAVE];                  // pair arrays: the load address is rounded down to the 16-byte piece
+    const int kstart = a.k_rotate ? (int)(((unsigned)tile * 7u) % (unsigned)ns) : 0;
+    const int rb_last = (a.O + 15) / 16 - 1;   // last row block of the packed arrays
 #pragma unroll
     for (int p = 0; p < PER_WAVE; ++p) {
-        amask[p] = ~0u;
         const int b = min(p * NW + wave_u, G::BLOCKS - 1);
         if (b < G::X_BLOCKS) {
             const int sub = b / (BT / 8);
@@ -120,23 +127,20 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
             stepb[p] = 128 * KU;
             voff[p] = (uint32_t)trow * (uint32_t)a.ldx + sub * 128 + chunk * 16;
         } else if (b < G::X_BLOCKS + G::V_BLOCKS) {
-            const int q = (b - G::X_BLOCKS) * 64 + lane;       // 16-byte slot index in the codes array
-            const int row = min(q / (G::RV / 16), BO - 1);
-            const int slot = q % (G::RV / 16);
-            const int chunk = slot ^ G::v_xor(row);
-            const int orow = min(o0 + row, a.O - 1);
+            // byte q of the stage's codes array = slice s, row block fb, byte w of that block
+            const int q = min((b - G::X_BLOCKS) * 1024 + lane * 16, G::V_BYTES - 16);
+            const int sl = q / (G::FB * G::VBLK), fb = (q % (G::FB * G::VBLK)) / G::VBLK, w = q % G::VBLK;
+            const int rb = min(o0 / 16 + fb, rb_last);
             sbase[p] = a.vals;
-            stepb[p] = G::RVS;
-            if (G::PAIR_V) amask[p] = ~15u;
-            voff[p] = (uint32_t)orow * (uint32_t)a.vstride + chunk * 16;
+            stepb[p] = KU * G::VBLK;
+            voff[p] = ((uint32_t)rb * (uint32_t)nk + (uint32_t)sl) * (uint32_t)G::VBLK + (uint32_t)w;
         } else {
-            const int q = (b - G::X_BLOCKS - G::V_BLOCKS) * 64 + lane;
-            const int row = min(q / (G::RM / 16), BO - 1);
-            const int orow = min(o0 + row, a.O - 1);
+            const int q = min((b - G::X_BLOCKS - G::V_BLOCKS) * 1024 + lane * 16, (G::M_BYTES > 16 ? G::M_BYTES : 16) - 16);
+            const int sl = q / (G::FB * G::MBLK_), fb = (q % (G::FB * G::MBLK_)) / G::MBLK_, w = q % G::MBLK_;
+            const int rb = min(o0 / 16 + fb, rb_last);
             sbase[p] = a.meta;
-            stepb[p] = G::RMS;
-            if (G::PAIR_M) amask[p] = ~15u;
-            voff[p] = (uint32_t)orow * (uint32_t)a.mstride + (q % (G::RM / 16)) * 16;
+            stepb[p] = KU * G::MBLK;
+            voff[p] = ((uint32_t)rb * (uint32_t)nk + (uint32_t)sl) * (uint32_t)G::MBLK + (uint32_t)w;
         }
         voff[p] += (uint32_t)kstart * stepb[p];
     }
@@ -147,7 +151,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         constexpr int SLOT = decltype(slot)::value;
 #pragma unroll
         for (int p = 0; p < PER_WAVE; ++p) {
-            dma16s(lds_mine + (SLOT * STAGE + p * NW * 1024), PAIR ? (voff[p] & amask[p]) : voff[p], sbase[p]);
+            dma16s(lds_mine + (SLOT * STAGE + p * NW * 1024), voff[p], sbase[p]);
             voff[p] += stepb[p];
         }
         if (++k_issue == ns) {                 // wrapped: back to K block 0
@@ -165,7 +169,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         constexpr int P0 = PART * PER_WAVE / PARTS, P1 = (PART + 1) * PER_WAVE / PARTS;
 #pragma unroll
         for (int p = P0; p < P1; ++p) {
-            dma16s(lds_mine + (SLOT * STAGE + p * NW * 1024), PAIR ? (voff[p] & amask[p]) : voff[p], sbase[p]);
+            dma16s(lds_mine + (SLOT * STAGE + p * NW * 1024), voff[p], sbase[p]);
             voff[p] += stepb[p];
         }
         if constexpr (PART == PARTS - 1) {
@@ -188,14 +192,9 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     const int xsw = (li >> 1) & 7;
     const int frag_x_lo = G::X_OFF + (wt * WT + li) * 128 + ((lg ^ xsw) * 16);
     const int frag_x_hi = G::X_OFF + (wt * WT + li) * 128 + (((lg + 4) ^ xsw) * 16);
-    int frag_v[KU];
-#pragma unroll
-    for (int s = 0; s < KU; ++s) {
-        const int off = (4 * s + lg) * U::VBYTES;              // byte offset of this lane's unit in the row
-        const int chunk = (off >> 4) ^ G::v_xor(li);
-        frag_v[s] = G::V_OFF + (wo * WO + li) * G::RV + chunk * 16 + (off & 15);
-    }
-    const int frag_m = G::M_OFF + (wo * WO + li) * G::RM + lg * U::MBYTES;
+    // weight fragments: the wavefront's FO row blocks of slice s start at frag_w + s * FB * block bytes
+    const int frag_v = G::V_OFF + wo * FO * G::VBLK;
+    const int frag_m = G::M_OFF + wo * FO * G::MBLK;
 
     // Fragments live in registers one slice ahead of the MFMAs: while the matrix pipe works on
     // slice k, the LDS reads of slice k+1 are already in flight.
@@ -203,10 +202,12 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         v8i b[FT];
         typename U::Raw w[FO];
     };
-    // `par` = parity of the stage (selects the half of a pair row)
-    auto fetch = [&](auto slot, auto sub, Frags& f, auto par) __attribute__((always_inline)) {
+    auto load_w = [&](const uint8_t* base, auto sub, auto foc) __attribute__((always_inline)) {
+        constexpr int s = decltype(sub)::value, fo = decltype(foc)::value;
+        return U::load_tiled(base + frag_v + (s * G::FB + fo) * G::VBLK, base + frag_m + (s * G::FB + fo) * G::MBLK, lane);
+    };
+    auto fetch = [&](auto slot, auto sub, Frags& f) __attribute__((always_inline)) {
         constexpr int s = decltype(sub)::value;
-        constexpr int PV = G::PAIR_V ? 8 * decltype(par)::value : 0, PM = G::PAIR_M ? 8 * decltype(par)::value : 0;
         const uint8_t* base = smem + decltype(slot)::value * STAGE;
 #pragma unroll
         for (int ft = 0; ft < FT; ++ft) {
@@ -214,9 +215,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
             const v4i hi = *reinterpret_cast<const v4i*>(base + s * G::X_SUB + frag_x_hi + ft * 16 * 128);
             f.b[ft] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         }
-#pragma unroll
-        for (int fo = 0; fo < FO; ++fo)
-            f.w[fo] = U::load(base + frag_v[s] + PV + fo * 16 * G::RV, base + frag_m + PM + s * 4 * U::MBYTES + fo * 16 * G::RM, 0);
+        int_for<FO>([&](auto foc) __attribute__((always_inline)) { f.w[decltype(foc)::value] = load_w(base, sub, foc); });
     };
     auto read_b = [&](auto slot, auto sub, auto ftc, v8i& dst) __attribute__((always_inline)) {
         constexpr int s = decltype(sub)::value, ft = decltype(ftc)::value;
@@ -225,35 +224,44 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         const v4i hi = *reinterpret_cast<const v4i*>(base + s * G::X_SUB + frag_x_hi + ft * 16 * 128);
         dst = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     };
-    auto read_w = [&](auto slot, auto sub, auto foc, auto par, typename U::Raw& dst) __attribute__((always_inline)) {
-        constexpr int s = decltype(sub)::value, fo = decltype(foc)::value;
-        constexpr int PV = G::PAIR_V ? 8 * decltype(par)::value : 0, PM = G::PAIR_M ? 8 * decltype(par)::value : 0;
-        const uint8_t* base = smem + decltype(slot)::value * STAGE;
-        dst = U::load(base + frag_v[s] + PV + fo * 16 * G::RV, base + frag_m + PM + s * 4 * U::MBYTES + fo * 16 * G::RM, 0);
+    auto read_w = [&](auto slot, auto sub, auto foc, typename U::Raw& dst) __attribute__((always_inline)) {
+        dst = load_w(smem + decltype(slot)::value * STAGE, sub, foc);
+    };
+    // The MFMAs of one weight fragment over token fragments [FT0, FT1) of `bsrc`: one sparse MFMA
+    // per pair of fragments, two (one per operand half) for the patterns that keep more than two
+    // entries in a subgroup of four.
+    auto mma_frag = [&](const typename U::Raw& w, const v8i* bsrc, auto foc, auto ft0, auto ft1) __attribute__((always_inline)) {
+        constexpr int fo = decltype(foc)::value;
+        if constexpr (U::DUAL) {
+            v4i c1, c2; int p1, p2;
+            U::decode2(w, c1, p1, c2, p2);
+#pragma unroll
+            for (int ft = decltype(ft0)::value; ft < decltype(ft1)::value; ++ft) {
+                acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(c1, bsrc[ft], acc[fo][ft], p1, 0, 0);
+                acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(c2, bsrc[ft], acc[fo][ft], p2, 0, 0);
+            }
+        } else {
+            v4i codes; int pos;
+            U::decode(w, codes, pos);
+#pragma unroll
+            for (int ft = decltype(ft0)::value; ft < decltype(ft1)::value; ++ft)
+                acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(codes, bsrc[ft], acc[fo][ft], pos, 0, 0);
+        }
     };
     // One group of a paced block: the MFMAs of weight fragment FO_I over token fragments
     // [FT0, FT1) of `bsrc`, then piece FO_I of the next stage's loads, fenced so that the compiler
     // keeps them in this order.  The caller places the group's LDS reads in front.
     auto mma_group = [&](const typename U::Raw& w, const v8i* bsrc, auto foc, auto ft0, auto ft1, auto slot, bool more) __attribute__((always_inline)) {
         constexpr int fo = decltype(foc)::value;
-        v4i codes; int pos;
-        U::decode(w, codes, pos);
-#pragma unroll
-        for (int ft = decltype(ft0)::value; ft < decltype(ft1)::value; ++ft)
-            acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(codes, bsrc[ft], acc[fo][ft], pos, 0, 0);
+        mma_frag(w, bsrc, foc, ft0, ft1);
         __builtin_amdgcn_sched_barrier(0);
         if (more) issue_part(slot, foc, std::integral_constant<int, FO>{});
         __builtin_amdgcn_sched_barrier(0);
     };
     auto mma = [&](const Frags& f) __attribute__((always_inline)) {
-#pragma unroll
-        for (int fo = 0; fo < FO; ++fo) {
-            v4i codes; int pos;
-            U::decode(f.w[fo], codes, pos);
-#pragma unroll
-            for (int ft = 0; ft < FT; ++ft)
-                acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(codes, f.b[ft], acc[fo][ft], pos, 0, 0);
-        }
+        int_for<FO>([&](auto foc) __attribute__((always_inline)) {
+            mma_frag(f.w[decltype(foc)::value], f.b, foc, std::integral_constant<int, 0>{}, std::integral_constant<int, FT>{});
+        });
     };
     auto interleave = [&]() __attribute__((always_inline)) {
         // One MFMA, then one LDS read issued in its shadow.  A wavefront issues in order, so
@@ -261,7 +269,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         // MFMAs and the LDS would idle while the matrix pipe runs.
 #pragma unroll
         for (int i = 0; i < FO * FT; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x008, U::DUAL ? 2 : 1, 0);   // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
         }
     };
@@ -284,24 +292,17 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
             bq[ft] = v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         }
     };
-    auto fetch_w = [&](auto slot, auto set, auto par) __attribute__((always_inline)) {
-        constexpr int PV = G::PAIR_V ? 8 * decltype(par)::value : 0, PM = G::PAIR_M ? 8 * decltype(par)::value : 0;
+    auto fetch_w = [&](auto slot, auto set) __attribute__((always_inline)) {
         const uint8_t* base = smem + decltype(slot)::value * STAGE;
-#pragma unroll
-        for (int fo = 0; fo < FO; ++fo)
-            wq[decltype(set)::value][fo] = U::load(base + frag_v[0] + PV + fo * 16 * G::RV, base + frag_m + PM + fo * 16 * G::RM, 0);
+        int_for<FO>([&](auto foc) __attribute__((always_inline)) {
+            wq[decltype(set)::value][decltype(foc)::value] = load_w(base, std::integral_constant<int, 0>{}, foc);
+        });
     };
     auto mma_half = [&](auto set, auto half) __attribute__((always_inline)) {
-#pragma unroll
-        for (int fo = 0; fo < FO; ++fo) {
-            v4i codes; int pos;
-            U::decode(wq[decltype(set)::value][fo], codes, pos);
-#pragma unroll
-            for (int i = 0; i < HT; ++i) {
-                const int ft = decltype(half)::value * HT + i;
-                acc[fo][ft] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(codes, bq[ft], acc[fo][ft], pos, 0, 0);
-            }
-        }
+        int_for<FO>([&](auto foc) __attribute__((always_inline)) {
+            mma_frag(wq[decltype(set)::value][decltype(foc)::value], bq, foc, std::integral_constant<int, decltype(half)::value * HT>{},
+                     std::integral_constant<int, decltype(half)::value * HT + HT>{});
+        });
     };
     // READS LDS reads against FO * HT MFMAs: the surplus first, then one for one.
     auto interleave_half = [&](auto reads) __attribute__((always_inline)) {
@@ -309,7 +310,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         if constexpr (READS > MMAS) __builtin_amdgcn_sched_group_barrier(0x100, READS - MMAS, 0);
 #pragma unroll
         for (int i = 0; i < MMAS; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x008, U::DUAL ? 2 : 1, 0);   // MFMA
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // DS read
         }
     };
@@ -343,10 +344,10 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     if constexpr (SPLIT) {
-        fetch_w(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        fetch_w(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
         fetch_b(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     } else {
-        fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, fr[0], std::integral_constant<int, 0>{});
+        fetch(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, fr[0]);
     }
 
     // Everything needed before the fragments of the first slice of stage j+1 can be read; SLOT is
@@ -376,12 +377,12 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
                 using Zero = std::integral_constant<int, 0>;
                 if constexpr (KU == 2) {
                     mma(fr[0]);
-                    fetch(std::integral_constant<int, SLOT>{}, std::integral_constant<int, 1>{}, fr[1], Zero{});
+                    fetch(std::integral_constant<int, SLOT>{}, std::integral_constant<int, 1>{}, fr[1]);
                     interleave();
                     const bool more = advance(j);
                     int_for<FO>([&](auto g) __attribute__((always_inline)) {
                         constexpr int fo = decltype(g)::value;
-                        read_w(Next{}, Zero{}, g, Zero{}, fr[0].w[fo]);
+                        read_w(Next{}, Zero{}, g, fr[0].w[fo]);
                         int_for<(fo + 1) * FT / FO - fo * FT / FO>([&](auto i) __attribute__((always_inline)) {
                             constexpr int ft = fo * FT / FO + decltype(i)::value;
                             read_b(Next{}, Zero{}, std::integral_constant<int, ft>{}, fr[0].b[ft]);
@@ -397,7 +398,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
                     // second half, while the next slice's weights and first half are read
                     int_for<FO>([&](auto g) __attribute__((always_inline)) {
                         constexpr int fo = decltype(g)::value;
-                        read_w(Next{}, Zero{}, g, std::integral_constant<int, (S + 1) % 2>{}, wq[1 - S % 2][fo]);
+                        read_w(Next{}, Zero{}, g, wq[1 - S % 2][fo]);
                         int_for<(fo + 1) * HT / FO - fo * HT / FO>([&](auto i) __attribute__((always_inline)) {
                             constexpr int ft = fo * HT / FO + decltype(i)::value;
                             read_b(Next{}, Zero{}, std::integral_constant<int, ft>{}, bq[ft]);
@@ -408,7 +409,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
                     const bool more = advance(j);
                     int_for<FO>([&](auto g) __attribute__((always_inline)) {
                         constexpr int fo = decltype(g)::value;
-                        read_w(Next{}, Zero{}, g, std::integral_constant<int, (S + 1) % 2>{}, fr[1 - S % 2].w[fo]);
+                        read_w(Next{}, Zero{}, g, fr[1 - S % 2].w[fo]);
                         int_for<(fo + 1) * FT / FO - fo * FT / FO>([&](auto i) __attribute__((always_inline)) {
                             constexpr int ft = fo * FT / FO + decltype(i)::value;
                             read_b(Next{}, Zero{}, std::integral_constant<int, ft>{}, fr[1 - S % 2].b[ft]);
@@ -432,7 +433,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
         if (tid < BO) {
             float* sp = reinterpret_cast<float*>(smem + SB_OFF) + tid;
             float g, h;
-            requant_column(a.act_scale, sp[0], a.bias ? sp[256] : 0.0f, a.out_scale, g, h);
+            requant_column(act_scale_of(a), sp[0], a.bias ? sp[256] : 0.0f, out_scale_of(a), g, h);
             sp[0] = g;
             sp[256] = h;
         }
@@ -450,13 +451,14 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     }
     uint8_t* out = reinterpret_cast<uint8_t*>(a.out);
     const int row0 = t0 + wt * WT + li, col0 = o0 + wo * WO;
+    const float s_act = act_scale_of(a);
     auto dequant = [&](auto foc, auto ftc, float (&y)[4]) __attribute__((always_inline)) {
         constexpr int fo = decltype(foc)::value, ft = decltype(ftc)::value;
         const v4i c = acc[fo][ft];
-        y[0] = (float)c[0] * (a.act_scale * sw[fo].x) + bw[fo].x;
-        y[1] = (float)c[1] * (a.act_scale * sw[fo].y) + bw[fo].y;
-        y[2] = (float)c[2] * (a.act_scale * sw[fo].z) + bw[fo].z;
-        y[3] = (float)c[3] * (a.act_scale * sw[fo].w) + bw[fo].w;
+        y[0] = (float)c[0] * (s_act * sw[fo].x) + bw[fo].x;
+        y[1] = (float)c[1] * (s_act * sw[fo].y) + bw[fo].y;
+        y[2] = (float)c[2] * (s_act * sw[fo].z) + bw[fo].z;
+        y[3] = (float)c[3] * (s_act * sw[fo].w) + bw[fo].w;
     };
     typedef unsigned v2u __attribute__((ext_vector_type(2)));
     if (a.out_dtype == 3) {
@@ -517,7 +519,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
                 emit8(da, db, row0 + (ft + (lg & 1)) * 16, col0 + fo * 16 + (lg >> 1) * 8);
             });
         }
-        absmax_commit(m, a.out_scale, a.absmax);
+        absmax_commit(m, out_scale_of(a), a.absmax);
         return;
     }
     if (a.out_dtype == 1) {
@@ -588,17 +590,16 @@ bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
     static_assert(lds <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
     if ((a.K / 128) % KU != 0) return false;
     // per-lane source offsets are 32-bit
-    if ((unsigned long long)a.tokens * a.ldx >= (1ull << 32) || (unsigned long long)a.O * a.vstride >= (1ull << 32)) return false;
+    if ((unsigned long long)a.tokens * a.ldx >= (1ull << 32) || packed_bytes(a.pv, a.O, a.K) >= (1ull << 32)) return false;
     const int tiles_t = (a.tokens + BT - 1) / BT, tiles_o = (a.O + BO - 1) / BO;
     const int n_tiles = tiles_t * tiles_o;
     const int grid = 8 * ((n_tiles + 7) / 8);
     auto kern = gemm_dma_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O, STAGES, KU>;
     if (lds > 64 * 1024) {
-        static bool raised = false;             // per instantiation; the attribute is sticky
-        if (!raised) {
+        static std::once_flag raised;           // per instantiation; the attribute is sticky
+        std::call_once(raised, [&]() {
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            raised = true;
-        }
+        });
     }
     // bf16 outputs of 14 MB and more are written through (measured at 4096 tokens: equal at
     // 12.6 MB, 17 % faster at 18.9 MB, slower below); fp32 always is, in the kernel.
@@ -609,22 +610,16 @@ bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
     return true;
 }
 
-// Tile choice.  The kernel is bound by the LDS (direct-load writes at the L1 fill rate of 64 B/clk
-// plus fragment reads), so the tile wants to be as large as the CU count allows: 256 x 192 where
-// that still gives every CU a tile, else 128 x 96 (exactly 256 workgroups for BERT-base's 768-wide
-// layers at 4096 tokens).  Rings of at most 80 KB let two workgroups share
-// a CU, which overlaps one's epilogue with the other's prologue when there are several rounds.
-// Stage rows must be whole 16-byte pieces, which decides whether a pattern can use
-// single-slice stages (KU = 1) or needs 256-column stages (KU = 2).
+// Tile choice.  The kernel is bound by the L2 -> LDS fill (line requests per multiply-add) and by
+// the fixed cost of a tile, so the tile wants to be as large as the CU count allows: 256 x 192
+// where that still gives every CU a tile, else 128 x 96 (exactly 256 workgroups for BERT-base's
+// 768-wide layers at 4096 tokens).  Rings of at most 80 KB let two workgroups share a CU, which
+// overlaps one's epilogue with the other's prologue when there are several rounds.
 template <int N, int M, int BITS>
 bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 {
     using U = Unit<N, M, BITS>;
     const bool k256 = (a.K % 256) == 0;
-    // patterns with 8 bytes of codes or index bits per row and 128 columns stage them in pairs of
-    // K blocks, which needs an even number of blocks
-    constexpr bool PAIR = (4 * U::VBYTES) == 8 || (4 * U::MBYTES) == 8;
-    if (PAIR && !k256) return false;
     if (cfg == 0) {
         // Cost of a tile shape = rounds over the 256 CUs x tile area x the shape's cost per
         // multiply-add relative to 256 x 192 (the L2->LDS fill per multiply-add, measured: 256 x 128
@@ -633,14 +628,14 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
         // out; a later shape must beat an earlier one by 5 %.  BERT-base at 4096 tokens: 256 x 192
         // for QKV and FFN-up (192 and 256 tiles), 128 x 96 for the 768-wide outputs (256 tiles);
         // BERT-large at 12288 tokens: 256 x 192 for the wide layers, 192 x 128 for the 1024-wide
-        // ones (512 tiles, two full rounds, against 288 of 256 x 192: 16.4 against 21.4 us at
-        // K = 1024, 57.0 against 63.0 us at K = 4096); at 4096 tokens 128 x 128 for them (256 tiles:
-        // 8.3 against 9.4 us, 23.7 against 26.4 us) and 256 x 128 for FFN-up (512 tiles: 20.2 against 22.4 us).
+        // ones (512 tiles, two full rounds, against 288 of 256 x 192); at 4096 tokens 128 x 128 for
+        // them (256 tiles) and 256 x 128 for FFN-up (512 tiles).
         struct Shape { int cfg, bt, bo, cost; };
         static const Shape shapes[] = {{122, 256, 192, 100}, {121, 256, 128, 135}, {128, 192, 128, 150}, {117, 128, 128, 166}, {0, 128, 96, 145}};
         long long best = -1;
         int pick = 0;
         for (const Shape& sh : shapes) {
+            if (U::DUAL && sh.cfg != 0 && sh.cfg != 117) continue;   // two operands per unit: the wide wave tiles would not fit the registers
             const long long ct = (a.O + sh.bo - 1) / sh.bo;
             if (sh.cfg != 0 && (ct * sh.bo - a.O) * 8 > a.O) continue;
             if (sh.cfg == 121 && a.K > 2048) continue;           // its K loop is no faster per step than that of 256 x 192: only pays while the fixed cost of a tile dominates
@@ -650,39 +645,51 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
         }
         const long long n96 = (long long)((a.tokens + 127) / 128) * ((a.O + 95) / 96);
         if (pick != 0) cfg = pick;
+        else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
         else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
         else if (n96 <= 256) cfg = (k256 && a.K >= 1536) ? 113 : 115;   // one round: 256-column stages for a long K (fewer, larger requests), else four wavefronts of 64 x 48
-        else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
         else cfg = 116;                                          // 128 x 96, two workgroups per CU
     }
-    if (cfg == 113) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(a, st);
-    if (cfg == 105) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 2>(a, st);
-    if (cfg == 119) return launch_dma_tile<N, M, BITS, 64, 96, 2, 2, 3, 2>(a, st);
     if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
     if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
-    if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
-    if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(a, st);
     if (cfg == 115) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
     if (cfg == 117) return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
-    if (cfg == 121) return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
-    if constexpr (U::IDENTITY) {                                 // further shapes, kept selectable for tuning
-        switch (cfg) {
-            case 101: return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 4, 1>(a, st);
-            case 109: return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 6, 1>(a, st);
-            default: break;
-        }
+    if constexpr (!U::DUAL) {
+        if (cfg == 113) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(a, st);
+        if (cfg == 105) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 2>(a, st);
+        if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
+        if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(a, st);
+        if (cfg == 121) return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
     }
     return false;
 }
 
 }  // namespace
 
-// Returns true when it launched a kernel for this problem.
-bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg)
+// One translation unit per set of patterns (NM_DMA_SET, given on the command line), so that the
+// many instantiations compile in parallel.  Returns true when it launched a kernel.
+#define NM_CAT2(a, b) a##b
+#define NM_CAT(a, b) NM_CAT2(a, b)
+bool NM_CAT(launch_gemm_dma_set, NM_DMA_SET)(const GemmArgs& a, hipStream_t st, int cfg)
 {
 #define NM_CASE(n, m, b) if (a.N == n && a.M == m && a.bits == b) return launch_dma_pattern<n, m, b>(a, st, cfg)
-    NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4);
-    NM_CASE(1, 8, 8); NM_CASE(2, 8, 8); NM_CASE(1, 8, 4); NM_CASE(2, 8, 4);
+#if NM_DMA_SET == 0
+    NM_CASE(2, 4, 8);
+#elif NM_DMA_SET == 1
+    NM_CASE(1, 4, 8); NM_CASE(2, 4, 4);
+#elif NM_DMA_SET == 2
+    NM_CASE(1, 4, 4); NM_CASE(1, 8, 8);
+#elif NM_DMA_SET == 3
+    NM_CASE(2, 8, 8); NM_CASE(1, 8, 4);
+#elif NM_DMA_SET == 4
+    NM_CASE(2, 8, 4);
+#elif NM_DMA_SET == 5
+    NM_CASE(4, 4, 8); NM_CASE(4, 4, 4); NM_CASE(3, 4, 8);
+#elif NM_DMA_SET == 6
+    NM_CASE(3, 4, 4); NM_CASE(4, 8, 8); NM_CASE(4, 8, 4);
+#else
+#error "NM_DMA_SET must be 0 .. 6"
+#endif
 #undef NM_CASE
     return false;
 }
