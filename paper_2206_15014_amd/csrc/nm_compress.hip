@@ -403,6 +403,16 @@ compress_rows(const float* __restrict__ W, int rows, int cols, int ldw,
     else encode_row(Divisor<false>{s, 0.0f});
 }
 
+// Workgroup -> its share of the rows.  Consecutive workgroups of a launch go to different XCDs
+// (eight, each with an L2 of its own).  In the tiled layout the 16 rows of a block share every
+// 128-byte line of the output, so the workgroups that write one block must sit on one XCD for the
+// line to leave its L2 whole instead of in eight masked pieces: workgroup i of n (n a multiple of
+// 8) takes share (i % 8) * (n / 8) + i / 8, which gives every XCD one contiguous range of rows.
+__device__ __forceinline__ int xcd_block(int i, int n, int flags)
+{
+    return (flags & TILED_LAYOUT) ? (i & 7) * (n >> 3) + (i >> 3) : i;
+}
+
 template <int N, int M, int BITS, int WPR, int RES>
 __global__ void __launch_bounds__(256)
 compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
@@ -410,7 +420,8 @@ compress_wave_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
                      int vstride_dw, int mstride_dw, int flags)      // GIVEN_SCALES: scales[] holds the rows' scales already
 {
     __shared__ float part[4];
-    compress_rows<N, M, BITS, RES, false>(W, rows, cols, ldw, vals, meta, scales, vstride_dw, mstride_dw, flags, WPR, blockIdx.x, part);
+    compress_rows<N, M, BITS, RES, false>(W, rows, cols, ldw, vals, meta, scales, vstride_dw, mstride_dw, flags, WPR,
+                                          xcd_block((int)blockIdx.x, (int)gridDim.x, flags), part);
 }
 
 // Several matrices of one pattern in one launch: the descriptors travel by value in the kernel
@@ -423,7 +434,7 @@ struct BatchItem {
     uint32_t* vals;
     uint32_t* meta;
     float* scales;
-    int rows, cols, ldw, vstride_dw, mstride_dw, wpr, first_block, pad;
+    int rows, cols, ldw, vstride_dw, mstride_dw, wpr, first_block, blocks;
 };
 struct BatchArgs {
     BatchItem it[BATCH_MAX];
@@ -442,7 +453,7 @@ compress_batch_kernel(const BatchArgs b)
         if ((int)blockIdx.x >= b.it[k].first_block) i = k;     // uniform: scalar loads from the argument segment
     const BatchItem& t = b.it[i];
     compress_rows<N, M, BITS, RES, ONCE>(t.W, t.rows, t.cols, t.ldw, t.vals, t.meta, t.scales, t.vstride_dw, t.mstride_dw, b.flags,
-                                   t.wpr, (int)blockIdx.x - t.first_block, part);
+                                   t.wpr, xcd_block((int)blockIdx.x - t.first_block, t.blocks, b.flags), part);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -530,7 +541,9 @@ void launch_wave_res(const float* W, int rows, int cols, int ldw, uint32_t* v, u
 {
     constexpr int RPB = 4 / WPR;
     const int rows_out = (flags & TILED_LAYOUT) ? ((rows + 15) & ~15) : rows;      // the tiled layout pads the rows
-    hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, WPR, RES>), dim3((rows_out + RPB - 1) / RPB), dim3(256), 0, st,
+    int blocks = (rows_out + RPB - 1) / RPB;
+    if (flags & TILED_LAYOUT) blocks = (blocks + 7) & ~7;      // whole rounds over the XCDs, see xcd_block
+    hipLaunchKernelGGL((compress_wave_kernel<N, M, BITS, WPR, RES>), dim3(blocks), dim3(256), 0, st,
                        W, rows, cols, ldw, v, m, scales, vstride / 4, mstride / 4, flags);
 }
 
@@ -672,9 +685,11 @@ int launch_compress_batch(const CompressItem* items, int count, int N, int M, in
         BatchItem& t = b.it[b.count++];
         t.W = c.W; t.vals = (uint32_t*)c.vals; t.meta = (uint32_t*)c.meta; t.scales = c.scales;
         t.rows = c.rows; t.cols = c.cols; t.ldw = c.ldw; t.vstride_dw = (int)pv.stride / 4; t.mstride_dw = (int)pm.stride / 4;
-        t.wpr = wpr; t.first_block = blocks; t.pad = 0;
+        t.wpr = wpr; t.first_block = blocks;
         const int rows_out = layout ? ((c.rows + 15) & ~15) : c.rows;     // the tiled layout pads the rows
-        blocks += (rows_out + rpb - 1) / rpb;
+        t.blocks = (rows_out + rpb - 1) / rpb;
+        if (layout) t.blocks = (t.blocks + 7) & ~7;                       // whole rounds over the XCDs, see xcd_block
+        blocks += t.blocks;
         max_mine = mine > max_mine ? mine : max_mine;
         if (b.count == BATCH_MAX) flush();
     }
