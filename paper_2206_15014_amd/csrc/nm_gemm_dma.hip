@@ -619,7 +619,6 @@ template <int N, int M, int BITS>
 bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 {
     using U = Unit<N, M, BITS>;
-    const bool k256 = (a.K % 256) == 0;
     if (cfg == 0) {
         // Cost of a tile shape = rounds over the 256 CUs x tile area x the shape's cost per
         // multiply-add relative to 256 x 192 (the L2->LDS fill per multiply-add, measured: 256 x 128
@@ -638,17 +637,23 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
             if (U::DUAL && sh.cfg != 0 && sh.cfg != 117) continue;   // two operands per unit: the wide wave tiles would not fit the registers
             const long long ct = (a.O + sh.bo - 1) / sh.bo;
             if (sh.cfg != 0 && (ct * sh.bo - a.O) * 8 > a.O) continue;
-            if (sh.cfg == 121 && a.K > 2048) continue;           // its K loop is no faster per step than that of 256 x 192: only pays while the fixed cost of a tile dominates
             const long long n = (long long)((a.tokens + sh.bt - 1) / sh.bt) * ct;
             const long long c = ((n + 255) / 256) * sh.bt * sh.bo * sh.cost;
             if (best < 0 || c * 105 < best * 100) { best = c; pick = sh.cfg; }
         }
         const long long n96 = (long long)((a.tokens + 127) / 128) * ((a.O + 95) / 96);
-        if (pick != 0) cfg = pick;
+        const long long n64x96 = (long long)((a.tokens + 63) / 64) * ((a.O + 95) / 96);
+        const long long n64x48 = (long long)((a.tokens + 63) / 64) * ((a.O + 47) / 48);
+        // A problem of fewer than 128 tiles of 128 x 96 leaves half the chip idle while every workgroup
+        // pulls its whole share of X and W through one CU's fill path: the smallest tile that still
+        // runs in one round (measured on 128 to 384 tokens: 128 x 768 -> 768 5.1 -> 4.2 us,
+        // 128 x 4096 -> 1024 10.9 -> 9.3 us, 384 x 1024 -> 3072 6.1 -> 5.0 us).
+        if (!U::DUAL && n96 < 128 && n64x48 <= 256) cfg = 130;
+        else if (!U::DUAL && n96 < 128 && n64x96 <= 256) cfg = 132;
+        else if (pick != 0) cfg = pick;
         else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
         else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
-        else if (n96 <= 256) cfg = (k256 && a.K >= 1536) ? 113 : 115;   // one round: 256-column stages for a long K (fewer, larger requests), else four wavefronts of 64 x 48
-        else cfg = 116;                                          // 128 x 96, two workgroups per CU
+        else cfg = 116;                                          // 128 x 96, eight wavefronts
     }
     if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
     if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
@@ -660,6 +665,10 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
         if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
         if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(a, st);
         if (cfg == 121) return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
+        // small tiles for problems of a few output tiles (few tokens): more workgroups, each with a
+        // smaller share of X and W to pull through its CU's fill path
+        if (cfg == 130) return launch_dma_tile<N, M, BITS, 64, 48, 2, 1, 4, 1>(a, st);
+        if (cfg == 132) return launch_dma_tile<N, M, BITS, 64, 96, 2, 2, 4, 1>(a, st);
     }
     return false;
 }
