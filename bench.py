@@ -42,14 +42,19 @@ def parse():
     ap.add_argument("--no-streaming-leg", action="store_true",
                     help="skip the second timed leg (buffer sets rotated over more than the 256 MB Infinity Cache)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
-    ap.add_argument("--workload", choices=["bert_base", "bert_large", "hetero", "single", "copy"], default="bert_base",
+    ap.add_argument("--workload", choices=["bert_base", "bert_large", "hetero", "table4", "table3", "single", "copy"], default="bert_base",
                     help="bert_base: the four GEMMs of a BERT-base layer at 4096 tokens (the benchmark); "
                          "bert_large: those of a BERT-large layer at 32x384 = 12288 tokens (the third workload of the "
                          "task's list; not the headline configuration); "
                          "hetero: the 48 GEMMs of a 12-layer BERT-base encoder with a seeded mix of 2:4 / 1:4 / 2:8 and "
                          "int8 / int4 schemes at 4096 tokens (the fifth workload of the task's list); "
+                         "table4: the 72 GEMMs (query, key, value separately) of a 12-layer BERT-base encoder under one of the "
+                         "configurations the paper's search chose (Sec. 5.4: dense and 2:4 components, 4- and 8-bit), see --task; "
+                         "table3: the batch x sequence sweep of the paper's inference table (Sec. 5.3) on BERT-large, the 96 "
+                         "GEMMs of 24 layers enqueued back to back for every token count; "
                          "single: one 768x768 layer at 128 tokens (the skinny shape, for profiling); "
                          "copy: a plain 256 MiB device copy (calibrates the HBM traffic counters)")
+    ap.add_argument("--task", default="MNLI", help="row of the Sec. 5.4 table for --workload table4 (MNLI, SST-2, QNLI, QQP, CoLA, STS-B, MRPC, RTE)")
     ap.add_argument("--tokens", type=int, default=None,
                     help="token count for the bert_base / bert_large layer sets instead of the workload's own (batch x "
                          "sequence length of the paper's inference table, e.g. 128 x 384 = 49152): a sweep, not the benchmark")
@@ -62,6 +67,81 @@ def parse():
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph",
                     help="graph: the launches of a step are captured once in a HIP graph and replayed")
     return ap.parse_args()
+
+
+def table3_sweep(args, lib, layout):
+    """Sec. 5.3's inference table as a workload: BERT-large, batch {1, 32, 64, 128} x sequence {128, 384}, linear layers only.
+    For every token count the 96 nm_gemm calls of 24 encoder layers (each layer with weight matrices of its own, compressed
+    beforehand as at deployment; bias, bf16 output; activations handed on through one buffer per width) are captured in one
+    HIP graph and replayed.  Prints one JSON line: the time of the 24-layer stack per token count."""
+    import dataclasses
+    import torch
+
+    import paper_2206_15014_amd as nm
+    from paper_2206_15014_amd import synth
+    from paper_2206_15014_amd.binding import NM_OUT_BF16
+
+    dev = torch.device("cuda:0")
+    layers = 24
+    shapes = synth.config3()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(3)
+    packed = []                                             # [layer][gemm] -> (vals, meta, scales, bias)
+    for _ in range(layers):
+        row = []
+        for g in shapes:
+            W = torch.randn((g.O, g.K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+            v, m, sc = nm.nm_compress(W, g.N, g.M, g.bits, layout=layout)
+            row.append((v, m, sc, torch.randn(g.O, generator=gen, device=dev, dtype=torch.float32) * 0.02))
+        packed.append(row)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    sweep = []
+    token_counts = [args.tokens] if args.tokens else [1 * 128, 1 * 384, 32 * 128, 64 * 128, 32 * 384, 128 * 128, 64 * 384, 128 * 384]
+    for T in token_counts:
+        X = {K: torch.randint(-127, 128, (T, K), generator=gen, device=dev, dtype=torch.int8) for K in (1024, 4096)}
+        out = {g.name: torch.empty((T, g.O), dtype=torch.bfloat16, device=dev) for g in shapes}
+
+        def enqueue(st):
+            for row in packed:
+                for g, (v, m, sc, b) in zip(shapes, row):
+                    rc = lib.nm_gemm(X[g.K].data_ptr(), T, g.K, g.K, 0.05, None, v.data_ptr(), m.data_ptr(), sc.data_ptr(), g.O, g.N, g.M,
+                                     g.bits, layout, b.data_ptr(), None, out[g.name].data_ptr(), NM_OUT_BF16, g.O, st)
+                    if rc != 0:
+                        raise RuntimeError("nm_gemm failed: %s" % nm.nm_status_string(rc))
+
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            enqueue(side.cuda_stream)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                enqueue(side.cuda_stream)
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(max(args.warmup // 10, 2)):
+            graph.replay()
+        torch.cuda.synchronize()
+        reps = max(args.steps // 10, 5)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / reps
+        ops = layers * sum(dataclasses.replace(g, T=T).dense_ops for g in shapes)
+        sweep.append({"tokens": T, "ms_24_layers": round(ms, 4), "us_per_gemm": round(ms * 1e3 / (4 * layers), 2),
+                      "dense_equiv_tops": round(ops / (ms * 1e-3) / 1e12, 1)})
+        del graph, X, out
+    head = [r for r in sweep if r["tokens"] == 32 * 384] or sweep[-1:]
+    print(json.dumps({
+        "metric": "dense-equivalent int8 TOPS of N:M sparse GEMM (BERT shapes) + % of int8 roofline",
+        "value": head[0]["dense_equiv_tops"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head[0]["ms_24_layers"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "BERT-large, 24 encoder layers x (QKV, attn-out, FFN-up, FFN-down) = 96 nm_gemm calls back to back in one HIP "
+                               "graph, 2:4 int8, bias, bf16 out, %s layout; step = the 24-layer stack at 32x384=12288 tokens; sweep = the "
+                               "batch x sequence grid of the paper's inference table (Sec. 5.3)" % args.layout},
+        "pct_of_int8_dense_peak": round(100.0 * head[0]["dense_equiv_tops"] / INT8_DENSE_PEAK_TOPS, 2),
+        "sweep": sweep}))
 
 
 def main():
@@ -92,10 +172,18 @@ def main():
                           "launches": max(args.steps, 1)}))
         return
     lib = binding.raw()
+    if args.workload == "table3":
+        table3_sweep(args, lib, layout)
+        return
     if args.workload == "single":
         g1 = synth.config1_tensors()[0]
         gemms = [synth.Gemm("single", g1.T, g1.K, g1.O, g1.N, g1.M, g1.bits, (1, 0, 0), outliers=False)]
         workload_name = "single 768x768 linear layer, 128 tokens, 2:4 int8"
+    elif args.workload == "table4":
+        gemms = synth.table4_encoder(args.task)
+        workload_name = ("12-layer BERT-base encoder under the configuration chosen for %s in the paper's Sec. 5.4 table (%s for query, key, "
+                         "value, attention output, FFN 1, FFN 2; Q = dense, S = 2:4), 72 GEMMs, 32x128=4096 tokens, activation and output "
+                         "buffers shared between layers" % (args.task, " ".join(synth.TABLE4[args.task])))
     elif args.workload == "hetero":
         gemms = synth.config5()
         workload_name = ("heterogeneous 12-layer BERT-base encoder, 48 GEMMs, schemes drawn from {2:4 i8, 1:4 i8, 2:4 i4, "
@@ -125,7 +213,7 @@ def main():
     # The 12-layer encoder keeps one activation buffer per reduction width and one output buffer per
     # layer shape, as an encoder does whose layers hand their activations on; the one-layer sets
     # give every GEMM its own.
-    shared = args.workload == "hetero"
+    shared = args.workload in ("hetero", "table4")
     acts, outs = {}, {}
     for g in gemms:
         W = synth.weights(g)

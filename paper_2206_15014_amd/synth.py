@@ -171,6 +171,37 @@ def config5(lo: float = 0.875, hi: float = 0.90) -> List[Gemm]:
     raise RuntimeError("config-5 sampler found no admissible draw")
 
 
+# ---- the chosen heterogeneous configurations of Sec. 5.4 (dense and sparse components mixed) ----
+
+# Component schemes as the table of Sec. 5.4 names them: Q = dense (no sparsity), S = 2 of 4 kept;
+# 4 / 8 = weight bits.  Columns: query, key, value, attention output, FFN 1, FFN 2.
+TABLE4_SCHEME = {"Q4": (4, 4, 4), "Q8": (4, 4, 8), "S4": (2, 4, 4), "S8": (2, 4, 8)}
+TABLE4 = {
+    "MNLI": ("Q4", "Q4", "Q4", "Q4", "S4", "S4"),
+    "SST-2": ("Q4", "Q8", "Q4", "S4", "Q4", "S4"),
+    "QNLI": ("Q4", "Q8", "Q4", "S4", "Q4", "S4"),
+    "QQP": ("Q4", "Q4", "Q4", "Q4", "S4", "S4"),
+    "CoLA": ("Q4", "Q8", "Q4", "Q4", "Q4", "S4"),
+    "STS-B": ("Q4", "S4", "Q4", "Q4", "S4", "S4"),
+    "MRPC": ("Q4", "S4", "Q4", "Q4", "S4", "S4"),
+    "RTE": ("Q4", "S4", "Q4", "S8", "Q4", "S4"),
+}
+
+
+def table4_encoder(task: str, T: int = 4096, H: int = 768, layers: int = 12) -> List[Gemm]:
+    """The linear layers of a BERT-base encoder under the configuration the paper's search chose for
+    `task` (Sec. 5.4): six GEMMs per layer - query, key and value separately, as the table lists
+    them - with the component's scheme, the same in every layer."""
+    names = ("query", "key", "value", "attn_out", "ffn_up", "ffn_down")
+    shapes = ((H, H), (H, H), (H, H), (H, H), (H, 4 * H), (4 * H, H))
+    out: List[Gemm] = []
+    for layer in range(layers):
+        for i, (name, (K, O), code) in enumerate(zip(names, shapes, TABLE4[task])):
+            N, M, bits = TABLE4_SCHEME[code]
+            out.append(Gemm(name, T, K, O, N, M, bits, (7, layer, i)))
+    return out
+
+
 def structured_weight_cases(K: int = 64, seed: int = 7) -> np.ndarray:
     """Rows built to hit the degenerate cases of projection and quantisation.
 

@@ -24,6 +24,19 @@ def test_accounting_reproduces_printed_ratios():
             assert abs(100 * flop - 20.8) < 0.051
 
 
+def test_table_of_chosen_configurations_is_the_printed_one():
+    rows = [l.split() for l in open(GOLDEN) if l.strip() and not l.startswith("#")]
+    assert {r[0]: tuple(r[1:7]) for r in rows} == synth.TABLE4
+    assert synth.TABLE4_SCHEME == SCHEME
+    gs = synth.table4_encoder("RTE")
+    assert len(gs) == 72 and len({g.seed for g in gs}) == 72
+    assert [(g.name, g.K, g.O, g.N, g.M, g.bits) for g in gs[:6]] == [
+        ("query", 768, 768, 4, 4, 4), ("key", 768, 768, 2, 4, 4), ("value", 768, 768, 4, 4, 4),
+        ("attn_out", 768, 768, 2, 4, 8), ("ffn_up", 768, 3072, 4, 4, 4), ("ffn_down", 3072, 768, 2, 4, 4)]
+    ratio, flop = synth.encoder_accounting([(g.N, g.M, g.bits) for g in gs], [g.K * g.O for g in gs])
+    assert abs(100 * ratio - 88.5) < 0.051 and abs(100 * flop - 25.0) < 0.051
+
+
 def test_size_column_of_glue_table():
     # Sec. 5.1 table: 324M dense encoder stack; 51.7M at 8-bit 2:4 and 31.4M at 4-bit 2:4
     # (the printed sizes carry about 1 MiB of unquantised biases / norms on top).
