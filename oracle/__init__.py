@@ -162,6 +162,30 @@ def compress_grouped(W, N, M, bits, rows_per_scale):
     return vals, meta, scales
 
 
+def dist_scales(W, N, M, bits, rows_per_scale, candidates):
+    """(scales float32 [rows], errors float64 [groups, candidates/2 + 1]): the scale of every row's
+    group that minimises the L2 distance between the kept weights and their quantised values."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    rows, cols = W.shape
+    scales = np.zeros(rows, dtype=np.float32)
+    ng = -(-rows // max(rows_per_scale, 1))
+    errors = np.zeros((ng, max(candidates, 0) // 2 + 1), dtype=np.float64)
+    _check(_load().nmo_dist_scales(_p(W), rows, cols, cols, N, M, bits, rows_per_scale, candidates, _p(scales), _p(errors)))
+    return scales, errors
+
+
+def compress_scaled(W, N, M, bits, scales):
+    """(vals, meta): compress with the per-row scales given."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    rows, cols = W.shape
+    vb, mb, _ = packed_sizes(rows, cols, N, M, bits)
+    vals = np.zeros((rows, vb // rows), dtype=np.uint8)
+    meta = np.zeros((rows, mb // rows), dtype=np.uint8)
+    _check(_load().nmo_compress_scaled(_p(W), rows, cols, cols, N, M, bits, _p(scales), _p(vals), _p(meta)))
+    return vals, meta
+
+
 def decompress(vals, meta, rows, cols, N, M, bits):
     vals = np.ascontiguousarray(vals, dtype=np.uint8)
     meta = np.ascontiguousarray(meta, dtype=np.uint8)

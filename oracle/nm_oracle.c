@@ -31,6 +31,11 @@
  *                      the scale group / largest code; "group" = a run of output
  *                      neurons, Sec. 4: 32 by default) and the scaled dual update
  *                      U <- U + W - Z of the ADMM decomposition.
+ *   nmo_dist_scales    Sec. 3.3.1, the second scale rule ("ADMM-Dist"): the scale that
+ *                      minimises the L2 distance between the quantised and the raw
+ *                      parameters, searched over a grid of candidates (the paper gives
+ *                      no algorithm: the grid is this build's reading, PARITY UNPINNED
+ *                      by the paper beyond "the chosen scale has the least error").
  *   nmo_requant        Sec. 5.3 (activations are 8-bit integers) with the scalar
  *                      quantiser of Sec. 3.3, Eq. 5 (o = 0) applied to a layer's
  *                      output, so that the next layer reads int8 again.
@@ -241,6 +246,80 @@ int nmo_compress_grouped(const float *W, int rows, int cols, int ldw, int N, int
         for (int r = r0; r < r1; ++r) scales[r] = all_zero ? 1.0f : s;
     }
     return nmo_compress_given(W, rows, cols, ldw, N, M, bits, vals, meta, scales);
+}
+
+/* project, quantise and pack with scales the caller supplies, one per row (e.g. those of nmo_dist_scales). */
+int nmo_compress_scaled(const float *W, int rows, int cols, int ldw, int N, int M, int bits,
+                        const float *scales, uint8_t *vals, uint8_t *meta)
+{
+    return nmo_compress_given(W, rows, cols, ldw, N, M, bits, vals, meta, scales);
+}
+
+/*
+ * Sec. 3.3.1, second rule: per scale group (rows_per_scale consecutive rows, the
+ * last group may be shorter) the scale that minimises the squared L2 distance
+ * between the parameters and their quantised-then-dequantised values.  The paper
+ * states the criterion and no algorithm; the reading used here:
+ *   - the distance is taken over the entries the N:M projection keeps (the pruned
+ *     ones are zero whatever the scale);
+ *   - candidates are s_c = (s_max * c) / C for c = C/2 .. C, with C = `candidates`
+ *     (even, 2 .. 64) and s_max the max-rule scale of the group (largest magnitude /
+ *     largest code, 1 for an all-zero group): the max rule itself (c = C) down to
+ *     half of it, which clips the largest entries in exchange for finer steps;
+ *     two fp32 operations per candidate, a multiplication and then a division;
+ *   - per entry: q = Eq. 5 with s_c (fp32 division, round half to even, clamp),
+ *     e = w - s_c * q and e * e in double; the group's error is their plain sum in
+ *     double, rows in order, columns in order;
+ *   - the least error wins; between equal errors the larger scale.
+ * scales[] receives every row's scale; errors, when given, the group errors as
+ * [group][C/2 + 1] (index c - C/2).
+ */
+int nmo_dist_scales(const float *W, int rows, int cols, int ldw, int N, int M, int bits,
+                    int rows_per_scale, int candidates, float *scales, double *errors)
+{
+    int rc = check_pattern(rows, cols, N, M, bits);
+    if (rc) return rc;
+    if (!W || !scales) return NMO_ERR_NULL;
+    if (ldw < cols || rows_per_scale < 1 || candidates < 2 || candidates > 64 || candidates % 2) return NMO_ERR_DIM;
+    int groups = cols / M, nc = candidates / 2 + 1;
+    for (int r = 0; r < rows; ++r)
+        for (int c = 0; c < cols; ++c)
+            if (!isfinite(W[(size_t)r * ldw + c])) return NMO_ERR_NONFINITE;
+    for (int r0 = 0, gi = 0; r0 < rows; r0 += rows_per_scale, ++gi) {
+        int r1 = r0 + rows_per_scale < rows ? r0 + rows_per_scale : rows;
+        float amax = 0.0f;
+        for (int r = r0; r < r1; ++r)
+            for (int c = 0; c < cols; ++c)
+                if (fabsf(W[(size_t)r * ldw + c]) > amax) amax = fabsf(W[(size_t)r * ldw + c]);
+        float qmax = (float)((1 << (bits - 1)) - 1);
+        volatile float smax_v = amax / qmax;
+        float smax = amax == 0.0f ? 1.0f : smax_v;
+        double best_err = 0.0;
+        float best_s = smax;
+        for (int c = candidates; c >= candidates / 2; --c) {      /* from the largest scale down: a tie keeps the larger */
+            volatile float num = smax * (float)c;
+            volatile float sc = num / (float)candidates;
+            double err = 0.0;
+            for (int r = r0; r < r1; ++r)
+                for (int g = 0; g < groups; ++g) {
+                    const float *w = W + (size_t)r * ldw + (size_t)g * M;
+                    uint8_t kept[8];
+                    project_group(w, N, M, kept);
+                    for (int j = 0; j < N; ++j) {
+                        float x = w[kept[j]];
+                        double e = (double)x - (double)sc * (double)nmo_quantize_one(x, sc, bits);
+                        err += e * e;
+                    }
+                }
+            if (errors) errors[(size_t)gi * nc + (c - candidates / 2)] = err;
+            if (c == candidates || err < best_err) {
+                best_err = err;
+                best_s = sc;
+            }
+        }
+        for (int r = r0; r < r1; ++r) scales[r] = best_s;
+    }
+    return NMO_OK;
 }
 
 /* The same with one scale per row (the library's default granularity). */
