@@ -36,7 +36,8 @@ enum nm_status {
     NM_ERR_ALIGN = -6,    /* pointer or leading dimension violates a stated alignment      */
     NM_ERR_HIP = -7,      /* the HIP runtime reported an error at launch                   */
     NM_ERR_LAYOUT = -8,   /* unknown layout code                                           */
-    NM_ERR_SCALE = -9     /* a host-side scale that is not a positive finite number        */
+    NM_ERR_SCALE = -9,    /* a host-side scale that is not a positive finite number        */
+    NM_ERR_WORKSPACE = -10 /* a workspace smaller than its size query asks for             */
 };
 
 /*
@@ -127,6 +128,44 @@ int nm_compress_grouped(const float *W_dev, int rows, int cols, int ldw,
                         int N, int M, int bits, int layout, int rows_per_scale,
                         void *vals_dev, void *meta_dev, float *scales_dev,
                         void *hip_stream);
+
+/*
+ * The paper's second scale rule (Sec. 3.3.1, "ADMM-Dist": choose the scale that minimises the L2
+ * distance between the quantised and the raw parameters), per group of rows_per_scale consecutive
+ * output neurons.  The paper states the criterion, not an algorithm; the library searches a grid:
+ *
+ *   s_max   the max-rule scale of the group (largest |w| / (2^(bits-1)-1), 1 for an all-zero group)
+ *   s_c     = (s_max * c) / candidates for c = candidates/2 .. candidates   (fp32: a multiplication,
+ *             then a division): from the max rule itself down to half of it
+ *   err(c)  = sum over the entries the N:M projection keeps (as nm_compress keeps them) of
+ *             (w - s_c * q)^2 with q = clamp(rne(w / s_c)), formed and summed in double
+ *   scale   = the s_c of least error; between equal errors the larger scale
+ *
+ * scales_dev[rows] receives every row's scale (the rows of a group hold the same value), ready
+ * for nm_compress_scaled.  Errors are summed in a fixed order that is not the plain left-to-right
+ * one, so two candidates whose errors agree to about 1e-15 relative may be ranked either way.
+ *
+ *   candidates      even, 2 .. 64.
+ *   workspace_dev   device scratch of nm_scale_search_workspace_bytes(rows, candidates) bytes
+ *                   (the rows' partial errors, [rows][candidates/2 + 1] doubles), 8-byte aligned,
+ *                   owned by the caller; contents before and after the call do not matter.
+ * Errors as for nm_compress_grouped; NM_ERR_WORKSPACE when workspace_bytes is too small.
+ */
+size_t nm_scale_search_workspace_bytes(int rows, int candidates);
+
+int nm_scale_search(const float *W_dev, int rows, int cols, int ldw,
+                    int N, int M, int bits, int rows_per_scale, int candidates,
+                    float *scales_dev, void *workspace_dev, size_t workspace_bytes,
+                    void *hip_stream);
+
+/*
+ * nm_compress with the scales given: scales_dev[rows] is an INPUT (one scale per row, each a
+ * positive finite float: those of nm_scale_search, or a caller's own), everything else as
+ * nm_compress - same projection, same quantiser, same packed formats.
+ */
+int nm_compress_scaled(const float *W_dev, int rows, int cols, int ldw,
+                       int N, int M, int bits, int layout, const float *scales_dev,
+                       void *vals_dev, void *meta_dev, void *hip_stream);
 
 /*
  * nm_compress on several matrices of one pattern in one call - the weight matrices of an encoder

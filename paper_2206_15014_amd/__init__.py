@@ -13,10 +13,12 @@ from .binding import (  # noqa: F401
     nm_compress,
     nm_compress_batch,
     nm_compress_grouped,
+    nm_compress_scaled,
     nm_decompress_i8,
     nm_gemm,
     nm_gemm_q8,
     nm_packed_sizes,
     nm_project,
+    nm_scale_search,
     nm_status_string,
 )

@@ -62,6 +62,12 @@ def _load():
     lib.nm_gemm.restype = c_int
     lib.nm_gemm.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp, c_vp,
                             c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_int, c_int, c_vp]
+    lib.nm_compress_scaled.restype = c_int
+    lib.nm_compress_scaled.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
+    lib.nm_scale_search_workspace_bytes.restype = ctypes.c_size_t
+    lib.nm_scale_search_workspace_bytes.argtypes = [c_int, c_int]
+    lib.nm_scale_search.restype = c_int
+    lib.nm_scale_search.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, ctypes.c_size_t, c_vp]
     lib.nm_project.restype = c_int
     lib.nm_project.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_int, c_vp, c_vp]
     lib.nm_gemm_q8.restype = c_int
@@ -157,6 +163,33 @@ def nm_compress_grouped(W, N: int, M: int, bits: int, rows_per_scale: int, vals=
                                      _ptr(vals), _ptr(meta), _ptr(scales), _stream(stream))
     if rc:
         raise NMError(rc, "nm_compress_grouped")
+    return vals, meta, scales
+
+
+def nm_scale_search(W, N: int, M: int, bits: int, rows_per_scale: int, candidates: int, scales=None, workspace=None, stream=None):
+    """The distance-minimising scale of every row's group (float32 [rows]); workspace: uint8 CUDA tensor of
+    nm_scale_search_workspace_bytes(rows, candidates) bytes, allocated here when not given."""
+    import torch
+    rows, cols = W.shape
+    if scales is None:
+        scales = torch.empty(rows, dtype=torch.float32, device=W.device)
+    if workspace is None:
+        workspace = torch.empty(max(_load().nm_scale_search_workspace_bytes(rows, candidates), 8), dtype=torch.uint8, device=W.device)
+    rc = _load().nm_scale_search(_ptr(W), rows, cols, W.stride(0), N, M, bits, rows_per_scale, candidates, _ptr(scales),
+                                 _ptr(workspace), workspace.numel(), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_scale_search")
+    return scales
+
+
+def nm_compress_scaled(W, N: int, M: int, bits: int, scales, vals=None, meta=None, stream=None, layout: int = NM_LAYOUT_ROWS):
+    """nm_compress with the per-row scales given (float32 CUDA tensor [rows]); returns (vals, meta, scales)."""
+    rows, cols = W.shape
+    vals, meta, scales = _packed_buffers(rows, cols, N, M, bits, layout, W.device, vals, meta, scales)
+    rc = _load().nm_compress_scaled(_ptr(W), rows, cols, W.stride(0), N, M, bits, layout, _ptr(scales),
+                                    _ptr(vals), _ptr(meta), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_compress_scaled")
     return vals, meta, scales
 
 

@@ -78,6 +78,39 @@ int nm_compress_grouped(const float* W_dev, int rows, int cols, int ldw, int N, 
                                static_cast<hipStream_t>(hip_stream));
 }
 
+int nm_compress_scaled(const float* W_dev, int rows, int cols, int ldw, int N, int M, int bits, int layout,
+                       const float* scales_dev, void* vals_dev, void* meta_dev, void* hip_stream)
+{
+    const int rc = check_pattern(rows, cols, N, M, bits, layout);
+    if (rc) return rc;
+    if (!W_dev || !vals_dev || (!meta_dev && N < M) || !scales_dev) return NM_ERR_NULL;
+    if (ldw < cols) return NM_ERR_DIM;
+    if ((uintptr_t)W_dev % 4 || (uintptr_t)scales_dev % 4) return NM_ERR_ALIGN;
+    canonical_dense(N, M);
+    // rows_per_scale 0: the kernels quantise with the scales they find (and leave the array as it is)
+    return nm::launch_compress(W_dev, rows, cols, ldw, N, M, bits, layout, 0, vals_dev, meta_dev, const_cast<float*>(scales_dev),
+                               static_cast<hipStream_t>(hip_stream));
+}
+
+size_t nm_scale_search_workspace_bytes(int rows, int candidates)
+{
+    if (rows <= 0 || candidates < 2 || candidates > 64 || candidates % 2) return 0;
+    return (size_t)rows * (size_t)(candidates / 2 + 1) * sizeof(double);
+}
+
+int nm_scale_search(const float* W_dev, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale, int candidates,
+                    float* scales_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream)
+{
+    const int rc = check_pattern(rows, cols, N, M, bits, NM_LAYOUT_ROWS);
+    if (rc) return rc;
+    if (!W_dev || !scales_dev || !workspace_dev) return NM_ERR_NULL;
+    if (ldw < cols || rows_per_scale < 1 || candidates < 2 || candidates > 64 || candidates % 2) return NM_ERR_DIM;
+    if ((uintptr_t)W_dev % 4 || (uintptr_t)scales_dev % 4 || (uintptr_t)workspace_dev % 8) return NM_ERR_ALIGN;
+    if (workspace_bytes < nm_scale_search_workspace_bytes(rows, candidates)) return NM_ERR_WORKSPACE;
+    return nm::launch_scale_search(W_dev, rows, cols, ldw, N, M, bits, rows_per_scale, candidates, scales_dev,
+                                   static_cast<double*>(workspace_dev), static_cast<hipStream_t>(hip_stream));
+}
+
 int nm_compress_batch(const nm_compress_item* items, int count, int N, int M, int bits, int layout, void* hip_stream)
 {
     if (count <= 0 || count > NM_COMPRESS_BATCH_MAX_ITEMS) return NM_ERR_DIM;
@@ -213,6 +246,7 @@ const char* nm_status_string(int status)
         case NM_ERR_HIP: return "HIP launch error";
         case NM_ERR_LAYOUT: return "unknown layout of the packed buffers";
         case NM_ERR_SCALE: return "scale is not a positive finite number";
+        case NM_ERR_WORKSPACE: return "workspace smaller than the size query says";
         default: return "unknown status";
     }
 }

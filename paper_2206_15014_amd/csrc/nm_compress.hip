@@ -599,9 +599,10 @@ int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, i
     begin_launch();
     // One scale per group of rows: the scales are computed first (row maxima, then the groups'),
     // and the kernels below quantise with what they find in scales[].
-    const int given = rows_per_scale > 1 ? 1 : 0;
+    // rows_per_scale 0: scales[] already holds the scales to use (the caller's own)
+    const int given = rows_per_scale != 1 ? 1 : 0;
     const int flags = (given ? GIVEN_SCALES : 0) | (layout ? TILED_LAYOUT : 0);
-    if (given) launch_group_scales(W, rows, cols, ldw, rows_per_scale, (float)((1 << (bits - 1)) - 1), scales, st);
+    if (rows_per_scale > 1) launch_group_scales(W, rows, cols, ldw, rows_per_scale, (float)((1 << (bits - 1)) - 1), scales, st);
     if (wave_kernel_takes(W, cols, ldw, N, M, bits, vals, meta)) {
         done = true;
 #define NM_CASE(n, m, b) else if (N == n && M == m && bits == b) launch_wave<n, m, b>(W, rows, cols, ldw, vals, meta, scales, vstride, mstride, flags, st)

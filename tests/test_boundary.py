@@ -18,7 +18,8 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", header))
     assert names >= {"nm_packed_sizes", "nm_compress", "nm_compress_grouped", "nm_compress_batch", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8",
-                     "nm_project", "nm_absmax_to_scale", "nm_status_string"}
+                     "nm_project", "nm_absmax_to_scale", "nm_scale_search", "nm_scale_search_workspace_bytes", "nm_compress_scaled",
+                     "nm_status_string"}
     lib = ctypes.CDLL(binding.library_path())
     for n in names:
         assert hasattr(lib, n), n
@@ -115,6 +116,21 @@ def test_entry_points_validate_before_launch():
     assert q(out=P + 2) == -6
     assert q(amax=P + 1) == -6
     assert q(sod=P + 1) == -6
+    lib.nm_scale_search_workspace_bytes.restype = ctypes.c_size_t
+    assert lib.nm_scale_search_workspace_bytes(768, 32) == 768 * 17 * 8
+    assert lib.nm_scale_search_workspace_bytes(768, 33) == 0 and lib.nm_scale_search_workspace_bytes(0, 32) == 0
+    ss = lambda **k: lib.nm_scale_search(*[k.get(n, d) for n, d in [
+        ("W", P), ("rows", 8), ("cols", 8), ("ldw", 8), ("N", 2), ("M", 4), ("bits", 8), ("rps", 4), ("C", 16), ("sc", P),
+        ("ws", P), ("wsb", 8 * 9 * 8), ("st", None)]])
+    assert ss(W=None) == -1 and ss(sc=None) == -1 and ss(ws=None) == -1
+    assert ss(C=0) == -2 and ss(C=7) == -2 and ss(C=66) == -2 and ss(rps=0) == -2 and ss(ldw=4) == -2
+    assert ss(N=5) == -3 and ss(bits=3) == -4
+    assert ss(ws=P + 4) == -6 and ss(W=P + 1) == -6
+    assert ss(wsb=8 * 9 * 8 - 1) == -10
+    cs = lambda **k: lib.nm_compress_scaled(*[k.get(n, d) for n, d in [
+        ("W", P), ("rows", 8), ("cols", 8), ("ldw", 8), ("N", 2), ("M", 4), ("bits", 8), ("layout", 0), ("sc", P), ("v", P), ("m", P), ("st", None)]])
+    assert cs(sc=None) == -1 and cs(v=None) == -1 and cs(m=None) == -1 and cs(m=None, N=4, W=None) == -1
+    assert cs(ldw=4) == -2 and cs(layout=1) == -3 and cs(layout=5) == -8 and cs(sc=P + 2) == -6
     assert lib.nm_absmax_to_scale(None, P, 0, None) == -1 and lib.nm_absmax_to_scale(P, None, 0, None) == -1
     assert lib.nm_absmax_to_scale(P, P + 2, 0, None) == -6
     assert lib.nm_absmax_to_scale(P, P, 0, None) == -2
@@ -122,5 +138,5 @@ def test_entry_points_validate_before_launch():
 
 def test_status_strings():
     assert nm.nm_status_string(0) == "ok"
-    assert all(nm.nm_status_string(c) not in ("", "unknown status") for c in range(-9, 1))
+    assert all(nm.nm_status_string(c) not in ("", "unknown status") for c in range(-10, 1))
     assert nm.nm_status_string(-99) == "unknown status"

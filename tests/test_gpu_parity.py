@@ -701,6 +701,64 @@ def test_compress_grouped_matches_oracle_and_feeds_the_gemm(N, M, bits, rps, lay
     check_outputs(acc_ref, sx, ref[2], bias, res["acc"], res["f32"], None, what="gemm on grouped scales")
 
 
+# ---- the distance-minimising scale rule (nm_scale_search) and compress with given scales -----------
+@pytest.mark.parametrize("rps", [1, 32, 70])
+@pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (2, 4, 4), (1, 4, 4), (2, 8, 4), (4, 4, 4), (3, 4, 8), (4, 8, 8)])
+def test_scale_search_matches_oracle_and_feeds_compress(N, M, bits, rps):
+    """Scales equal to the oracle's, bit for bit - except where the oracle's own errors of the two
+    candidates agree to 1e-12 relative (the sums run in different orders on the two sides; either choice
+    is then a correct minimiser); then nm_compress_scaled with those scales against the oracle, byte for
+    byte in both layouts, and the result through nm_gemm."""
+    say("scale search", N, M, bits, "rows per scale", rps)
+    rng = np.random.default_rng([N, M, bits, rps, 12])
+    C = 32
+    for rows, cols, ldw in [(70, 256, None), (257, 768, 776), (5, 8 * M, None), (768, 768, None)]:
+        W = (rng.standard_normal((rows, cols)) * rng.random((rows, 1)) * 0.05).astype(np.float32)
+        W[rng.integers(0, rows)] = 0.0
+        W[::7] *= np.linspace(0.05, 4.0, cols).astype(np.float32)           # heavy-tailed rows: a smaller scale pays
+        s_ref, err = oracle.dist_scales(W, N, M, bits, rps, C)
+        Wt = torch.from_numpy(W).to(DEV)
+        if ldw is not None:
+            buf = torch.zeros((rows, ldw), dtype=torch.float32, device=DEV)
+            buf[:, :cols] = Wt
+            Wt = buf[:, :cols]
+        s_dev = nm.nm_scale_search(Wt, N, M, bits, rps, C)
+        torch.cuda.synchronize()
+        s_gpu = s_dev.cpu().numpy()
+        qmax = (1 << (bits - 1)) - 1
+        for gi, r0 in enumerate(range(0, rows, rps)):
+            blk = slice(r0, min(r0 + rps, rows))
+            assert np.all(s_gpu[blk] == s_gpu[r0])
+            if s_gpu[r0] == s_ref[r0]:
+                continue
+            amax = np.abs(W[blk]).max()
+            smax = np.float32(amax) / np.float32(qmax)
+            cands = [np.float32(np.float32(smax * np.float32(c)) / np.float32(C)) for c in range(C // 2, C + 1)]
+            assert s_gpu[r0] in cands, "group %d: %r is no candidate" % (gi, s_gpu[r0])
+            e_gpu, e_ref = err[gi][cands.index(s_gpu[r0])], err[gi].min()
+            assert e_gpu <= e_ref * (1 + 1e-12), "group %d: chose error %r, least is %r" % (gi, e_gpu, e_ref)
+        if bits == 4 and rows >= 70:
+            assert np.any(s_gpu < np.abs(W).max(axis=1) / np.float32(qmax) * 0.99)     # the search does move scales
+        if cols % 128 == 0:
+            for layout in LAYOUTS:
+                packed = nm.nm_compress_scaled(Wt, N, M, bits, s_dev, layout=layout)
+                torch.cuda.synchronize()
+                v, m = oracle.compress_scaled(W, N, M, bits, s_gpu)
+                if layout == TILED:
+                    v, m = oracle.to_tiled(v, m, cols, N, M, bits)
+                assert_packed_equal(packed, (v, m, s_gpu), "scaled %dx%d layout %d" % (rows, cols, layout))
+    T, K, O = 200, 256, 136
+    W, Xq, sx, bias, _, _ = small_case(N, M, bits, T, K, O, 14)
+    Wt = torch.from_numpy(W).to(DEV)
+    s_dev = nm.nm_scale_search(Wt, N, M, bits, rps, C)
+    packed = nm.nm_compress_scaled(Wt, N, M, bits, s_dev, layout=TILED)
+    torch.cuda.synchronize()
+    v, m = oracle.compress_scaled(W, N, M, bits, s_dev.cpu().numpy())
+    acc_ref = oracle.gemm_sparse(Xq, v, m, O, N, M, bits)
+    res = run_gemm(Xq, sx, packed, O, N, M, bits, bias, want=("acc", "f32"), layout=TILED)
+    check_outputs(acc_ref, sx, s_dev.cpu().numpy(), bias, res["acc"], res["f32"], None, what="gemm on searched scales")
+
+
 # ---- several matrices in one call (nm_compress_batch): byte for byte what nm_compress gives -----
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (1, 4, 4), (2, 8, 4), (4, 8, 8), (3, 4, 8), (4, 4, 8), (8, 8, 4)])
