@@ -159,6 +159,28 @@ int nm_scale_search(const float *W_dev, int rows, int cols, int ldw,
                     void *hip_stream);
 
 /*
+ * nm_scale_search for callers that cannot allocate or pass device memory of their own for scratch:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same
+ * launches, the same result bit for bit; the rows' partial errors go to an array built into the
+ * library (static device memory, NM_SCALE_SEARCH_STATIC_MAX_BYTES per GPU, held from the first call
+ * on that GPU until the process ends) instead of a workspace.  The call allocates and frees
+ * nothing.
+ *   - rows * (candidates/2 + 1) * 8 must not exceed NM_SCALE_SEARCH_STATIC_MAX_BYTES (3072 rows at
+ *     64 candidates need 0.8 MB): NM_ERR_WORKSPACE otherwise, with a message on stderr, nothing
+ *     enqueued; larger problems take nm_scale_search.
+ *   - every call on a GPU uses that GPU's one array: calls that overlap in time on the same GPU
+ *     (different streams without an ordering between them) race on it and give wrong scales.
+ *     Nothing in the array has to be cleared between calls.
+ *   - the first call on a GPU looks the array's address up (hipGetSymbolAddress, once per device);
+ *     make that call outside any stream capture.
+ * Other arguments and errors as for nm_scale_search.
+ */
+#define NM_SCALE_SEARCH_STATIC_MAX_BYTES (2u << 20)
+int nm_scale_search_static(const float *W_dev, int rows, int cols, int ldw,
+                           int N, int M, int bits, int rows_per_scale, int candidates,
+                           float *scales_dev, void *hip_stream);
+
+/*
  * nm_compress with the scales given: scales_dev[rows] is an INPUT (one scale per row, each a
  * positive finite float: those of nm_scale_search, or a caller's own), everything else as
  * nm_compress - same projection, same quantiser, same packed formats.

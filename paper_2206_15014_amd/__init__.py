@@ -20,5 +20,6 @@ from .binding import (  # noqa: F401
     nm_packed_sizes,
     nm_project,
     nm_scale_search,
+    nm_scale_search_static,
     nm_status_string,
 )

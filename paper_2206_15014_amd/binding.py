@@ -68,6 +68,8 @@ def _load():
     lib.nm_scale_search_workspace_bytes.argtypes = [c_int, c_int]
     lib.nm_scale_search.restype = c_int
     lib.nm_scale_search.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, ctypes.c_size_t, c_vp]
+    lib.nm_scale_search_static.restype = c_int
+    lib.nm_scale_search_static.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp]
     lib.nm_project.restype = c_int
     lib.nm_project.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_int, c_vp, c_vp]
     lib.nm_gemm_q8.restype = c_int
@@ -179,6 +181,15 @@ def nm_scale_search(W, N: int, M: int, bits: int, rows_per_scale: int, candidate
                                  _ptr(workspace), workspace.numel(), _stream(stream))
     if rc:
         raise NMError(rc, "nm_scale_search")
+    return scales
+
+
+def nm_scale_search_static(W, N: int, M: int, bits: int, rows_per_scale: int, candidates: int, scales, stream=None):
+    """nm_scale_search on the library's built-in scratch array: allocates nothing, so `scales` (float32 [rows]) must be given."""
+    rows, cols = W.shape
+    rc = _load().nm_scale_search_static(_ptr(W), rows, cols, W.stride(0), N, M, bits, rows_per_scale, candidates, _ptr(scales), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_scale_search_static")
     return scales
 
 

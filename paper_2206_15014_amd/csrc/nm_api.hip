@@ -111,6 +111,24 @@ int nm_scale_search(const float* W_dev, int rows, int cols, int ldw, int N, int 
                                    static_cast<double*>(workspace_dev), static_cast<hipStream_t>(hip_stream));
 }
 
+int nm_scale_search_static(const float* W_dev, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale, int candidates,
+                           float* scales_dev, void* hip_stream)
+{
+    const int rc = check_pattern(rows, cols, N, M, bits, NM_LAYOUT_ROWS);
+    if (rc) return rc;
+    if (!W_dev || !scales_dev) return NM_ERR_NULL;
+    if (ldw < cols || rows_per_scale < 1 || candidates < 2 || candidates > 64 || candidates % 2) return NM_ERR_DIM;
+    if ((uintptr_t)W_dev % 4 || (uintptr_t)scales_dev % 4) return NM_ERR_ALIGN;
+    const size_t need = nm_scale_search_workspace_bytes(rows, candidates);
+    if (need > NM_SCALE_SEARCH_STATIC_MAX_BYTES) {
+        fprintf(stderr, "libnm: nm_scale_search_static: %d rows x %d candidates need %zu bytes of scratch, the built-in array holds %zu; "
+                        "use nm_scale_search with a workspace\n", rows, candidates / 2 + 1, need, (size_t)NM_SCALE_SEARCH_STATIC_MAX_BYTES);
+        return NM_ERR_WORKSPACE;
+    }
+    return nm::launch_scale_search_static(W_dev, rows, cols, ldw, N, M, bits, rows_per_scale, candidates, scales_dev,
+                                          static_cast<hipStream_t>(hip_stream));
+}
+
 int nm_compress_batch(const nm_compress_item* items, int count, int N, int M, int bits, int layout, void* hip_stream)
 {
     if (count <= 0 || count > NM_COMPRESS_BATCH_MAX_ITEMS) return NM_ERR_DIM;

@@ -109,6 +109,8 @@ int launch_project(const float* W, const float* U, int rows, int cols, int ldw, 
                    int rows_per_scale, float* Z, float* U_out, int ldz, float* scales, hipStream_t st);
 int launch_scale_search(const float* W, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale,
                         int candidates, float* scales, double* row_errors, hipStream_t st);
+int launch_scale_search_static(const float* W, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale,
+                               int candidates, float* scales, hipStream_t st);
 int launch_absmax_to_scale(float* absmax, float* scale, int reset, hipStream_t st);
 int launch_smfmac_probe(int blocks, int iters, unsigned long long* counters, hipStream_t st);
 int launch_gemm(const GemmArgs& a, hipStream_t st);

@@ -13,7 +13,16 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
+#include "nm.h"
 #include "nm_internal.h"
+
+// Scratch of the entry point that allocates nothing (nm_scale_search_static): the rows' partial
+// errors live in this array instead of a caller's workspace.  Every GPU the library runs on holds
+// its own copy, at its own address, until the process ends.  In host code the name is only a handle
+// for hipGetSymbolAddress - never a device address.
+static __device__ __align__(256) unsigned char scratch[NM_SCALE_SEARCH_STATIC_MAX_BYTES];
 
 namespace nm {
 
@@ -124,6 +133,43 @@ int launch_scale_search(const float* W, int rows, int cols, int ldw, int N, int 
     const long long n_groups = ((long long)rows + rows_per_scale - 1) / rows_per_scale;
     hipLaunchKernelGGL(choose_scale_kernel, dim3((unsigned)((n_groups + 3) / 4)), dim3(256), 0, st, row_errors, rows, rows_per_scale, candidates, scales);
     return launch_status();
+}
+
+// The device address of `scratch` on the current device, looked up once per device (with that
+// device current) and kept.  Returns 0, or NM_ERR_HIP.
+static int static_scratch(void** out)
+{
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex lock;
+    static void* address[MAX_DEVICES] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        fprintf(stderr, "libnm: nm_scale_search_static: no current device\n");
+        return NM_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> guard(lock);
+    if (address[dev] == nullptr) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr) {
+            fprintf(stderr, "libnm: nm_scale_search_static: hipGetSymbolAddress failed on device %d: %s\n", dev, hipGetErrorString(e));
+            return NM_ERR_HIP;
+        }
+        address[dev] = p;
+    }
+    *out = address[dev];
+    return 0;
+}
+
+int launch_scale_search_static(const float* W, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale,
+                               int candidates, float* scales, hipStream_t st)
+{
+    void* p = nullptr;
+    const int rc = static_scratch(&p);
+    if (rc) return rc;
+    // Nothing in the array has to start at zero: the second launch writes the partial errors of
+    // every row and candidate of this call before the third reads exactly those.
+    return launch_scale_search(W, rows, cols, ldw, N, M, bits, rows_per_scale, candidates, scales, static_cast<double*>(p), st);
 }
 
 }  // namespace nm
