@@ -634,7 +634,8 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
         long long best = -1;
         int pick = 0;
         for (const Shape& sh : shapes) {
-            if (U::DUAL && sh.cfg != 0 && sh.cfg != 117) continue;   // two operands per unit: the wide wave tiles would not fit the registers
+            if (U::DUAL && BITS == 8 && sh.cfg != 0 && sh.cfg != 117) continue;   // two operands per unit of 24 or 32 bytes: the wide wave tiles would not fit the registers
+            if (U::DUAL && N == 3 && sh.cfg == 122) continue;
             const long long ct = (a.O + sh.bo - 1) / sh.bo;
             if (sh.cfg != 0 && (ct * sh.bo - a.O) * 8 > a.O) continue;
             const long long n = (long long)((a.tokens + sh.bt - 1) / sh.bt) * ct;
@@ -659,12 +660,16 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
     if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
     if (cfg == 115) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
     if (cfg == 117) return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
+    if constexpr (!U::DUAL || (BITS == 4 && N != 3)) {      // (3:4 needs a few registers more for its index bits: it would spill)
+        if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
+    }
+    if constexpr (!U::DUAL || BITS == 4) {
+        if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(a, st);
+        if (cfg == 121) return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
+    }
     if constexpr (!U::DUAL) {
         if (cfg == 113) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(a, st);
         if (cfg == 105) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 2>(a, st);
-        if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
-        if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(a, st);
-        if (cfg == 121) return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
         // small tiles for problems of a few output tiles (few tokens): more workgroups, each with a
         // smaller share of X and W to pull through its CU's fill path
         if (cfg == 130) return launch_dma_tile<N, M, BITS, 64, 48, 2, 1, 4, 1>(a, st);
