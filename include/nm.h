@@ -212,6 +212,18 @@ int nm_compress_batch(const nm_compress_item *items, int count,
                       int N, int M, int bits, int layout, void *hip_stream);
 
 /*
+ * The packed values and metadata of a matrix from one layout to the other (layout_in names the
+ * layout of the inputs; the outputs are in the other one, sizes from nm_packed_sizes): for weights
+ * that were compressed, stored or exchanged in the row layout and are to be multiplied by the
+ * fast kernels, which read the tiled one.  A pure byte permutation (the padding rows of the tiled
+ * layout are written as zeros); the scales are layout-independent and not touched.  Needs
+ * cols % 128 == 0; the buffers must not overlap.
+ */
+int nm_repack(const void *vals_in_dev, const void *meta_in_dev, int rows, int cols,
+              int N, int M, int bits, int layout_in,
+              void *vals_out_dev, void *meta_out_dev, void *hip_stream);
+
+/*
  * Expand packed weights to the dense integer matrix Wq_dev[rows][cols] (int8,
  * zeros at pruned positions, int4 codes sign-extended).  Inverse of the packing
  * step; used to check that the sparse product equals the dense one.

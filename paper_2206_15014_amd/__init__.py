@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     nm_gemm_q8,
     nm_packed_sizes,
     nm_project,
+    nm_repack,
     nm_scale_search,
     nm_scale_search_static,
     nm_status_string,

@@ -70,6 +70,8 @@ def _load():
     lib.nm_scale_search.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, ctypes.c_size_t, c_vp]
     lib.nm_scale_search_static.restype = c_int
     lib.nm_scale_search_static.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp]
+    lib.nm_repack.restype = c_int
+    lib.nm_repack.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp]
     lib.nm_project.restype = c_int
     lib.nm_project.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_int, c_vp, c_vp]
     lib.nm_gemm_q8.restype = c_int
@@ -225,6 +227,16 @@ def nm_compress_batch(Ws, N: int, M: int, bits: int, outs=None, stream=None, lay
     if rc:
         raise NMError(rc, "nm_compress_batch")
     return outs
+
+
+def nm_repack(vals, meta, rows: int, cols: int, N: int, M: int, bits: int, layout_in: int, stream=None):
+    """(vals, meta) in the other layout than layout_in (a byte permutation; the scales do not change)."""
+    layout_out = NM_LAYOUT_TILED if layout_in == NM_LAYOUT_ROWS else NM_LAYOUT_ROWS
+    v, m, _ = _packed_buffers(rows, cols, N, M, bits, layout_out, vals.device, None, None, 0)
+    rc = _load().nm_repack(_ptr(vals), _ptr(meta), rows, cols, N, M, bits, layout_in, _ptr(v), _ptr(m), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_repack")
+    return v, m
 
 
 def nm_decompress_i8(vals, meta, rows: int, cols: int, N: int, M: int, bits: int, out=None, stream=None,

@@ -147,6 +147,18 @@ int nm_compress_batch(const nm_compress_item* items, int count, int N, int M, in
     return nm::launch_compress_batch(v.data(), count, N, M, bits, layout, static_cast<hipStream_t>(hip_stream));
 }
 
+int nm_repack(const void* vals_in_dev, const void* meta_in_dev, int rows, int cols, int N, int M, int bits, int layout_in,
+              void* vals_out_dev, void* meta_out_dev, void* hip_stream)
+{
+    int rc = check_pattern(rows, cols, N, M, bits, layout_in);
+    if (rc) return rc;
+    rc = check_pattern(rows, cols, N, M, bits, NM_LAYOUT_TILED);     // the other side is tiled, or this one is
+    if (rc) return rc;
+    if (!vals_in_dev || !vals_out_dev || ((!meta_in_dev || !meta_out_dev) && N < M)) return NM_ERR_NULL;
+    return nm::launch_repack(vals_in_dev, meta_in_dev, rows, cols, N, M, bits, layout_in, vals_out_dev, meta_out_dev,
+                             static_cast<hipStream_t>(hip_stream));
+}
+
 int nm_decompress_i8(const void* vals_dev, const void* meta_dev, int rows, int cols,
                      int N, int M, int bits, int layout, int8_t* Wq_dev, void* hip_stream)
 {

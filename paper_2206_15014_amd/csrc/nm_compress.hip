@@ -535,6 +535,17 @@ decompress_kernel(const uint8_t* __restrict__ vals, const uint8_t* __restrict__ 
     for (int c = 0; c < M; ++c) dst[c] = out[c];
 }
 
+// One packed array from one layout to the other, a byte per thread; rows that only pad the tiled
+// layout to a multiple of 16 are written as zeros.
+__global__ void __launch_bounds__(256)
+repack_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst, int rows, int rows_out, PackedArray ps, PackedArray pd)
+{
+    const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (long long)rows_out * ps.stride) return;
+    const uint32_t row = (uint32_t)(id / ps.stride), b = (uint32_t)(id % ps.stride);
+    dst[pd.at(row, b)] = (row < (uint32_t)rows) ? src[ps.at(row, b)] : (uint8_t)0;
+}
+
 template <int N, int M, int BITS, int WPR, int RES>
 void launch_wave_res(const float* W, int rows, int cols, int ldw, uint32_t* v, uint32_t* m, float* scales,
                      int vstride, int mstride, int flags, hipStream_t st)
@@ -695,6 +706,23 @@ int launch_compress_batch(const CompressItem* items, int count, int N, int M, in
         if (b.count == BATCH_MAX) flush();
     }
     flush();
+    return launch_status();
+}
+
+int launch_repack(const void* vals_in, const void* meta_in, int rows, int cols, int N, int M, int bits, int layout_in,
+                  void* vals_out, void* meta_out, hipStream_t st)
+{
+    begin_launch();
+    const int layout_out = 1 - layout_in;
+    const int rows_out = layout_out ? ((rows + 15) & ~15) : rows;
+    const PackedArray vs = packed_values(cols, N, M, bits, layout_in), vd = packed_values(cols, N, M, bits, layout_out);
+    const PackedArray ms = packed_meta(cols, N, M, layout_in), md = packed_meta(cols, N, M, layout_out);
+    const long long nv = (long long)rows_out * vs.stride, nmeta = (long long)rows_out * ms.stride;
+    hipLaunchKernelGGL(repack_kernel, dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st,
+                       (const uint8_t*)vals_in, (uint8_t*)vals_out, rows, rows_out, vs, vd);
+    if (nmeta > 0)
+        hipLaunchKernelGGL(repack_kernel, dim3((unsigned)((nmeta + 255) / 256)), dim3(256), 0, st,
+                           (const uint8_t*)meta_in, (uint8_t*)meta_out, rows, rows_out, ms, md);
     return launch_status();
 }
 

@@ -103,6 +103,8 @@ struct CompressItem {
 int launch_compress_batch(const CompressItem* items, int count, int N, int M, int bits, int layout, hipStream_t st);
 void launch_group_scales(const float* W, int rows, int cols, int ldw, int rows_per_scale, float qmax, float* scales,
                          hipStream_t st);
+int launch_repack(const void* vals_in, const void* meta_in, int rows, int cols, int N, int M, int bits, int layout_in,
+                  void* vals_out, void* meta_out, hipStream_t st);
 int launch_decompress(const void* vals, const void* meta, int rows, int cols, int N, int M, int bits, int layout,
                       int8_t* Wq, hipStream_t st);
 int launch_project(const float* W, const float* U, int rows, int cols, int ldw, int N, int M, int bits,

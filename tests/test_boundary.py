@@ -18,7 +18,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", header))
     assert names >= {"nm_packed_sizes", "nm_compress", "nm_compress_grouped", "nm_compress_batch", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8",
-                     "nm_project", "nm_absmax_to_scale", "nm_scale_search", "nm_scale_search_workspace_bytes", "nm_compress_scaled",
+                     "nm_project", "nm_absmax_to_scale", "nm_scale_search", "nm_scale_search_workspace_bytes", "nm_scale_search_static", "nm_compress_scaled", "nm_repack",
                      "nm_status_string"}
     lib = ctypes.CDLL(binding.library_path())
     for n in names:
@@ -131,6 +131,9 @@ def test_entry_points_validate_before_launch():
         ("W", P), ("rows", 8), ("cols", 8), ("ldw", 8), ("N", 2), ("M", 4), ("bits", 8), ("layout", 0), ("sc", P), ("v", P), ("m", P), ("st", None)]])
     assert cs(sc=None) == -1 and cs(v=None) == -1 and cs(m=None) == -1 and cs(m=None, N=4, W=None) == -1
     assert cs(ldw=4) == -2 and cs(layout=1) == -3 and cs(layout=5) == -8 and cs(sc=P + 2) == -6
+    assert lib.nm_repack(P, P, 8, 8, 2, 4, 8, 0, P, P, None) == -3          # cols % 128
+    assert lib.nm_repack(P, None, 8, 128, 2, 4, 8, 0, P, P, None) == -1 and lib.nm_repack(P, P, 8, 128, 2, 4, 8, 2, P, P, None) == -8
+    assert lib.nm_repack(None, None, 8, 128, 4, 4, 8, 1, P, None, None) == -1
     assert lib.nm_absmax_to_scale(None, P, 0, None) == -1 and lib.nm_absmax_to_scale(P, None, 0, None) == -1
     assert lib.nm_absmax_to_scale(P, P + 2, 0, None) == -6
     assert lib.nm_absmax_to_scale(P, P, 0, None) == -2

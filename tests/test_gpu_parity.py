@@ -191,6 +191,22 @@ def test_decompress_round_trip(layout):
         assert np.array_equal(out.cpu().numpy(), want), (N, M, bits)
 
 
+@pytest.mark.parametrize("N,M,bits", ALL_SCHEMES)
+def test_repack_between_the_layouts(N, M, bits):
+    rng = np.random.default_rng([N, M, bits, 44])
+    for rows, cols in [(37, 256), (768, 768), (5, 128)]:
+        W = (rng.standard_normal((rows, cols)) * 0.02).astype(np.float32)
+        vr, mr, _ = oracle.compress(W, N, M, bits)
+        vt, mt = oracle.to_tiled(vr, mr, cols, N, M, bits)
+        dv, dm = torch.from_numpy(vr).to(DEV), torch.from_numpy(mr).to(DEV)
+        v2, m2 = nm.nm_repack(dv, dm, rows, cols, N, M, bits, ROWS)
+        torch.cuda.synchronize()
+        assert np.array_equal(v2.cpu().numpy(), vt) and np.array_equal(m2.cpu().numpy(), mt)
+        v3, m3 = nm.nm_repack(v2, m2, rows, cols, N, M, bits, TILED)
+        torch.cuda.synchronize()
+        assert np.array_equal(v3.cpu().numpy(), vr) and np.array_equal(m3.cpu().numpy(), mr)
+
+
 # ---- GEMM, small shapes spanning several tiles with ragged edges ------------------------------
 
 def small_case(N, M, bits, T, K, O, seed, with_bias=True):
