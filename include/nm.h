@@ -7,8 +7,9 @@
  *
  * Ownership and execution model (all entry points):
  *   - every *_dev pointer is DEVICE memory owned by the caller; the library
- *     allocates nothing, keeps no device state between calls and never frees
- *     anything;
+ *     allocates nothing and never frees anything; the only device memory of its
+ *     own is the fixed scratch array of nm_scale_search_static (see there), and no
+ *     result depends on anything an earlier call left behind;
  *   - work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
  *     the default stream) and the call returns without synchronising;
  *   - buffers of one call must not overlap;

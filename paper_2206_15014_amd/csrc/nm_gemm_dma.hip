@@ -39,9 +39,9 @@ namespace nm {
 
 namespace {
 
-// KU = 128-column slices per stage.  With KU = 2 a stage row of 2:4 int8 codes is one full
-// 128-byte line and the index rows are 32 bytes: the memory system sees a third fewer requests
-// per byte than with single-slice stages, at the price of a coarser ring.
+// KU = 128-column slices per stage (1 or 2): two slices per stage halve the barriers per column
+// at the price of a coarser ring.  In the tiled layout consecutive slices of a row block are
+// adjacent in memory, so either way every direct load fetches whole 128-byte lines.
 template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU>
 __global__ void __launch_bounds__(64 * WAVES_T * WAVES_O)
 gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
