@@ -368,7 +368,7 @@ def full_size_case(g, layout, rows=None):
     # every output element was written (the buffers were pre-filled with a sentinel)
     for k in ("f32", "f32only"):
         assert np.count_nonzero(res[k] == -7.0) < 4
-    assert np.count_nonzero(res["bf16"] == 0xC0E0) < 64
+    assert np.count_nonzero(res["bf16"] == 0xC0E0) < max(64, 4e-6 * res["bf16"].size)     # -7.0 is a value bf16 outputs do take now and then
 
 
 @pytest.mark.parametrize("layout", LAYOUTS)
@@ -448,14 +448,16 @@ def test_dense_and_three_of_four_at_bert_base_size(N, M, bits):
         full_size_case(g, TILED, stratified_tokens(g.T, seed=N + bits))
 
 
-@pytest.mark.parametrize("T", [128, 384, 8192, 16384])
+@pytest.mark.parametrize("T", [128, 384, 8192, 16384, 24576, 49152])
 def test_inference_table_token_counts_bert_large(T):
     """Token counts of the paper's inference table (Sec. 5.3: batch {1, 32, 64, 128} x sequence {128, 384}) that the
     workloads above do not cover, on the BERT-large layer set: the tile choice differs with the token count."""
     import dataclasses
     for g in synth.config3():
+        if T > 16384 and g.name in ("qkv", "attn_out"):
+            continue                               # the two largest counts: the FFN pair (both reduction widths, both tile families)
         g = dataclasses.replace(g, T=T)
-        full_size_case(g, TILED, stratified_tokens(g.T, per_block=1 if T > 4096 else 2, seed=T % 97))
+        full_size_case(g, TILED, stratified_tokens(g.T, per_block=1 if T > 4096 else 2, block=64 if T <= 16384 else 128, seed=T % 97))
 
 
 # ---- requantised output (nm_gemm_q8) -------------------------------------------------------------
