@@ -24,7 +24,7 @@ DUAL_SCHEMES = [(3, 4, 8), (3, 4, 4), (4, 8, 8), (4, 8, 4), (4, 4, 8), (4, 4, 4)
 ALL_SCHEMES = FAST_SCHEMES + DUAL_SCHEMES + [(3, 8, 4), (5, 8, 8), (7, 8, 4), (8, 8, 8), (8, 8, 4)]
 LAYOUTS = [ROWS, TILED]
 # tile variants of the LDS-direct kernels (tiled layout); the second list is what the two-operand patterns compile
-DMA_TILES = [105, 112, 113, 115, 116, 117, 121, 122, 128, 130, 132]
+DMA_TILES = [105, 112, 113, 115, 116, 117, 121, 122, 123, 128, 130, 132]
 DUAL_TILES = [112, 115, 116, 117]
 
 
