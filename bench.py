@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-streaming-leg", action="store_true",
                     help="skip the second timed leg (buffer sets rotated over more than the 256 MB Infinity Cache)")
+    ap.add_argument("--no-power-leg", action="store_true",
+                    help="skip the leg that runs the dominant GEMM's shape with a 16 times longer reduction for about two seconds and "
+                         "reads board power and shader clock from rocm-smi meanwhile (what the K loop costs per step, and what bounds it)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--workload", choices=["bert_base", "bert_large", "hetero", "table4", "table3", "single", "copy"], default="bert_base",
                     help="bert_base: the four GEMMs of a BERT-base layer at 4096 tokens (the benchmark); "
@@ -142,6 +145,88 @@ def table3_sweep(args, lib, layout):
                                "batch x sequence grid of the paper's inference table (Sec. 5.3)" % args.layout},
         "pct_of_int8_dense_peak": round(100.0 * head[0]["dense_equiv_tops"] / INT8_DENSE_PEAK_TOPS, 2),
         "sweep": sweep}))
+
+
+def smi_read():
+    """(socket power in watts, shader clock in MHz, power limit in watts) as rocm-smi reports them now; None where it does not say."""
+    import re
+    import subprocess
+    try:
+        out = subprocess.run(["rocm-smi", "-a", "--json"], capture_output=True, text=True, timeout=30).stdout
+        card = json.loads(out)
+        card = card[sorted(card)[0]]
+        m = re.search(r"(\d+)\s*Mhz", str(card.get("sclk clock speed:", "")), re.I)
+
+        def num(key):
+            try:
+                return float(card.get(key))
+            except (TypeError, ValueError):
+                return None
+        return (num("current_socket_power (W)"), int(m.group(1)) if m else None, num("Max Graphics Package Power (W)"))
+    except Exception:
+        return None
+
+
+def k_loop_leg(args, lib, nm, torch, gd, layout, out_torch, out_code, timed_launches, check, dev):
+    side = torch.cuda.Stream()
+    mult = 16
+    while mult > 2 and gd.T * gd.K * mult > (192 << 20):
+        mult //= 2
+    us = {}
+    keep = None
+    for m in (mult // 2, mult):
+        K = gd.K * m
+        W = torch.randn((gd.O, K), dtype=torch.float32, device=dev) * 0.02
+        X = torch.randint(-127, 128, (gd.T, K), dtype=torch.int8, device=dev)
+        vals, meta, scales = nm.nm_compress(W, gd.N, gd.M, gd.bits, layout=layout)
+        del W
+        bias = torch.zeros(gd.O, dtype=torch.float32, device=dev)
+        out = torch.empty((gd.T, gd.O), dtype=out_torch, device=dev)
+        a = (X.data_ptr(), gd.T, K, K, 0.01, None, vals.data_ptr(), meta.data_ptr(), scales.data_ptr(), gd.O, gd.N, gd.M, gd.bits,
+             layout, bias.data_ptr(), None, out.data_ptr(), out_code, gd.O, torch.cuda.current_stream().cuda_stream)
+        us[m] = timed_launches(lib.nm_gemm, a, 10)
+        keep = (a, X, vals, meta, scales, bias, out)
+    steps_long, steps_half = gd.K * mult // 128, gd.K * mult // 256
+    us_per_step = (us[mult] - us[mult // 2]) / (steps_long - steps_half)
+    in_loop_tops = 2.0 * gd.T * gd.O * 128 / us_per_step / 1e6
+    # about three seconds of the long launch in one go; two rocm-smi readings while they run
+    a = keep[0]
+    g = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        b = a[:-1] + (side.cuda_stream,)
+        check(lib.nm_gemm(*b))
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            for _ in range(20):
+                check(lib.nm_gemm(*b))
+    torch.cuda.current_stream().wait_stream(side)
+    replays = max(1, int(3.2e6 / (20 * us[mult])))
+    import threading
+    readings = []
+
+    def sampler():
+        for wait in (0.9, 0.9):
+            time.sleep(wait)
+            readings.append((smi_read(), not torch.cuda.current_stream().query()))
+    th = threading.Thread(target=sampler)
+    th.start()
+    for _ in range(replays):
+        g.replay()
+    torch.cuda.synchronize()
+    th.join()
+    watts = sclk = cap = None
+    good = [r for r, busy in readings if r is not None and busy]
+    if good:
+        watts, sclk, cap = good[-1]
+    return {"shape": "%d tokens, K = %d and %d (%d and %d times the layer's), %d outputs" % (gd.T, gd.K * mult // 2, gd.K * mult, mult // 2, mult, gd.O),
+            "us_long": round(us[mult], 2), "us_half": round(us[mult // 2], 2),
+            "us_per_128_column_step": round(us_per_step, 4),
+            "dense_equiv_tops_in_loop": round(in_loop_tops, 1),
+            "frac_dense_peak_in_loop": round(in_loop_tops / INT8_DENSE_PEAK_TOPS, 4),
+            "board_power_w": watts, "board_power_limit_w": cap, "sclk_mhz_in_loop": sclk,
+            "note": "board power and shader clock: rocm-smi's readings about two seconds into three seconds of that launch repeated "
+                    "back to back (null: rocm-smi gave nothing, or the launches had ended before the reading)"}
 
 
 def main():
@@ -445,6 +530,16 @@ def main():
     dense_ops = sum(g.dense_ops for g in gemms)
     value = dense_ops / (ms_per_step * 1e-3) / 1e12
 
+    # ---- the K loop on its own, and what the board does under it --------------------------------------------
+    # The dominant GEMM's token count and output width with a reduction 16 and 8 times as long: the difference of
+    # the two durations is the cost of the K steps alone (launch, first loads and stores cancel).  While the long
+    # one runs for about three seconds, rocm-smi's socket power and shader clock are read twice: the loop runs
+    # at the board's power limit with the clock pulled down, which - not the L2s, the LDS or the matrix pipe -
+    # is what sets its rate when every CU is busy.
+    k_loop = None
+    if not args.no_power_leg and args.launch == "graph" and args.workload in ("bert_base", "bert_large") and args.out_dtype != "i8":
+        k_loop = k_loop_leg(args, lib, nm, torch, gemms[dom], layout, out_torch, out_code, timed_launches, check, dev)
+
     gd = gemms[dom]
     names = [g.name for g in gemms]
     if len(set(names)) < len(names):       # several layers: say which layer and scheme
@@ -477,6 +572,7 @@ def main():
         "same_work_with_%s_compress" % other_mode: None if other_ms is None else {
             "ms_per_step": round(other_ms, 5), "value": round(dense_ops / (other_ms * 1e-3) / 1e12, 2)},
         "streaming_leg": streaming,
+        "k_loop_leg": k_loop,
         "roofline": {
             # the roof that binds this kernel: the larger of its two fractions, both from the method's own work
             "bound": "hbm" if hbm_bound else "mfma",

@@ -4,10 +4,12 @@
 //
 // Why: at these layer shapes one workgroup per CU streams its X tile (first touch from HBM,
 // about a microsecond away) and its slice of the packed weights (from L2) at the CU's L1 fill
-// rate, which - not the MFMA pipe - bounds the kernel.  Keeping several stages of loads in
-// flight without spending registers or LDS-store issue slots is what the direct-to-LDS load is
-// for; the packed weight bytes travel in their compact form and are widened / re-encoded to the
-// MFMA operand in registers (Sec. 5.3: low-bit weights are widened for the ALUs).
+// rate; that, the LDS traffic of the fragment reads and - with every CU busy - the board's power
+// limit (the clock is pulled down) bound the kernel, not the MFMA pipe.  Keeping several stages
+// of loads in flight without spending registers or LDS-store issue slots is what the
+// direct-to-LDS load is for; the packed weight bytes travel in their compact form and are
+// widened / re-encoded to the MFMA operand in registers (Sec. 5.3: low-bit weights are widened
+// for the ALUs).
 //
 // The packed weights are read in the tiled layout of include/nm.h: what one 16-row x 128-column
 // fragment consumes is one contiguous run of memory, so a direct load asks the L2 for eight whole
@@ -610,7 +612,8 @@ bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
     return true;
 }
 
-// Tile choice.  The kernel is bound by the L2 -> LDS fill (line requests per multiply-add) and by
+// Tile choice.  The kernel is bound by the bytes it moves per multiply-add (L2 -> LDS, LDS ->
+// registers: time with few workgroups, energy under the power limit with many) and by
 // the fixed cost of a tile, so the tile wants to be as large as the CU count allows: 256 x 192
 // where that still gives every CU a tile, else 128 x 96 (exactly 256 workgroups for BERT-base's
 // 768-wide layers at 4096 tokens).  Rings of at most 80 KB let two workgroups share a CU, which
