@@ -259,8 +259,8 @@ int nm_decompress_i8(const void *vals_dev, const void *meta_dev, int rows, int c
  * aligned to its element.  The matrix-core kernels additionally need K % 128 == 0, O % 4 == 0,
  * ldo % 4 == 0 and 16-byte aligned X_dev, ldx, vals_dev, meta_dev, scales_dev, bias_dev, acc_dev,
  * out_dev, and a pattern they cover: N <= 2 (either layout; the tiled layout runs the fastest
- * kernels), or 3:4, 4:8 and dense N = M in the tiled layout.  Any other call is computed by a
- * slow one-thread-per-output kernel with the same results.
+ * kernels), or any other pattern (N >= 3, dense N = M included) in the tiled layout.  Any other
+ * call is computed by a slow one-thread-per-output kernel with the same results.
  */
 int nm_gemm(const int8_t *X_dev, int tokens, int K, int ldx, float act_scale,
             const float *act_scale_dev,

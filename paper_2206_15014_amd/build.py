@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnm.so")
 # (source, extra flags, object name).  The LDS-direct GEMM kernels are one source compiled once per
 # set of N:M patterns, so that their many instantiations build in parallel.
-DMA_SETS = 7
+DMA_SETS = 11
 SOURCES = [("nm_gemm_dma.hip", ["-DNM_DMA_SET=%d" % k], "nm_gemm_dma_%d.o" % k) for k in range(DMA_SETS)] + \
           [(s, [], s.replace(".hip", ".o")) for s in ["nm_api.hip", "nm_compress.hip", "nm_gemm.hip", "nm_project.hip", "nm_scale_search.hip"]]
 

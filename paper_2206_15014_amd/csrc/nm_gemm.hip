@@ -342,12 +342,17 @@ bool launch_gemm_dma_set3(const GemmArgs& a, hipStream_t st, int cfg);
 bool launch_gemm_dma_set4(const GemmArgs& a, hipStream_t st, int cfg);
 bool launch_gemm_dma_set5(const GemmArgs& a, hipStream_t st, int cfg);
 bool launch_gemm_dma_set6(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set7(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set8(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set9(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set10(const GemmArgs& a, hipStream_t st, int cfg);
 
 bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg)
 {
     return launch_gemm_dma_set0(a, st, cfg) || launch_gemm_dma_set1(a, st, cfg) || launch_gemm_dma_set2(a, st, cfg) ||
            launch_gemm_dma_set3(a, st, cfg) || launch_gemm_dma_set4(a, st, cfg) || launch_gemm_dma_set5(a, st, cfg) ||
-           launch_gemm_dma_set6(a, st, cfg);
+           launch_gemm_dma_set6(a, st, cfg) || launch_gemm_dma_set7(a, st, cfg) || launch_gemm_dma_set8(a, st, cfg) ||
+           launch_gemm_dma_set9(a, st, cfg) || launch_gemm_dma_set10(a, st, cfg);
 }
 
 int launch_smfmac_probe(int blocks, int iters, unsigned long long* counters, hipStream_t st)

@@ -217,7 +217,7 @@ struct Unit {
     }
 
     // Patterns that can keep more than two entries in an aligned subgroup of four columns (3:4,
-    // 4:8, dense): the unit becomes TWO legal operands of the sparse MFMA, multiplied one after the
+    // 3:8 .. 7:8, dense): the unit becomes TWO legal operands of the sparse MFMA, multiplied one after the
     // other against the same activations.  Of the (up to four) entries a subgroup keeps, operand
     // 1 takes the first two and operand 2 the rest, zero where there is none.  The sparse
     // instruction at twice its issue count does the work of the dense one at the same rate, and
@@ -225,14 +225,14 @@ struct Unit {
     static __device__ __forceinline__ void decode2(const Raw& r, v4i& c1, int& p1, v4i& c2, int& p2)
     {
         static_assert(DUAL, "patterns with more than two kept entries per group");
-        // the codes as bytes, in entry order
-        uint32_t w[EPU / 4];
+        // the codes as bytes, in entry order (4-bit units may end in the middle of a dword)
+        uint32_t w[2 * ((EPU + 7) / 8)];
         if constexpr (BITS == 8) {
 #pragma unroll
             for (int d = 0; d < EPU / 4; ++d) w[d] = r.v[d];
         } else {
 #pragma unroll
-            for (int d = 0; d < EPU / 8; ++d) {
+            for (int d = 0; d < (EPU + 7) / 8; ++d) {
                 const uint32_t x = r.v[d];
                 const uint32_t lo = sext4x4(x & 0x0F0F0F0Fu);          // entries 0, 2, 4, 6 of this dword
                 const uint32_t hi = sext4x4((x >> 4) & 0x0F0F0F0Fu);   // entries 1, 3, 5, 7
@@ -267,18 +267,19 @@ struct Unit {
             p1 = (int)q1;
             p2 = (int)(q2 | 0xCCCCCCCCu);                      // the empty slot points at column 3 (its code is zero)
         } else {
-            static_assert(N == 4 && M == 8, "dual operands: 3:4, 4:8 and dense");
-            // group g (8 columns) keeps 4 entries, dword g of w, offsets 4 bits each: the codes are
-            // scattered to their columns (zeros elsewhere) and the 8 columns then split as a dense group
+            static_assert(M == 8 && N >= 3 && N < 8, "dual operands: 3:4, 3:8 .. 7:8 and dense");
+            // group g (8 columns) keeps entries N*g .. N*g+N-1 of the unit, one byte of w and one
+            // 4-bit offset each: the codes are scattered to their columns (zeros elsewhere) and the
+            // 8 columns then split as a dense group
             uint32_t a1[4], a2[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const uint32_t m16 = (r.m[g / 2] >> (16 * (g & 1))) & 0xFFFFu;
                 uint64_t d = 0;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t code = (w[g] >> (8 * j)) & 0xFFu;
-                    const uint32_t sh = ((m16 >> (4 * j)) & 7u) * 8u;
+                for (int j = 0; j < N; ++j) {
+                    const int e = N * g + j;
+                    const uint32_t code = (w[e / 4] >> (8 * (e % 4))) & 0xFFu;
+                    const uint32_t sh = ((r.m[e / 8] >> (4 * (e % 8))) & 7u) * 8u;
                     d |= (uint64_t)code << sh;
                 }
                 const uint32_t lo = (uint32_t)d, hi = (uint32_t)(d >> 32);

@@ -622,6 +622,9 @@ template <int N, int M, int BITS>
 bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 {
     using U = Unit<N, M, BITS>;
+    // 3:8, 5:8, 6:8, 7:8: units of 6 to 28 bytes that the dwords of a register do not divide; the
+    // 128-wide tiles only (their decode, not the staging, bounds them).
+    constexpr bool ODD8 = (M == 8 && N >= 3 && N < 8 && N != 4);
     if (cfg == 0) {
         // Cost of a tile shape = rounds over the 256 CUs x tile area x the shape's cost per
         // multiply-add relative to 256 x 192 (the L2->LDS fill per multiply-add, measured: 256 x 128
@@ -643,6 +646,7 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
         for (const Shape& sh : shapes) {
             if (U::DUAL && BITS == 8 && sh.cfg != 0 && sh.cfg != 117) continue;   // two operands per unit of 24 or 32 bytes: the wide wave tiles would not fit the registers
             if (U::DUAL && N == 3 && sh.cfg == 122) continue;
+            if (ODD8 && sh.cfg != 0 && sh.cfg != 117) continue;
             if (!U::IDENTITY && sh.cfg == 123) continue;
             const long long ct = (a.O + sh.bo - 1) / sh.bo;
             if (sh.cfg != 0 && (ct * sh.bo - a.O) * 8 > a.O) continue;
@@ -660,18 +664,20 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
         if (!U::DUAL && n96 < 128 && n64x48 <= 256) cfg = 130;
         else if (!U::DUAL && n96 < 128 && n64x96 <= 256) cfg = 132;
         else if (pick != 0) cfg = pick;
-        else if (n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
+        else if (!ODD8 && n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
         else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
         else cfg = 116;                                          // 128 x 96, eight wavefronts
     }
-    if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
+    if constexpr (!ODD8) {
+        if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
+    }
     if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
     if (cfg == 115) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
     if (cfg == 117) return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
-    if constexpr (!U::DUAL || (BITS == 4 && N != 3)) {      // (3:4 needs a few registers more for its index bits: it would spill)
+    if constexpr (!U::DUAL || (BITS == 4 && N != 3 && !ODD8)) {      // (3:4 needs a few registers more for its index bits: it would spill)
         if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
     }
-    if constexpr (!U::DUAL || BITS == 4) {
+    if constexpr (!U::DUAL || (BITS == 4 && !ODD8)) {
         if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(a, st);
         if (cfg == 121) return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
     }
@@ -712,8 +718,16 @@ bool NM_CAT(launch_gemm_dma_set, NM_DMA_SET)(const GemmArgs& a, hipStream_t st, 
     NM_CASE(4, 4, 8); NM_CASE(4, 4, 4); NM_CASE(3, 4, 8);
 #elif NM_DMA_SET == 6
     NM_CASE(3, 4, 4); NM_CASE(4, 8, 8); NM_CASE(4, 8, 4);
+#elif NM_DMA_SET == 7
+    NM_CASE(3, 8, 8); NM_CASE(3, 8, 4);
+#elif NM_DMA_SET == 8
+    NM_CASE(5, 8, 8); NM_CASE(5, 8, 4);
+#elif NM_DMA_SET == 9
+    NM_CASE(6, 8, 8); NM_CASE(6, 8, 4);
+#elif NM_DMA_SET == 10
+    NM_CASE(7, 8, 8); NM_CASE(7, 8, 4);
 #else
-#error "NM_DMA_SET must be 0 .. 6"
+#error "NM_DMA_SET must be 0 .. 10"
 #endif
 #undef NM_CASE
     return false;

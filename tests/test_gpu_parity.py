@@ -26,6 +26,8 @@ LAYOUTS = [ROWS, TILED]
 # tile variants of the LDS-direct kernels (tiled layout); the second list is what the two-operand patterns compile
 DMA_TILES = [105, 112, 113, 115, 116, 117, 121, 122, 123, 128, 130, 132]
 DUAL_TILES = [112, 115, 116, 117]
+ODD8_SCHEMES = [(n, 8, b) for n in (3, 5, 6, 7) for b in (8, 4)]     # units of 6 .. 28 bytes, also two operands per unit
+ODD8_TILES = [115, 116, 117]
 
 
 def say(*a):
@@ -260,6 +262,15 @@ def test_gemm_two_operand_patterns_on_the_matrix_pipe(N, M, bits, tile):
     multiplied as two operands of the sparse MFMA.  Ragged tiles, K of 1 to 11 slices, a row count
     that is not a multiple of 16 (the tiled layout's padding rows are read, as zeros)."""
     _gemm_small(N, M, bits, tile, TILED, shapes=[(200, 256, 136), (129, 128, 260), (300, 1408, 200), (520, 768, 404)], seed=4)
+
+
+@pytest.mark.parametrize("tile", [0] + ODD8_TILES)
+@pytest.mark.parametrize("N,M,bits", ODD8_SCHEMES)
+def test_gemm_other_patterns_of_eight_on_the_matrix_pipe(N, M, bits, tile):
+    """3:8, 5:8, 6:8 and 7:8: the kept entries of a group are scattered to their columns in registers and
+    the group is multiplied as two operands of the sparse MFMA, like a dense one.  Units of 6 to 28 bytes
+    (pieces of 2, 4 or 8 bytes in the tiled layout), ragged tiles, K of 1 to 11 slices."""
+    _gemm_small(N, M, bits, tile, TILED, shapes=[(200, 256, 136), (129, 128, 260), (300, 1408, 200), (520, 768, 404)], seed=6)
 
 
 @pytest.mark.parametrize("layout", LAYOUTS)
