@@ -22,7 +22,6 @@
 #include <stdint.h>
 #include <stdlib.h>
 
-#include <mutex>
 
 #include <type_traits>
 
@@ -300,10 +299,8 @@ void launch_tile(const GemmArgs& a, hipStream_t st)
     const size_t lds = STAGES * (size_t)TileGeom<BT, BO>::STAGE;
     auto kern = gemm_smfmac_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O, DEPTH, STAGES>;
     if (lds > 64 * 1024) {
-        static std::once_flag raised;           // per instantiation; the attribute is sticky
-        std::call_once(raised, [&]() {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        });
+        static std::atomic<uint64_t> raised{0};   // per instantiation
+        raise_lds_limit(reinterpret_cast<const void*>(kern), lds, raised);
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WAVES_T * WAVES_O), lds, st, a, tiles_o, n_tiles);
 }

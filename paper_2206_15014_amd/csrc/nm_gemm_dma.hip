@@ -32,7 +32,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <mutex>
 
 #include "nm_internal.h"
 #include "nm_gemm_common.h"
@@ -598,10 +597,8 @@ bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
     const int grid = 8 * ((n_tiles + 7) / 8);
     auto kern = gemm_dma_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O, STAGES, KU>;
     if (lds > 64 * 1024) {
-        static std::once_flag raised;           // per instantiation; the attribute is sticky
-        std::call_once(raised, [&]() {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        });
+        static std::atomic<uint64_t> raised{0};   // per instantiation
+        raise_lds_limit(reinterpret_cast<const void*>(kern), lds, raised);
     }
     // bf16 outputs of 14 MB and more are written through (measured at 4096 tokens: equal at
     // 12.6 MB, 17 % faster at 18.9 MB, slower below); fp32 always is, in the kernel.

@@ -7,6 +7,8 @@
 #include <stdint.h>
 #include <stdio.h>
 
+#include <atomic>
+
 namespace nm {
 
 // ---------------------------------------------------------------------------------------------
@@ -88,6 +90,19 @@ inline int launch_status()
     if (e == hipSuccess) return 0;
     fprintf(stderr, "libnm: kernel launch failed: %s\n", hipGetErrorString(e));
     return -7;
+}
+
+// Kernels whose LDS ring exceeds 64 KB need their dynamic-LDS limit raised, an attribute a device
+// keeps per kernel: `done` (one word per kernel instantiation) has a bit per device that has it.
+// Two threads may both raise it the first time; that is harmless.
+inline void raise_lds_limit(const void* kernel, size_t lds_bytes, std::atomic<uint64_t>& done)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return;
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    done.fetch_or(bit, std::memory_order_release);
 }
 
 // Each returns 0 or NM_ERR_HIP (-7).
