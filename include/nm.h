@@ -272,6 +272,41 @@ int nm_gemm(const int8_t *X_dev, int tokens, int K, int ldx, float act_scale,
             int ldo, void *hip_stream);
 
 /*
+ * Several linear layers of one scheme in one launch: the query, key and value layers of an
+ * attention block, say, where the chosen configuration compresses them alike (Sec. 5.4 lists the
+ * three as separate components; Sec. 5.3's GEMMs otherwise).  Item i gives exactly what
+ * nm_gemm(items[i].X_dev, ..., N, M, bits, layout, ..., out_dtype, items[i].ldo) gives, element
+ * for element; N, M, bits, layout and out_dtype are common to all items, every other argument
+ * is per item with nm_gemm's meaning, requirements and errors (shapes and inputs may differ
+ * between items; several items may read the same X_dev).  Where every item meets what
+ * nm_gemm's matrix-core kernels need in the tiled layout, the items' output tiles are computed
+ * by one kernel launch (each launch costs about two microseconds of idle time between kernels,
+ * a third of such a layer's GEMM at 4096 tokens); otherwise the items are launched one after the
+ * other.  `items` is HOST memory, read during the call and not kept; the output buffers of
+ * different items must not overlap each other or any input.  count <= 0 or
+ * count > NM_GEMM_BATCH_MAX_ITEMS is NM_ERR_DIM; an item nm_gemm would refuse gives its error
+ * and nothing is enqueued.
+ */
+#define NM_GEMM_BATCH_MAX_ITEMS 4
+typedef struct nm_gemm_item {
+    const int8_t *X_dev;          /* [tokens][ldx] int8                                   */
+    int tokens, K, ldx;
+    float act_scale;
+    const float *act_scale_dev;   /* replaces act_scale when not NULL                     */
+    const void *vals_dev;         /* packed weights of an [O][K] matrix                   */
+    const void *meta_dev;
+    const float *scales_dev;      /* float[O]                                             */
+    int O;
+    const float *bias_dev;        /* float[O] or NULL                                     */
+    int32_t *acc_dev;             /* [tokens][ldo] or NULL                                */
+    void *out_dev;                /* [tokens][ldo] of out_dtype, or NULL with NM_OUT_NONE */
+    int ldo;
+} nm_gemm_item;
+
+int nm_gemm_batch(const nm_gemm_item *items, int count,
+                  int N, int M, int bits, int layout, int out_dtype, void *hip_stream);
+
+/*
  * Training side of the same constraints: the Z-update of the ADMM decomposition (Sec. 3.1),
  * Z = Pi(W + U), i.e. Eq. 3 applied to W + U, with the quantisation constraint solved after the
  * sparsity constraint (Sec. 3.3.1: in that order the two projections in sequence are the joint

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     nm_compress_scaled,
     nm_decompress_i8,
     nm_gemm,
+    nm_gemm_batch,
     nm_gemm_q8,
     nm_packed_sizes,
     nm_project,

@@ -22,6 +22,15 @@ class CompressItem(ctypes.Structure):
     _fields_ = [("W_dev", ctypes.c_void_p), ("rows", ctypes.c_int), ("cols", ctypes.c_int), ("ldw", ctypes.c_int),
                 ("vals_dev", ctypes.c_void_p), ("meta_dev", ctypes.c_void_p), ("scales_dev", ctypes.c_void_p)]
 
+
+class GemmItem(ctypes.Structure):
+    """nm_gemm_item of include/nm.h."""
+    _fields_ = [("X_dev", ctypes.c_void_p), ("tokens", ctypes.c_int), ("K", ctypes.c_int), ("ldx", ctypes.c_int),
+                ("act_scale", ctypes.c_float), ("act_scale_dev", ctypes.c_void_p),
+                ("vals_dev", ctypes.c_void_p), ("meta_dev", ctypes.c_void_p), ("scales_dev", ctypes.c_void_p), ("O", ctypes.c_int),
+                ("bias_dev", ctypes.c_void_p), ("acc_dev", ctypes.c_void_p), ("out_dev", ctypes.c_void_p), ("ldo", ctypes.c_int)]
+
+
 _lib = None
 
 
@@ -62,6 +71,8 @@ def _load():
     lib.nm_gemm.restype = c_int
     lib.nm_gemm.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_vp, c_vp,
                             c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_int, c_int, c_vp]
+    lib.nm_gemm_batch.restype = c_int
+    lib.nm_gemm_batch.argtypes = [ctypes.POINTER(GemmItem), c_int, c_int, c_int, c_int, c_int, c_int, c_vp]
     lib.nm_compress_scaled.restype = c_int
     lib.nm_compress_scaled.argtypes = [c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp]
     lib.nm_scale_search_workspace_bytes.restype = ctypes.c_size_t
@@ -265,6 +276,31 @@ def nm_gemm(X, act_scale: float, vals, meta, scales, O: int, N: int, M: int, bit
     if rc:
         raise NMError(rc, "nm_gemm")
     return acc, out
+
+
+def gemm_items(calls):
+    """The nm_gemm_item array for `calls`: dicts with X, act_scale, vals, meta, scales, O and, optionally,
+    bias, acc, out, ldo, act_scale_dev (the arguments of nm_gemm with the same names)."""
+    arr = (GemmItem * len(calls))()
+    for i, c in enumerate(calls):
+        X = c["X"]
+        tokens, K = X.shape
+        ref = c.get("out") if c.get("out") is not None else c.get("acc")
+        ldo = c.get("ldo")
+        if ldo is None:
+            ldo = ref.stride(0) if ref is not None else c["O"]
+        arr[i] = GemmItem(_ptr(X), tokens, K, X.stride(0), float(c["act_scale"]), _ptr(c.get("act_scale_dev")),
+                          _ptr(c["vals"]), _ptr(c.get("meta")), _ptr(c["scales"]), c["O"],
+                          _ptr(c.get("bias")), _ptr(c.get("acc")), _ptr(c.get("out")), ldo)
+    return arr
+
+
+def nm_gemm_batch(calls, N: int, M: int, bits: int, out_dtype: int = NM_OUT_NONE, stream=None, layout: int = NM_LAYOUT_ROWS):
+    """nm_gemm for every entry of `calls` (see gemm_items) in one call; outputs are written in place."""
+    arr = gemm_items(calls)
+    rc = _load().nm_gemm_batch(arr, len(calls), N, M, bits, layout, out_dtype, _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_gemm_batch")
 
 
 def nm_gemm_q8(X, act_scale: float, vals, meta, scales, O: int, N: int, M: int, bits: int,

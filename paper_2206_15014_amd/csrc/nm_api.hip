@@ -220,6 +220,26 @@ int nm_gemm(const int8_t* X_dev, int tokens, int K, int ldx, float act_scale, co
     return nm::launch_gemm(a, static_cast<hipStream_t>(hip_stream));
 }
 
+int nm_gemm_batch(const nm_gemm_item* items, int count, int N, int M, int bits, int layout, int out_dtype, void* hip_stream)
+{
+    if (!items) return NM_ERR_NULL;
+    if (count <= 0 || count > NM_GEMM_BATCH_MAX_ITEMS) return NM_ERR_DIM;
+    static_assert(NM_GEMM_BATCH_MAX_ITEMS == nm::GEMM_BATCH_MAX, "the ABI's limit is the kernels' limit");
+    if (out_dtype != NM_OUT_NONE && out_dtype != NM_OUT_F32 && out_dtype != NM_OUT_BF16) return NM_ERR_DTYPE;
+    nm::GemmArgs a[NM_GEMM_BATCH_MAX_ITEMS];
+    for (int i = 0; i < count; ++i) {
+        const nm_gemm_item& it = items[i];
+        const int rc = gemm_args(a[i], it.X_dev, it.tokens, it.K, it.ldx, it.act_scale, it.act_scale_dev, it.vals_dev, it.meta_dev,
+                                 it.scales_dev, it.O, N, M, bits, layout, it.bias_dev, it.ldo);
+        if (rc) return rc;
+        if ((out_dtype == NM_OUT_NONE) != (it.out_dev == nullptr)) return NM_ERR_DTYPE;
+        if (!it.acc_dev && !it.out_dev) return NM_ERR_NULL;
+        if ((uintptr_t)it.acc_dev % 4 || (uintptr_t)it.out_dev % (out_dtype == NM_OUT_BF16 ? 2 : 4)) return NM_ERR_ALIGN;
+        a[i].acc = it.acc_dev; a[i].out = it.out_dev; a[i].out_dtype = out_dtype;
+    }
+    return nm::launch_gemm_batch(a, count, static_cast<hipStream_t>(hip_stream));
+}
+
 int nm_project(const float* W_dev, const float* U_dev, int rows, int cols, int ldw,
                int N, int M, int bits, int rows_per_scale,
                float* Z_dev, float* U_out_dev, int ldz, float* scales_dev, void* hip_stream)

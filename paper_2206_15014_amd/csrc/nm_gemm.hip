@@ -332,24 +332,26 @@ void launch_pattern(const GemmArgs& a, hipStream_t st, int tile_cfg)
 
 }  // namespace
 
-bool launch_gemm_dma_set0(const GemmArgs& a, hipStream_t st, int cfg);
-bool launch_gemm_dma_set1(const GemmArgs& a, hipStream_t st, int cfg);
-bool launch_gemm_dma_set2(const GemmArgs& a, hipStream_t st, int cfg);
-bool launch_gemm_dma_set3(const GemmArgs& a, hipStream_t st, int cfg);
-bool launch_gemm_dma_set4(const GemmArgs& a, hipStream_t st, int cfg);
-bool launch_gemm_dma_set5(const GemmArgs& a, hipStream_t st, int cfg);
-bool launch_gemm_dma_set6(const GemmArgs& a, hipStream_t st, int cfg);
-bool launch_gemm_dma_set7(const GemmArgs& a, hipStream_t st, int cfg);
-bool launch_gemm_dma_set8(const GemmArgs& a, hipStream_t st, int cfg);
-bool launch_gemm_dma_set9(const GemmArgs& a, hipStream_t st, int cfg);
-bool launch_gemm_dma_set10(const GemmArgs& a, hipStream_t st, int cfg);
+bool launch_gemm_dma_set0(const GemmArgs* items, int count, hipStream_t st, int cfg);
+bool launch_gemm_dma_set1(const GemmArgs* items, int count, hipStream_t st, int cfg);
+bool launch_gemm_dma_set2(const GemmArgs* items, int count, hipStream_t st, int cfg);
+bool launch_gemm_dma_set3(const GemmArgs* items, int count, hipStream_t st, int cfg);
+bool launch_gemm_dma_set4(const GemmArgs* items, int count, hipStream_t st, int cfg);
+bool launch_gemm_dma_set5(const GemmArgs* items, int count, hipStream_t st, int cfg);
+bool launch_gemm_dma_set6(const GemmArgs* items, int count, hipStream_t st, int cfg);
+bool launch_gemm_dma_set7(const GemmArgs* items, int count, hipStream_t st, int cfg);
+bool launch_gemm_dma_set8(const GemmArgs* items, int count, hipStream_t st, int cfg);
+bool launch_gemm_dma_set9(const GemmArgs* items, int count, hipStream_t st, int cfg);
+bool launch_gemm_dma_set10(const GemmArgs* items, int count, hipStream_t st, int cfg);
 
-bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg)
+bool launch_gemm_dma(const GemmArgs* items, int count, hipStream_t st, int cfg)
 {
-    return launch_gemm_dma_set0(a, st, cfg) || launch_gemm_dma_set1(a, st, cfg) || launch_gemm_dma_set2(a, st, cfg) ||
-           launch_gemm_dma_set3(a, st, cfg) || launch_gemm_dma_set4(a, st, cfg) || launch_gemm_dma_set5(a, st, cfg) ||
-           launch_gemm_dma_set6(a, st, cfg) || launch_gemm_dma_set7(a, st, cfg) || launch_gemm_dma_set8(a, st, cfg) ||
-           launch_gemm_dma_set9(a, st, cfg) || launch_gemm_dma_set10(a, st, cfg);
+    return launch_gemm_dma_set0(items, count, st, cfg) || launch_gemm_dma_set1(items, count, st, cfg) ||
+           launch_gemm_dma_set2(items, count, st, cfg) || launch_gemm_dma_set3(items, count, st, cfg) ||
+           launch_gemm_dma_set4(items, count, st, cfg) || launch_gemm_dma_set5(items, count, st, cfg) ||
+           launch_gemm_dma_set6(items, count, st, cfg) || launch_gemm_dma_set7(items, count, st, cfg) ||
+           launch_gemm_dma_set8(items, count, st, cfg) || launch_gemm_dma_set9(items, count, st, cfg) ||
+           launch_gemm_dma_set10(items, count, st, cfg);
 }
 
 int launch_smfmac_probe(int blocks, int iters, unsigned long long* counters, hipStream_t st)
@@ -366,16 +368,42 @@ int launch_absmax_to_scale(float* absmax, float* scale, int reset, hipStream_t s
     return launch_status();
 }
 
-int launch_gemm(const GemmArgs& a, hipStream_t st)
+namespace {
+
+// What the matrix-core kernels ask of a call beyond the ABI's own requirements.
+bool fast_path_ok(const GemmArgs& a)
 {
     const bool out_ok = a.out_dtype == 0 || (uintptr_t)a.out % 16 == 0;   // (int8 codes: rows are then whole dwords, ldo % 4 == 0)
-    const bool fast = a.K % 128 == 0 && a.O % 4 == 0 && a.ldx % 16 == 0 && a.ldo % 4 == 0 &&
-                      (uintptr_t)a.X % 16 == 0 && (uintptr_t)a.vals % 16 == 0 && (uintptr_t)a.meta % 16 == 0 &&
-                      (uintptr_t)a.scales % 16 == 0 && (uintptr_t)a.bias % 16 == 0 && (uintptr_t)a.acc % 16 == 0 && out_ok;
+    return a.K % 128 == 0 && a.O % 4 == 0 && a.ldx % 16 == 0 && a.ldo % 4 == 0 &&
+           (uintptr_t)a.X % 16 == 0 && (uintptr_t)a.vals % 16 == 0 && (uintptr_t)a.meta % 16 == 0 &&
+           (uintptr_t)a.scales % 16 == 0 && (uintptr_t)a.bias % 16 == 0 && (uintptr_t)a.acc % 16 == 0 && out_ok;
+}
+
+}  // namespace
+
+int launch_gemm_batch(const GemmArgs* items, int count, hipStream_t st)
+{
+    bool together = count > 1;
+    for (int i = 0; i < count && together; ++i) together = fast_path_ok(items[i]) && items[i].pv.tiled;
+    if (together) {
+        begin_launch();
+        const int tile_cfg = forced_gemm_tile();
+        if (launch_gemm_dma(items, count, st, tile_cfg >= 100 ? tile_cfg : 0)) return launch_status();
+    }
+    for (int i = 0; i < count; ++i) {
+        const int rc = launch_gemm(items[i], st);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
+int launch_gemm(const GemmArgs& a, hipStream_t st)
+{
+    const bool fast = fast_path_ok(a);
     begin_launch();
     const int tile_cfg = forced_gemm_tile();    // 0 unless a test forces a variant
     // Tiled layout: the LDS-direct kernels (tile_cfg 0 = their own choice, >= 100 = a forced variant).
-    if (fast && a.pv.tiled && launch_gemm_dma(a, st, tile_cfg >= 100 ? tile_cfg : 0)) return launch_status();
+    if (fast && a.pv.tiled && launch_gemm_dma(&a, 1, st, tile_cfg >= 100 ? tile_cfg : 0)) return launch_status();
     // Row layout, at most two kept per group: the register-staged kernel (tile_cfg 1 .. 3 force its shapes).
     if (fast && !a.pv.tiled && a.N <= 2) {
 #define NM_CASE(n, m, b) else if (a.N == n && a.M == m && a.bits == b) launch_pattern<n, m, b>(a, st, tile_cfg)

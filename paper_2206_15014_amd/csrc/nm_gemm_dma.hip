@@ -40,12 +40,23 @@ namespace nm {
 
 namespace {
 
+// The arguments every workgroup needs before its first operand loads, fetched in one round trip
+// to the argument memory: left to itself the compiler fetches each where it is first used, four
+// dependent round trips of a few hundred nanoseconds each before the first load is issued.
+__device__ __forceinline__ void fetch_now(GemmArgs& a)
+{
+    asm volatile("" : "+s"(a.X), "+s"(a.vals), "+s"(a.meta), "+s"(a.scales), "+s"(a.bias), "+s"(a.tokens), "+s"(a.K),
+                      "+s"(a.ldx), "+s"(a.O), "+s"(a.k_rotate), "+s"(a.out), "+s"(a.acc), "+s"(a.out_dtype), "+s"(a.ldo),
+                      "+s"(a.store_through), "+s"(a.out_scale));
+}
+
+// The work of one workgroup: output tile `tile` (of `tiles_o` column tiles per token tile) of the
+// GEMM `a`.
 // KU = 128-column slices per stage (1 or 2): two slices per stage halve the barriers per column
 // at the price of a coarser ring.  In the tiled layout consecutive slices of a row block are
 // adjacent in memory, so either way every direct load fetches whole 128-byte lines.
 template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU>
-__global__ void __launch_bounds__(64 * WAVES_T * WAVES_O)
-gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
+__device__ __forceinline__ void gemm_dma_tile(const GemmArgs& a, const int tiles_o, const int tile)
 {
     using U = Unit<N, M, BITS>;
     using G = DmaGeom<N, M, BITS, BT, BO, KU>;
@@ -65,9 +76,6 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     const int lane = tid & 63, wave = tid >> 6;
     const int wt = wave % WAVES_T, wo = wave / WAVES_T;
 
-    const int per_xcd = (n_tiles + 7) >> 3;
-    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (tile >= n_tiles) return;               // whole workgroup leaves before any barrier
     const int t0 = (tile / tiles_o) * BT;
     const int o0 = (tile % tiles_o) * BO;
     const int nk = a.K >> 7;                   // 128-column slices
@@ -116,6 +124,7 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     // block 0 (3.5-4.5 % on the 4096-token layer sets).
     const int kstart = a.k_rotate ? (int)(((unsigned)tile * 7u) % (unsigned)ns) : 0;
     const int rb_last = (a.O + 15) / 16 - 1;   // last row block of the packed arrays
+    const uint32_t lds_mine = (uint32_t)(uintptr_t)smem + (uint32_t)wave_u * 1024u;
 #pragma unroll
     for (int p = 0; p < PER_WAVE; ++p) {
         const int b = min(p * NW + wave_u, G::BLOCKS - 1);
@@ -144,9 +153,18 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
             voff[p] = ((uint32_t)rb * (uint32_t)nk + (uint32_t)sl) * (uint32_t)G::MBLK + (uint32_t)w;
         }
         voff[p] += (uint32_t)kstart * stepb[p];
+        // The first stage's load of this block leaves at once (ring slot 0): the address work of
+        // the remaining blocks - some hundred instructions in all - then runs in the shadow of
+        // the memory latency instead of in front of it.
+        dma16s(lds_mine + p * NW * 1024, voff[p], sbase[p]);
+        voff[p] += stepb[p];
     }
-    const uint32_t lds_mine = (uint32_t)(uintptr_t)smem + (uint32_t)wave_u * 1024u;
-    int k_issue = kstart;                      // K block of the next stage to issue
+    int k_issue = kstart + 1;                  // K block of the next stage to issue
+    if (k_issue == ns) {                       // a single stage: back to K block 0
+        k_issue = 0;
+#pragma unroll
+        for (int p = 0; p < PER_WAVE; ++p) voff[p] -= (uint32_t)ns * stepb[p];
+    }
     // Issues the next stage of the stream into ring slot SLOT (a compile-time value).
     auto issue = [&](auto slot) __attribute__((always_inline)) {
         constexpr int SLOT = decltype(slot)::value;
@@ -327,8 +345,8 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     constexpr int AHEAD = STAGES - 1;
     static_assert(AHEAD >= 1, "at least two stages");
     static_assert(AHEAD * PER_WAVE < 64, "loads in flight must fit the counter");
-    int_for<AHEAD + 1>([&](auto jj) __attribute__((always_inline)) {
-        if (decltype(jj)::value < ns) issue(std::integral_constant<int, decltype(jj)::value % STAGES>{});
+    int_for<AHEAD>([&](auto jj) __attribute__((always_inline)) {     // stage 0 left with the address set-up above
+        if (decltype(jj)::value + 1 < ns) issue(std::integral_constant<int, (decltype(jj)::value + 1) % STAGES>{});
     });
 
     Frags fr[2];
@@ -581,31 +599,94 @@ gemm_dma_kernel(const GemmArgs a, const int tiles_o, const int n_tiles)
     }
 }
 
+// One GEMM per launch.  Workgroup -> tile: each XCD (workgroups are dealt to the eight XCDs in
+// turn) takes a contiguous run of tiles, so that the CUs behind one L2 share token rows.
 template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU>
-bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
+__global__ void __launch_bounds__(64 * WAVES_T * WAVES_O)
+gemm_dma_kernel(const GemmArgs a_in, const int tiles_o, const int n_tiles)
+{
+    GemmArgs a = a_in;
+    fetch_now(a);                              // ahead of the early exit: one round trip for everything
+    const int per_xcd = (n_tiles + 7) >> 3;
+    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= n_tiles) return;               // whole workgroup leaves before any barrier
+    gemm_dma_tile<N, M, BITS, BT, BO, WAVES_T, WAVES_O, STAGES, KU>(a, tiles_o, tile);
+}
+
+// Several GEMMs per launch (nm_gemm_batch): each workgroup first finds the item its tile belongs
+// to - a second, dependent round trip to the argument memory before the first loads, which a
+// launch of one GEMM does without (it costs that launch 0.1 to 0.5 us), hence a kernel of its own.
+template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU>
+__global__ void __launch_bounds__(64 * WAVES_T * WAVES_O)
+gemm_dma_batch_kernel(const GemmBatch p)
+{
+    const int n_tiles = p.first_tile[p.count];
+    const int per_xcd = (n_tiles + 7) >> 3;
+    int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= n_tiles) return;
+    int item = 0;                              // uniform over the workgroup
+    while (item + 1 < p.count && tile >= p.first_tile[item + 1]) ++item;
+    GemmArgs a = p.item[item];
+    fetch_now(a);
+    gemm_dma_tile<N, M, BITS, BT, BO, WAVES_T, WAVES_O, STAGES, KU>(a, p.tiles_o[item], tile - p.first_tile[item]);
+}
+
+template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU, bool BATCHABLE = false>
+bool launch_dma_tile(const GemmArgs* items, int count, hipStream_t st)
 {
     using G = DmaGeom<N, M, BITS, BT, BO, KU>;
     constexpr int NW = WAVES_T * WAVES_O;
     constexpr int PER_WAVE = (G::BLOCKS + NW - 1) / NW;
     constexpr size_t lds = (size_t)STAGES * PER_WAVE * NW * 1024 + 2048;   // ring, then scales and bias of the tile
     static_assert(lds <= 160 * 1024, "LDS ring exceeds the 160 KB of a CU");
-    if ((a.K / 128) % KU != 0) return false;
-    // per-lane source offsets are 32-bit
-    if ((unsigned long long)a.tokens * a.ldx >= (1ull << 32) || packed_bytes(a.pv, a.O, a.K) >= (1ull << 32)) return false;
-    const int tiles_t = (a.tokens + BT - 1) / BT, tiles_o = (a.O + BO - 1) / BO;
-    const int n_tiles = tiles_t * tiles_o;
+    if (count > 1 && !BATCHABLE) return false;
+    GemmBatch b;
+    b.count = count;
+    b.first_tile[0] = 0;
+    long long out_bytes = 0;
+    for (int i = 0; i < count; ++i) {
+        const GemmArgs& a = items[i];
+        if ((a.K / 128) % KU != 0) return false;
+        // per-lane source offsets are 32-bit
+        if ((unsigned long long)a.tokens * a.ldx >= (1ull << 32) || packed_bytes(a.pv, a.O, a.K) >= (1ull << 32)) return false;
+        const int tiles_t = (a.tokens + BT - 1) / BT;
+        b.tiles_o[i] = (a.O + BO - 1) / BO;
+        if ((long long)b.first_tile[i] + (long long)tiles_t * b.tiles_o[i] > 0x7FFFFFF0ll) return false;
+        b.first_tile[i + 1] = b.first_tile[i] + tiles_t * b.tiles_o[i];
+        b.item[i] = a;
+        out_bytes += (long long)a.tokens * a.O * 2;
+    }
+    for (int i = count; i < GEMM_BATCH_MAX; ++i) {      // unused slots: defined values
+        b.item[i] = items[0];
+        b.tiles_o[i] = 0;
+        b.first_tile[i + 1] = b.first_tile[count];
+    }
+    const int n_tiles = b.first_tile[count];
     const int grid = 8 * ((n_tiles + 7) / 8);
+    // bf16 outputs of 14 MB and more (all items of the launch together) are written through
+    // (measured at 4096 tokens: equal at 12.6 MB, 17 % faster at 18.9 MB, slower below); fp32
+    // always is, in the kernel.
+    for (int i = 0; i < count; ++i) {
+        b.item[i].store_through = out_bytes >= (14ll << 20);
+        b.item[i].k_rotate = n_tiles > 256;     // more tiles than CUs: see the kernel
+    }
+    if constexpr (BATCHABLE) {
+        if (count > 1) {
+            auto kern = gemm_dma_batch_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O, STAGES, KU>;
+            if (lds > 64 * 1024) {
+                static std::atomic<uint64_t> raised{0};   // per instantiation
+                raise_lds_limit(reinterpret_cast<const void*>(kern), lds, raised);
+            }
+            hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), lds, st, b);
+            return true;
+        }
+    }
     auto kern = gemm_dma_kernel<N, M, BITS, BT, BO, WAVES_T, WAVES_O, STAGES, KU>;
     if (lds > 64 * 1024) {
         static std::atomic<uint64_t> raised{0};   // per instantiation
         raise_lds_limit(reinterpret_cast<const void*>(kern), lds, raised);
     }
-    // bf16 outputs of 14 MB and more are written through (measured at 4096 tokens: equal at
-    // 12.6 MB, 17 % faster at 18.9 MB, slower below); fp32 always is, in the kernel.
-    GemmArgs b = a;
-    b.store_through = (long long)a.tokens * a.O * 2 >= (14ll << 20);
-    b.k_rotate = n_tiles > 256;                 // more tiles than CUs: see the kernel
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), lds, st, b, tiles_o, n_tiles);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NW), lds, st, b.item[0], b.tiles_o[0], n_tiles);
     return true;
 }
 
@@ -616,9 +697,16 @@ bool launch_dma_tile(const GemmArgs& a, hipStream_t st)
 // 768-wide layers at 4096 tokens).  Rings of at most 80 KB let two workgroups share a CU, which
 // overlaps one's epilogue with the other's prologue when there are several rounds.
 template <int N, int M, int BITS>
-bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
+bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cfg)
 {
     using U = Unit<N, M, BITS>;
+    // The tile is chosen for the launch as a whole: the items' output widths side by side (query,
+    // key and value of one layer are one 3 x wider layer to the cost model), the most tokens.
+    GemmArgs a = items[0];
+    for (int i = 1; i < count; ++i) {
+        a.O += items[i].O;
+        a.tokens = a.tokens > items[i].tokens ? a.tokens : items[i].tokens;
+    }
     // 3:8, 5:8, 6:8, 7:8: units of 6 to 28 bytes that the dwords of a register do not divide; the
     // 128-wide tiles only (their decode, not the staging, bounds them).
     constexpr bool ODD8 = (M == 8 && N >= 3 && N < 8 && N != 4);
@@ -645,7 +733,9 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
             if (U::DUAL && N == 3 && sh.cfg == 122) continue;
             if (ODD8 && sh.cfg != 0 && sh.cfg != 117) continue;
             if (!U::IDENTITY && sh.cfg == 123) continue;
-            const long long ct = (a.O + sh.bo - 1) / sh.bo;
+            if (count > 1 && sh.cfg != 122 && sh.cfg != 117 && sh.cfg != 0) continue;   // the shapes compiled for several GEMMs per launch
+            long long ct = 0;                  // column tiles, item by item
+            for (int i = 0; i < count; ++i) ct += (items[i].O + sh.bo - 1) / sh.bo;
             if (sh.cfg != 0 && (ct * sh.bo - a.O) * 8 > a.O) continue;
             const long long n = (long long)((a.tokens + sh.bt - 1) / sh.bt) * ct;
             const long long c = ((n + 255) / 256) * sh.bt * sh.bo * sh.cost;
@@ -659,35 +749,35 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
         // runs in one round (measured on 128 to 384 tokens: 128 x 768 -> 768 5.1 -> 4.2 us,
         // 128 x 4096 -> 1024 10.9 -> 9.3 us, 384 x 1024 -> 3072 6.1 -> 5.0 us).
         if (!U::DUAL && n96 < 128 && n64x48 <= 256) cfg = 130;
-        else if (!U::DUAL && n96 < 128 && n64x96 <= 256) cfg = 132;
+        else if (!U::DUAL && n96 < 128 && n64x96 <= 256 && count == 1) cfg = 132;
         else if (pick != 0) cfg = pick;
-        else if (!ODD8 && n96 >= 1024 && a.tokens >= 256) cfg = 112;      // many rounds: 256 x 96
+        else if (!ODD8 && n96 >= 1024 && a.tokens >= 256 && count == 1) cfg = 112;      // many rounds: 256 x 96
         else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
         else cfg = 116;                                          // 128 x 96, eight wavefronts
     }
     if constexpr (!ODD8) {
-        if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(a, st);
+        if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(items, count, st);
     }
-    if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1>(a, st);
-    if (cfg == 115) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1>(a, st);
-    if (cfg == 117) return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1>(a, st);
+    if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1, true>(items, count, st);
+    if (cfg == 115) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1, true>(items, count, st);
+    if (cfg == 117) return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1, true>(items, count, st);
     if constexpr (!U::DUAL || (BITS == 4 && N != 3 && !ODD8)) {      // (3:4 needs a few registers more for its index bits: it would spill)
-        if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1>(a, st);
+        if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1, true>(items, count, st);
     }
     if constexpr (!U::DUAL || (BITS == 4 && !ODD8)) {
-        if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(a, st);
-        if (cfg == 121) return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(a, st);
+        if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(items, count, st);
+        if (cfg == 121) return launch_dma_tile<N, M, BITS, 256, 128, 4, 2, 3, 1>(items, count, st);
     }
     if constexpr (U::IDENTITY) {
-        if (cfg == 123) return launch_dma_tile<N, M, BITS, 256, 256, 2, 2, 3, 1>(a, st);
+        if (cfg == 123) return launch_dma_tile<N, M, BITS, 256, 256, 2, 2, 3, 1>(items, count, st);
     }
     if constexpr (!U::DUAL) {
-        if (cfg == 113) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(a, st);
-        if (cfg == 105) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 2>(a, st);
+        if (cfg == 113) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(items, count, st);
+        if (cfg == 105) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 2>(items, count, st);
         // small tiles for problems of a few output tiles (few tokens): more workgroups, each with a
         // smaller share of X and W to pull through its CU's fill path
-        if (cfg == 130) return launch_dma_tile<N, M, BITS, 64, 48, 2, 1, 4, 1>(a, st);
-        if (cfg == 132) return launch_dma_tile<N, M, BITS, 64, 96, 2, 2, 4, 1>(a, st);
+        if (cfg == 130) return launch_dma_tile<N, M, BITS, 64, 48, 2, 1, 4, 1, true>(items, count, st);
+        if (cfg == 132) return launch_dma_tile<N, M, BITS, 64, 96, 2, 2, 4, 1>(items, count, st);
     }
     return false;
 }
@@ -698,9 +788,10 @@ bool launch_dma_pattern(const GemmArgs& a, hipStream_t st, int cfg)
 // many instantiations compile in parallel.  Returns true when it launched a kernel.
 #define NM_CAT2(a, b) a##b
 #define NM_CAT(a, b) NM_CAT2(a, b)
-bool NM_CAT(launch_gemm_dma_set, NM_DMA_SET)(const GemmArgs& a, hipStream_t st, int cfg)
+bool NM_CAT(launch_gemm_dma_set, NM_DMA_SET)(const GemmArgs* items, int count, hipStream_t st, int cfg)
 {
-#define NM_CASE(n, m, b) if (a.N == n && a.M == m && a.bits == b) return launch_dma_pattern<n, m, b>(a, st, cfg)
+    const GemmArgs& a = items[0];
+#define NM_CASE(n, m, b) if (a.N == n && a.M == m && a.bits == b) return launch_dma_pattern<n, m, b>(items, count, st, cfg)
 #if NM_DMA_SET == 0
     NM_CASE(2, 4, 8);
 #elif NM_DMA_SET == 1

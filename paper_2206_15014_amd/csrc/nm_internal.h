@@ -81,6 +81,16 @@ struct GemmArgs {
     float* absmax;         // out_dtype 3: max |y| is max-combined into it, or null
 };
 
+// Several GEMMs of one pattern in one launch (nm_gemm_batch): the items' tiles are numbered one
+// item after the other.
+constexpr int GEMM_BATCH_MAX = 4;
+struct GemmBatch {
+    GemmArgs item[GEMM_BATCH_MAX];
+    int first_tile[GEMM_BATCH_MAX + 1];    // item i owns tiles [first_tile[i], first_tile[i + 1])
+    int tiles_o[GEMM_BATCH_MAX];           // column tiles of item i
+    int count;
+};
+
 // Launch-error bracket: begin_launch() drops any stale error left in this thread by earlier HIP
 // calls of the caller; launch_status() reports what the launch itself produced.
 inline void begin_launch() { (void)hipGetLastError(); }
@@ -131,9 +141,12 @@ int launch_scale_search_static(const float* W, int rows, int cols, int ldw, int 
 int launch_absmax_to_scale(float* absmax, float* scale, int reset, hipStream_t st);
 int launch_smfmac_probe(int blocks, int iters, unsigned long long* counters, hipStream_t st);
 int launch_gemm(const GemmArgs& a, hipStream_t st);
-// LDS-direct kernels (tiled layout).  `cfg` 0 = the launcher's own tile choice, otherwise a forced
-// variant; false: not handled, nothing launched.
-bool launch_gemm_dma(const GemmArgs& a, hipStream_t st, int cfg);
+// `count` (1 .. GEMM_BATCH_MAX) GEMMs of one pattern, layout and output type: one launch where the
+// LDS-direct kernels cover every item, else one launch per item.
+int launch_gemm_batch(const GemmArgs* items, int count, hipStream_t st);
+// LDS-direct kernels (tiled layout), `count` items in one launch.  `cfg` 0 = the launcher's own
+// tile choice, otherwise a forced variant; false: not handled, nothing launched.
+bool launch_gemm_dma(const GemmArgs* items, int count, hipStream_t st, int cfg);
 
 // Tile variant forced by the tests (0 = automatic), see nm_test_hooks.h.
 int forced_gemm_tile();

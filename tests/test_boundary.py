@@ -18,7 +18,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", header))
     assert names >= {"nm_packed_sizes", "nm_compress", "nm_compress_grouped", "nm_compress_batch", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8",
-                     "nm_project", "nm_absmax_to_scale", "nm_scale_search", "nm_scale_search_workspace_bytes", "nm_scale_search_static", "nm_compress_scaled", "nm_repack",
+                     "nm_gemm_batch", "nm_project", "nm_absmax_to_scale", "nm_scale_search", "nm_scale_search_workspace_bytes", "nm_scale_search_static", "nm_compress_scaled", "nm_repack",
                      "nm_status_string"}
     lib = ctypes.CDLL(binding.library_path())
     for n in names:
@@ -143,3 +143,26 @@ def test_status_strings():
     assert nm.nm_status_string(0) == "ok"
     assert all(nm.nm_status_string(c) not in ("", "unknown status") for c in range(-10, 1))
     assert nm.nm_status_string(-99) == "unknown status"
+
+
+def test_gemm_batch_validates_before_launch():
+    lib = binding.raw()
+    P = 0x1000          # never dereferenced on the host; validation fails first
+    item = lambda **k: binding.GemmItem(*[k.get(n, d) for n, d in [
+        ("X", P), ("tokens", 4), ("K", 8), ("ldx", 8), ("act_scale", 1.0), ("act_scale_dev", None), ("vals", P), ("meta", P),
+        ("scales", P), ("O", 8), ("bias", None), ("acc", P), ("out", None), ("ldo", 8)]])
+    call = lambda items, count=None, N=2, M=4, bits=8, layout=0, out_dtype=0: lib.nm_gemm_batch(
+        (binding.GemmItem * max(len(items), 1))(*items), len(items) if count is None else count, N, M, bits, layout, out_dtype, None)
+    assert lib.nm_gemm_batch(None, 1, 2, 4, 8, 0, 0, None) == -1
+    assert call([item()], count=0) == -2
+    assert call([item()] * 5) == -2                              # more than NM_GEMM_BATCH_MAX_ITEMS
+    assert call([item()], out_dtype=3) == -5
+    assert call([item(), item(X=None)]) == -1                    # the second item is refused: nothing is enqueued
+    assert call([item(), item(ldo=4)]) == -2
+    assert call([item(), item(acc=None)]) == -1                  # no output at all
+    assert call([item(out=P)]) == -5                             # output given, output type none
+    assert call([item(), item(acc=P + 2)]) == -6
+    assert call([item()], N=5) == -3
+    assert call([item()], bits=5) == -4
+    assert call([item()], layout=9) == -8
+    assert call([item()], layout=1) == -3                        # tiled layout needs K % 128 == 0

@@ -273,6 +273,59 @@ def test_gemm_other_patterns_of_eight_on_the_matrix_pipe(N, M, bits, tile):
     _gemm_small(N, M, bits, tile, TILED, shapes=[(200, 256, 136), (129, 128, 260), (300, 1408, 200), (520, 768, 404)], seed=6)
 
 
+def _gemm_batch(N, M, bits, layout, tile, shapes, seed, shared_x=False):
+    """nm_gemm_batch over `shapes` [(T, K, O), ...] against the oracle item by item: accumulators + fp32 in
+    one call, bf16 in another (the kernels' epilogues); outputs padded, the padding must stay as it was."""
+    say("gemm batch", N, M, bits, "layout", layout, "tile", tile, shapes)
+    cases = [small_case(N, M, bits, T, K, O, seed + i) for i, (T, K, O) in enumerate(shapes)]
+    if shared_x:                              # query, key and value: one activation tensor
+        cases = [(c[0], cases[0][1], cases[0][2], c[3], c[4],
+                  oracle.gemm_sparse(cases[0][1], c[4][0], c[4][1], shapes[i][2], N, M, bits)) for i, c in enumerate(cases)]
+    X0 = torch.from_numpy(cases[0][1]).to(DEV)
+    with forced_tile(tile):
+        for dtype, code in ((torch.float32, NM_OUT_F32), (torch.bfloat16, NM_OUT_BF16)):
+            calls, keep = [], []
+            for (T, K, O), (W, Xq, sx, bias, ref, acc_ref) in zip(shapes, cases):
+                packed = gpu_compress(W, N, M, bits, layout=layout)
+                ldo = O + 8
+                acc = torch.full((T, ldo), -7, dtype=torch.int32, device=DEV) if code == NM_OUT_F32 else None
+                out = torch.full((T, ldo), -7.0, dtype=dtype, device=DEV)
+                calls.append(dict(X=X0 if shared_x else torch.from_numpy(Xq).to(DEV), act_scale=float(sx), vals=packed[0], meta=packed[1],
+                                  scales=packed[2], O=O, bias=torch.from_numpy(bias).to(DEV), acc=acc, out=out, ldo=ldo))
+                keep.append((acc, out))
+            nm.nm_gemm_batch(calls, N, M, bits, out_dtype=code, layout=layout)
+            torch.cuda.synchronize()
+            for i, ((T, K, O), (W, Xq, sx, bias, ref, acc_ref), (acc, out)) in enumerate(zip(shapes, cases, keep)):
+                what = "item %d T%d K%d O%d" % (i, T, K, O)
+                if code == NM_OUT_F32:
+                    a, f = acc.cpu().numpy(), out.cpu().numpy()
+                    assert np.all(a[:, O:] == -7) and np.all(f[:, O:] == -7.0), what + ": padding touched"
+                    check_outputs(acc_ref, sx, ref[2], bias, a[:, :O], f[:, :O], None, what=what)
+                else:
+                    b16 = out.view(torch.int16).cpu().numpy().view(np.uint16)
+                    assert np.all(b16[:, O:] == 0xC0E0), what + ": padding touched"
+                    check_outputs(acc_ref, sx, ref[2], bias, None, None, b16[:, :O], what=what)
+
+
+@pytest.mark.parametrize("tile", [0, 116, 122, 130])
+@pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (2, 4, 4), (1, 8, 8), (4, 4, 4), (4, 8, 8), (3, 4, 8)])
+def test_gemm_batch_one_launch_for_several_layers(N, M, bits, tile):
+    """Items of different shapes (ragged tiles, K of 1 to 6 slices) whose tiles share one launch of a
+    tiled-layout kernel; then query / key / value: three layers on one activation tensor."""
+    _gemm_batch(N, M, bits, TILED, tile, [(200, 256, 136), (129, 128, 260), (300, 768, 200), (16, 384, 64)], seed=11)
+    _gemm_batch(N, M, bits, TILED, tile, [(520, 256, 256), (520, 256, 256), (520, 256, 192)], seed=12, shared_x=True)
+
+
+@pytest.mark.parametrize("layout,N,M,bits,shapes", [
+    (ROWS, 2, 4, 8, [(70, 256, 136), (33, 128, 64)]),              # row layout: one launch per item
+    (ROWS, 3, 4, 8, [(33, 40, 18), (7, 12, 5)]),                   # generic kernel
+    (TILED, 2, 4, 8, [(129, 128, 130), (64, 256, 64)]),            # O % 4 != 0 in one item: the batch goes item by item
+    (TILED, 2, 8, 4, [(77, 384, 96)]),                             # a batch of one
+])
+def test_gemm_batch_falls_back_to_one_launch_per_item(layout, N, M, bits, shapes):
+    _gemm_batch(N, M, bits, layout, 0, shapes, seed=13)
+
+
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("N,M,bits", ALL_SCHEMES)
 def test_gemm_generic_path_odd_shapes(N, M, bits, layout):
