@@ -58,6 +58,9 @@ def parse():
                          "single: one 768x768 layer at 128 tokens (the skinny shape, for profiling); "
                          "copy: a plain 256 MiB device copy (calibrates the HBM traffic counters)")
     ap.add_argument("--task", default="MNLI", help="row of the Sec. 5.4 table for --workload table4 (MNLI, SST-2, QNLI, QQP, CoLA, STS-B, MRPC, RTE)")
+    ap.add_argument("--qkv", choices=["grouped", "separate"], default="grouped",
+                    help="--workload table4: query, key and value layers of one scheme share a launch (nm_gemm_batch), or every layer "
+                         "has its own nm_gemm call")
     ap.add_argument("--tokens", type=int, default=None,
                     help="token count for the bert_base / bert_large layer sets instead of the workload's own (batch x "
                          "sequence length of the paper's inference table, e.g. 128 x 384 = 49152): a sweep, not the benchmark")
@@ -351,13 +354,43 @@ def main():
         items = binding.compress_items([j["W"] for j in js], [(j["vals"], j["meta"], j["scales"]) for j in js])
         batches.append((items, len(js)) + scheme + (layout,))
 
+    # The GEMM launches of a step: one nm_gemm per layer, except that the query / key / value layers of an
+    # attention block that share a scheme (and their input) go through one nm_gemm_batch call.
+    units = [(gemm_fn, ga[:-1]) for ga in gargs]
+    grouped_launches = 0
+    if args.workload == "table4" and args.qkv == "grouped" and args.out_dtype != "i8":
+        units, keep_items, i = [], [], 0
+        scheme = lambda j: (j["g"].N, j["g"].M, j["g"].bits, j["g"].K, j["X"].data_ptr())
+        while i < len(jobs):
+            block = [i]
+            if jobs[i]["g"].name == "query":      # the three projections of one attention block are independent of each other
+                while i + len(block) < len(jobs) and jobs[i + len(block)]["g"].name in ("key", "value"):
+                    block.append(i + len(block))
+            done = set()
+            for k in block:
+                if k in done:
+                    continue
+                run = [m for m in block if m not in done and scheme(jobs[m]) == scheme(jobs[k])]
+                done.update(run)
+                if len(run) > 1:
+                    g = jobs[k]["g"]
+                    items = binding.gemm_items([dict(X=jobs[m]["X"], act_scale=jobs[m]["sx"], vals=jobs[m]["vals"], meta=jobs[m]["meta"],
+                                                     scales=jobs[m]["scales"], O=jobs[m]["g"].O, bias=jobs[m]["bias"], out=jobs[m]["out"])
+                                                for m in run])
+                    keep_items.append(items)
+                    units.append((lib.nm_gemm_batch, (items, len(run), g.N, g.M, g.bits, layout, out_code)))
+                    grouped_launches += 1
+                else:
+                    units.append((gemm_fn, gargs[k][:-1]))
+            i += len(block)
+
     def run_step(st, mode=None):
         """The launches of one step on stream `st`."""
         if (mode or args.compress) == "batched":
             for b in batches:
                 check(lib.nm_compress_batch(*b, st))
-            for ga in gargs:
-                check(gemm_fn(*(ga[:-1] + (st,))))
+            for fn, ua in units:
+                check(fn(*(ua + (st,))))
         else:
             for ca, ga in zip(cargs, gargs):
                 check(lib.nm_compress(*(ca[:-1] + (st,))))
@@ -573,6 +606,8 @@ def main():
             "ms_per_step": round(other_ms, 5), "value": round(dense_ops / (other_ms * 1e-3) / 1e12, 2)},
         "streaming_leg": streaming,
         "k_loop_leg": k_loop,
+        "gemm_launches_per_step": len(units),
+        "grouped_qkv_launches": grouped_launches,
         "roofline": {
             # the roof that binds this kernel: the larger of its two fractions, both from the method's own work
             "bound": "hbm" if hbm_bound else "mfma",
