@@ -437,10 +437,13 @@ struct BatchItem {
     int rows, cols, ldw, vstride_dw, mstride_dw, wpr, first_block, blocks;
 };
 struct BatchArgs {
-    BatchItem it[BATCH_MAX];
+    // the table a workgroup searches for its item, one aligned 64-byte run at the front of the
+    // argument block so that it arrives in one scalar load; unused entries hold INT_MAX
+    int first_block[BATCH_MAX];
     int count;
     int flags;             // of compress_rows
     int stream_loads;      // the weights are loaded with the streaming hint
+    BatchItem it[BATCH_MAX];
 };
 
 template <int N, int M, int BITS, int RES, bool ONCE>
@@ -448,10 +451,15 @@ __global__ void __launch_bounds__(256)
 compress_batch_kernel(const BatchArgs b)
 {
     __shared__ float part[4];
+    // Two round trips to the argument memory before the first weights are asked for: the table,
+    // then every field of the item at once (fetched where first used they were four to seven).
     int i = 0;
-    for (int k = 1; k < b.count; ++k)
-        if ((int)blockIdx.x >= b.it[k].first_block) i = k;     // uniform: scalar loads from the argument segment
-    const BatchItem& t = b.it[i];
+#pragma unroll
+    for (int k = 1; k < BATCH_MAX; ++k)
+        if ((int)blockIdx.x >= b.first_block[k]) i = k;        // uniform
+    BatchItem t = b.it[i];
+    asm volatile("" : "+s"(t.W), "+s"(t.vals), "+s"(t.meta), "+s"(t.scales), "+s"(t.rows), "+s"(t.cols), "+s"(t.ldw),
+                      "+s"(t.vstride_dw), "+s"(t.mstride_dw), "+s"(t.wpr), "+s"(t.first_block), "+s"(t.blocks));
     compress_rows<N, M, BITS, RES, ONCE>(t.W, t.rows, t.cols, t.ldw, t.vals, t.meta, t.scales, t.vstride_dw, t.mstride_dw, b.flags,
                                    t.wpr, xcd_block((int)blockIdx.x - t.first_block, t.blocks, b.flags), part);
 }
@@ -682,7 +690,9 @@ int launch_compress_batch(const CompressItem* items, int count, int N, int M, in
         NM_CASE(1, 8, 4); NM_CASE(2, 8, 4); NM_CASE(4, 8, 4);
 #undef NM_CASE
         b.count = 0; blocks = 0; max_mine = 0;
+        for (int k = 0; k < BATCH_MAX; ++k) b.first_block[k] = 0x7FFFFFFF;
     };
+    for (int k = 0; k < BATCH_MAX; ++k) b.first_block[k] = 0x7FFFFFFF;
     for (int i = 0; i < count; ++i) {
         const CompressItem& c = items[i];
         const PackedArray pv = packed_values(c.cols, N, M, bits, layout), pm = packed_meta(c.cols, N, M, layout);
@@ -698,6 +708,7 @@ int launch_compress_batch(const CompressItem* items, int count, int N, int M, in
         t.W = c.W; t.vals = (uint32_t*)c.vals; t.meta = (uint32_t*)c.meta; t.scales = c.scales;
         t.rows = c.rows; t.cols = c.cols; t.ldw = c.ldw; t.vstride_dw = (int)pv.stride / 4; t.mstride_dw = (int)pm.stride / 4;
         t.wpr = wpr; t.first_block = blocks;
+        b.first_block[b.count - 1] = blocks;
         const int rows_out = layout ? ((c.rows + 15) & ~15) : c.rows;     // the tiled layout pads the rows
         t.blocks = (rows_out + rpb - 1) / rpb;
         if (layout) t.blocks = (t.blocks + 7) & ~7;                       // whole rounds over the XCDs, see xcd_block
