@@ -753,6 +753,7 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         else if (pick != 0) cfg = pick;
         else if (!ODD8 && n96 >= 1024 && a.tokens >= 256 && count == 1) cfg = 112;      // many rounds: 256 x 96
         else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
+        else if (a.K >= 2048 && (a.K / 128) % 2 == 0 && count == 1) cfg = 113;   // long reductions: two slices per stage, half the barriers (1 % at K = 3072, 5 % at 4096)
         else cfg = 116;                                          // 128 x 96, eight wavefronts
     }
     if constexpr (!ODD8) {
@@ -773,7 +774,6 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     }
     if constexpr (!U::DUAL) {
         if (cfg == 113) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(items, count, st);
-        if (cfg == 105) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 2>(items, count, st);
         // small tiles for problems of a few output tiles (few tokens): more workgroups, each with a
         // smaller share of X and W to pull through its CU's fill path
         if (cfg == 130) return launch_dma_tile<N, M, BITS, 64, 48, 2, 1, 4, 1, true>(items, count, st);
