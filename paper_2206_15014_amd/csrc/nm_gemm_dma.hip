@@ -13,9 +13,9 @@
 //
 // The packed weights are read in the tiled layout of include/nm.h: what one 16-row x 128-column
 // fragment consumes is one contiguous run of memory, so a direct load asks the L2 for eight whole
-// 128-byte lines (in the row layout it gathered 16 or 64 pieces of as many different lines, and
-// the L2 -> LDS fill is bound by the number of line requests, not by bytes), and the fragment
-// reads from LDS are lane-contiguous.
+// 128-byte lines (in the row layout it gathered 16 or 64 pieces of as many different lines: a
+// fifth to a quarter more L2 requests per launch), and the fragment reads from LDS are
+// lane-contiguous.
 //
 // Stage layout (KU 128-column K steps).  A direct load writes 64 lanes x 16 bytes to 1 KB of
 // consecutive LDS in lane order, so every array is a sequence of 1 KB blocks and the layout
@@ -109,8 +109,7 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& a, const int tiles
     // Load p of wave w fills block b = p * NW + w of the stage; blocks past the last real one are
     // padding and refetch it.  Which array a block belongs to depends on the wavefront only, so
     // its base address and its step along K are scalars; each lane keeps a 32-bit byte offset
-    // that is advanced in place after every issue.  (The inner loop is bound by the number of
-    // instructions a wavefront has to issue - one per four cycles - so every one saved counts.)
+    // that is advanced in place after every issue: one add per load in the inner loop.
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     uint32_t voff[PER_WAVE];                   // this lane's byte offset from sbase[p], at the next stage to issue
     const uint8_t* sbase[PER_WAVE];
@@ -712,7 +711,7 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     constexpr bool ODD8 = (M == 8 && N >= 3 && N < 8 && N != 4);
     if (cfg == 0) {
         // Cost of a tile shape = rounds over the 256 CUs x tile area x the shape's cost per
-        // multiply-add relative to 256 x 192 (the L2->LDS fill per multiply-add, measured: 256 x 128
+        // multiply-add relative to 256 x 192 (time per multiply-add with the chip full, measured: 256 x 128
         // 1.35, 192 x 128 1.5, 128 x 128 1.66, 128 x 96 1.45 with its two workgroups per CU).  A
         // shape whose last column tile would compute more than an eighth of the columns in vain is
         // out; a later shape must beat an earlier one by 5 %.  BERT-base at 4096 tokens: 256 x 192
