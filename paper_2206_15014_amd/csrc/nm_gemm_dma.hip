@@ -709,6 +709,11 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     // 3:8, 5:8, 6:8, 7:8: units of 6 to 28 bytes that the dwords of a register do not divide; the
     // 128-wide tiles only (their decode, not the staging, bounds them).
     constexpr bool ODD8 = (M == 8 && N >= 3 && N < 8 && N != 4);
+    // 3:4 and 4:8 at 4 bits: the costliest decodes of the patterns that fit the wide tile.  Its eight
+    // wavefronts arranged 2 x 4 (wave tiles of 128 x 48) decode every weight fragment twice instead
+    // of four times: 256 x 192 in that arrangement (4:8 FFN-up 22.8 -> 20.8 us, QKV 22.3 -> 18.4;
+    // 3:4, which does not fit the registers of the 4 x 2 arrangement, 26.8 -> 21.3 and 19.1 -> 18.0).
+    constexpr bool WIDE24 = (BITS == 4 && ((N == 3 && M == 4) || (N == 4 && M == 8)));
     if (cfg == 0) {
         // Cost of a tile shape = rounds over the 256 CUs x tile area x the shape's cost per
         // multiply-add relative to 256 x 192 (time per multiply-add with the chip full, measured: 256 x 128
@@ -729,7 +734,7 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         int pick = 0;
         for (const Shape& sh : shapes) {
             if (U::DUAL && BITS == 8 && sh.cfg != 0 && sh.cfg != 117) continue;   // two operands per unit of 24 or 32 bytes: the wide wave tiles would not fit the registers
-            if (U::DUAL && N == 3 && sh.cfg == 122) continue;
+            if (U::DUAL && N == 3 && sh.cfg == 122 && !WIDE24) continue;
             if (ODD8 && sh.cfg != 0 && sh.cfg != 117) continue;
             if (!U::IDENTITY && sh.cfg == 123) continue;
             if (count > 1 && sh.cfg != 122 && sh.cfg != 117 && sh.cfg != 0) continue;   // the shapes compiled for several GEMMs per launch
@@ -749,6 +754,7 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         // 128 x 4096 -> 1024 10.9 -> 9.3 us, 384 x 1024 -> 3072 6.1 -> 5.0 us).
         if (!U::DUAL && n96 < 128 && n64x48 <= 256) cfg = 130;
         else if (!U::DUAL && n96 < 128 && n64x96 <= 256 && count == 1) cfg = 132;
+        else if (pick == 122 && WIDE24) cfg = count == 1 ? 126 : (N == 3 ? 117 : 122);
         else if (pick != 0) cfg = pick;
         else if (!ODD8 && n96 >= 1024 && a.tokens >= 256 && count == 1) cfg = 112;      // many rounds: 256 x 96
         else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
@@ -761,6 +767,9 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1, true>(items, count, st);
     if (cfg == 115) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1, true>(items, count, st);
     if (cfg == 117) return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1, true>(items, count, st);
+    if constexpr (WIDE24) {
+        if (cfg == 126) return launch_dma_tile<N, M, BITS, 256, 192, 2, 4, 3, 1>(items, count, st);
+    }
     if constexpr (!U::DUAL || (BITS == 4 && N != 3 && !ODD8)) {      // (3:4 needs a few registers more for its index bits: it would spill)
         if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1, true>(items, count, st);
     }

@@ -255,7 +255,7 @@ def test_gemm_decoded_patterns_on_the_tiled_kernels(N, M, bits, tile):
     _gemm_small(N, M, bits, tile, TILED, shapes=[(520, 768, 400), (200, 256, 136), (300, 1536, 200)], seed=3)
 
 
-@pytest.mark.parametrize("tile", [0] + DUAL_TILES + [121, 122, 128])
+@pytest.mark.parametrize("tile", [0] + DUAL_TILES + [121, 122, 126, 128])
 @pytest.mark.parametrize("N,M,bits", DUAL_SCHEMES + [(8, 8, 8)])
 def test_gemm_two_operand_patterns_on_the_matrix_pipe(N, M, bits, tile):
     """3:4, 4:8 and dense matrices (more than two kept entries per subgroup of four): each unit is
