@@ -100,8 +100,8 @@ int nm_packed_sizes(int rows, int cols, int N, int M, int bits, int layout,
  *   W_dev      [rows][ldw] float, row-major; rows = output neurons, cols = inputs;
  *              ldw (elements) >= cols; 4-byte aligned (NM_ERR_ALIGN otherwise).  With W_dev
  *              and ldw*4 16-byte aligned, vals_dev / meta_dev 4-byte aligned and packed rows
- *              that are whole dwords the wavefront-per-row kernels run (N in {1, 2} or N = M,
- *              and 4:8); anything else takes a slow thread-per-row kernel, same bytes.
+ *              that are whole dwords the wavefront-per-row kernels run; anything else takes
+ *              a slow thread-per-row kernel, same bytes.
  *   layout     nm_layout of the outputs.
  *   vals_dev, meta_dev, scales_dev   outputs, sizes from nm_packed_sizes; scales_dev 4-byte
  *              aligned; meta_dev may be NULL for a dense matrix.

@@ -465,6 +465,116 @@ compress_batch_kernel(const BatchArgs b)
 }
 
 // ---------------------------------------------------------------------------------------------
+// The patterns whose groups do not pack into whole fractions of a dword (3:4, 3:8, 5:8, 6:8, 7:8:
+// 6 to 56 value bits and 6 to 28 index bits per group): a wavefront per row, four rows per
+// workgroup.  Lane l encodes groups l, l + 64, ... as the kernels above do (same ranking, same
+// quantiser) and ORs each group's bits into the row's image in LDS at their bit offset, wherever
+// that falls in a dword; the image then goes out in dwords, to either layout.  Needs a 16-byte
+// aligned W, ldw % 4 == 0 and packed rows of whole dwords.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void or_bits(uint32_t* image, uint32_t bit, uint64_t v)     // v < 2^56
+{
+    const uint32_t d = bit >> 5, sh = bit & 31u;
+    const uint64_t lo = v << sh;
+    const uint32_t hi = sh ? (uint32_t)(v >> (64u - sh)) : 0u;      // what the shift pushed past 64 bits
+    if ((uint32_t)lo) atomicOr(&image[d], (uint32_t)lo);            // (a zero part may lie past the row's end)
+    if ((uint32_t)(lo >> 32)) atomicOr(&image[d + 1], (uint32_t)(lo >> 32));
+    if (hi) atomicOr(&image[d + 2], hi);
+}
+
+template <int N, int M, int BITS>
+__global__ void __launch_bounds__(256)
+compress_rowimage_kernel(const float* __restrict__ W, int rows, int cols, int ldw,
+                         uint8_t* __restrict__ vals, uint8_t* __restrict__ meta, float* __restrict__ scales,
+                         PackedArray pv, PackedArray pm, int given)
+{
+    constexpr int IB = (M == 4) ? 2 : 4;
+    constexpr int VB = N * BITS, MB = N * IB;          // value / index bits per group
+    constexpr int F4 = M / 4;
+    constexpr float QMAX = (float)((1 << (BITS - 1)) - 1);
+    extern __shared__ uint32_t images[];               // per wavefront: value dwords, then index dwords, of one row
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int row = blockIdx.x * 4 + wave;
+    const int rows_out = pv.tiled ? ((rows + 15) & ~15) : rows;     // the tiled layout pads the rows with zero bytes
+    if (row >= rows_out) return;                       // (no workgroup-wide barrier below)
+    const int vdw = (int)pv.stride / 4, mdw = (int)pm.stride / 4;
+    uint32_t* vimg = images + wave * (vdw + mdw);
+    uint32_t* mimg = vimg + vdw;
+    for (int d = lane; d < vdw + mdw; d += 64) vimg[d] = 0u;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    if (row < rows) {
+        const float4* __restrict__ w4 = reinterpret_cast<const float4*>(W + (size_t)row * ldw);
+        const int groups = cols / M;
+        float s;
+        if (given) {
+            s = scales[row];
+        } else {
+            float amax = 0.0f;
+            for (int i = lane; i < groups * F4; i += 64) {
+                const float4 v = w4[i];
+                amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+            }
+            amax = wave_max(amax);
+            s = (amax == 0.0f) ? 1.0f : amax / QMAX;   // Sec. 3.3.1; an all-zero row keeps scale 1
+            if (lane == 0) scales[row] = s;
+        }
+        auto encode_row = [&](auto divisor) __attribute__((always_inline)) {
+            for (int g = lane; g < groups; g += 64) {
+                float x[M];
+#pragma unroll
+                for (int f = 0; f < F4; ++f) {
+                    const float4 v = w4[g * F4 + f];
+                    x[4 * f + 0] = v.x; x[4 * f + 1] = v.y; x[4 * f + 2] = v.z; x[4 * f + 3] = v.w;
+                }
+                const uint32_t mask = keep_mask<N, M>(x);
+                uint64_t vbits = 0;
+                uint32_t mbits = 0;
+#pragma unroll
+                for (int j = 0; j < N; ++j) {
+                    float v = 0.0f;
+                    uint32_t col = 0;
+#pragma unroll
+                    for (int c = j; c <= M - N + j; ++c) {          // slot j can only hold columns j .. M-N+j
+                        const bool here = ((mask >> c) & 1u) && (__builtin_popcount(mask & ((1u << c) - 1u)) == j);
+                        v = here ? x[c] : v;
+                        col = here ? (uint32_t)c : col;
+                    }
+                    const int q = quantize<BITS>(v, divisor);
+                    vbits |= (uint64_t)((uint32_t)q & ((1u << BITS) - 1u)) << (j * BITS);
+                    mbits |= col << (j * IB);
+                }
+                or_bits(vimg, (uint32_t)g * VB, vbits);
+                or_bits(mimg, (uint32_t)g * MB, (uint64_t)mbits);
+            }
+        };
+        if (s >= 0x1p-60f && s <= 0x1p60f) encode_row(Divisor<true>{s, __fdiv_rn(1.0f, s)});
+        else encode_row(Divisor<false>{s, 0.0f});
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    // the image, a dword at a time; in the tiled layout a dword lies inside one piece of a unit when
+    // the pieces are 4 bytes or more, and is two pieces (of two different units or halves) otherwise
+    auto copy_out = [&](const uint32_t* img, int ndw, uint8_t* base, const PackedArray& pa) __attribute__((always_inline)) {
+        const bool halves = pa.tiled && piece_bytes((int)pa.ub) < 4;
+        for (int d = lane; d < ndw; d += 64) {
+            const uint32_t v = *reinterpret_cast<const volatile uint32_t*>(img + d);
+            if (!halves) {
+                *reinterpret_cast<uint32_t*>(base + pa.at((uint32_t)row, 4u * d)) = v;
+            } else {
+                *reinterpret_cast<uint16_t*>(base + pa.at((uint32_t)row, 4u * d)) = (uint16_t)v;
+                *reinterpret_cast<uint16_t*>(base + pa.at((uint32_t)row, 4u * d + 2u)) = (uint16_t)(v >> 16);
+            }
+        }
+    };
+    copy_out(vimg, vdw, vals, pv);
+    copy_out(mimg, mdw, meta, pm);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Any pattern, any width, any alignment, either layout: one thread per row, bytes written one at
 // a time.
 // ---------------------------------------------------------------------------------------------
@@ -629,6 +739,21 @@ int launch_compress(const float* W, int rows, int cols, int ldw, int N, int M, i
         NM_CASE(2, 4, 8); NM_CASE(1, 4, 8); NM_CASE(2, 4, 4); NM_CASE(1, 4, 4); NM_CASE(4, 4, 8); NM_CASE(4, 4, 4);
         NM_CASE(1, 8, 8); NM_CASE(2, 8, 8); NM_CASE(4, 8, 8);
         NM_CASE(1, 8, 4); NM_CASE(2, 8, 4); NM_CASE(4, 8, 4);
+        else done = false;
+#undef NM_CASE
+    }
+    // the other patterns: a wavefront per row with the row's bits assembled in LDS
+    const size_t image_bytes = 4 * (size_t)(vstride + mstride);       // four rows per workgroup
+    if (!done && N < M && (uintptr_t)W % 16 == 0 && ldw % 4 == 0 && (uintptr_t)vals % 4 == 0 && (uintptr_t)meta % 4 == 0 &&
+        vstride % 4 == 0 && mstride % 4 == 0 && image_bytes <= 64 * 1024) {
+        const int rows_out = layout ? ((rows + 15) & ~15) : rows;
+        done = true;
+#define NM_CASE(n, m, b) else if (N == n && M == m && bits == b) \
+        hipLaunchKernelGGL((compress_rowimage_kernel<n, m, b>), dim3((rows_out + 3) / 4), dim3(256), image_bytes, st, \
+                           W, rows, cols, ldw, (uint8_t*)vals, (uint8_t*)meta, scales, pv, pm, given)
+        if (false) {}
+        NM_CASE(3, 4, 8); NM_CASE(3, 4, 4); NM_CASE(3, 8, 8); NM_CASE(3, 8, 4); NM_CASE(5, 8, 8); NM_CASE(5, 8, 4);
+        NM_CASE(6, 8, 8); NM_CASE(6, 8, 4); NM_CASE(7, 8, 8); NM_CASE(7, 8, 4);
         else done = false;
 #undef NM_CASE
     }

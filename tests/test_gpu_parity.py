@@ -147,7 +147,7 @@ def run_gemm(Xq, sx, packed, O, N, M, bits, bias=None, want=("acc", "f32"), ldo=
 # ---- compress ---------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("layout", LAYOUTS)
-@pytest.mark.parametrize("N,M,bits", ALL_SCHEMES)
+@pytest.mark.parametrize("N,M,bits", ALL_SCHEMES + [(3, 8, 8), (5, 8, 4), (6, 8, 8), (6, 8, 4), (7, 8, 8)])
 @pytest.mark.parametrize("rows,cols", [(70, 768), (9, 4352), (5, 64), (3, 24), (130, 1024)])
 def test_compress_matches_oracle(N, M, bits, rows, cols, layout):
     if cols % M or (layout == TILED and cols % 128):
