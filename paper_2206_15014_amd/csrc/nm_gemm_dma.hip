@@ -721,9 +721,9 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         // shape whose last column tile would compute more than an eighth of the columns in vain is
         // out; a later shape must beat an earlier one by 5 %.  BERT-base at 4096 tokens: 256 x 192
         // for QKV and FFN-up (192 and 256 tiles), 128 x 96 for the 768-wide outputs (256 tiles);
-        // BERT-large at 12288 tokens: 256 x 192 for the wide layers, 192 x 128 for the 1024-wide
-        // ones (512 tiles, two full rounds, against 288 of 256 x 192); at 4096 tokens 128 x 128 for
-        // them (256 tiles) and 256 x 128 for FFN-up (512 tiles).
+        // BERT-large at 12288 tokens: 256 x 192 for QKV, 256 x 256 for FFN-up and the 1024-wide
+        // layers (768 and 192 tiles); at 4096 tokens 128 x 128 for the 1024-wide ones (256 tiles);
+        // at 8192 and 24576 tokens 256 x 128 for them.
         struct Shape { int cfg, bt, bo, cost; };
         // 256 x 256 (four wavefronts of 128 x 128, one per SIMD, accumulators in 256 registers) moves the
         // fewest bytes per multiply-add but hides latency worst: cost 1.15.  It wins where 192 does not
