@@ -326,6 +326,50 @@ def test_gemm_batch_falls_back_to_one_launch_per_item(layout, N, M, bits, shapes
     _gemm_batch(N, M, bits, layout, 0, shapes, seed=13)
 
 
+def test_gemm_batch_replayed_from_a_graph():
+    """Query / key / value as one nm_gemm_batch launch captured in a HIP graph: the item table lives in
+    host memory that is read during the call only, so replays on new activations (same buffers) must
+    give the new results."""
+    say("gemm batch in a graph")
+    N, M, bits, T, K = 2, 4, 8, 520, 768
+    rng = np.random.default_rng(77)
+    Os = [256, 256, 192]
+    Ws = [(rng.standard_normal((O, K)) * 0.02).astype(np.float32) for O in Os]
+    refs = [oracle.compress(W, N, M, bits) for W in Ws]
+    packed = [gpu_compress(W, N, M, bits, layout=TILED) for W in Ws]
+    biases = [(rng.standard_normal(O) * 0.02).astype(np.float32) for O in Os]
+    X = torch.zeros((T, K), dtype=torch.int8, device=DEV)
+    sx_dev = torch.ones(1, dtype=torch.float32, device=DEV)
+    accs = [torch.zeros((T, O), dtype=torch.int32, device=DEV) for O in Os]
+    outs = [torch.zeros((T, O), dtype=torch.float32, device=DEV) for O in Os]
+    bdev = [torch.from_numpy(b).to(DEV) for b in biases]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+
+    def enqueue(st):
+        calls = [dict(X=X, act_scale=0.0, act_scale_dev=sx_dev, vals=p[0], meta=p[1], scales=p[2], O=O, bias=b, acc=a, out=o)
+                 for p, O, b, a, o in zip(packed, Os, bdev, accs, outs)]
+        nm.nm_gemm_batch(calls, N, M, bits, out_dtype=NM_OUT_F32, layout=TILED, stream=st)
+
+    with torch.cuda.stream(side):
+        enqueue(side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            enqueue(side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        Xq, sx = synth.quantize_activations((rng.standard_normal((T, K)) * (1.0 + rep)).astype(np.float32))
+        X.copy_(torch.from_numpy(Xq))
+        sx_dev.fill_(float(sx))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, O in enumerate(Os):
+            acc_ref = oracle.gemm_sparse(Xq, refs[i][0], refs[i][1], O, N, M, bits)
+            check_outputs(acc_ref, sx, refs[i][2], biases[i], accs[i].cpu().numpy(), outs[i].cpu().numpy(), None, what="replay %d item %d" % (rep, i))
+
+
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("N,M,bits", ALL_SCHEMES)
 def test_gemm_generic_path_odd_shapes(N, M, bits, layout):
