@@ -326,6 +326,13 @@ def test_gemm_batch_falls_back_to_one_launch_per_item(layout, N, M, bits, shapes
     _gemm_batch(N, M, bits, layout, 0, shapes, seed=13)
 
 
+@pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (1, 8, 4), (4, 4, 8), (7, 8, 4)])
+def test_gemm_tiled_kernels_smallest_shapes(N, M, bits):
+    """The smallest problems the matrix-core kernels of the tiled layout accept: one token, four output columns,
+    one 128-column slice; one token against a long reduction; a single column tile of 4 with many tokens."""
+    _gemm_small(N, M, bits, 0, TILED, shapes=[(1, 128, 4), (1, 4096, 8), (300, 128, 4), (2, 256, 20), (17, 128, 100)], seed=9)
+
+
 def test_gemm_batch_replayed_from_a_graph():
     """Query / key / value as one nm_gemm_batch launch captured in a HIP graph: the item table lives in
     host memory that is read during the call only, so replays on new activations (same buffers) must
