@@ -713,6 +713,14 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     // wavefronts arranged 2 x 4 (wave tiles of 128 x 48) decode every weight fragment twice instead
     // of four times: 256 x 192 in that arrangement (4:8 FFN-up 22.8 -> 20.8 us, QKV 22.3 -> 18.4;
     // 3:4, which does not fit the registers of the 4 x 2 arrangement, 26.8 -> 21.3 and 19.1 -> 18.0).
+    // 3:4 and the N:8 patterns with N >= 3 spend more time decoding a weight fragment than multiplying
+    // it, and every wavefront that shares the fragment decodes it again.  128 x 128 with the eight
+    // wavefronts side by side along the outputs (wave tiles of 128 tokens x 16 outputs) decodes every
+    // fragment once, at the price of every wavefront reading the whole token tile: better wherever
+    // the launch is one round of such tiles (4:8 int8 FFN-down 24.1 -> 19.8 us, attention output
+    // 9.3 -> 8.1; 7:8 int8 34.7 -> 26.1) and, for six or seven kept of eight, everywhere
+    // (7:8 int8 FFN-up 45.9 -> 32.1 us).
+    constexpr bool DECODE_BOUND = U::DUAL && N != M;
     constexpr bool WIDE24 = (BITS == 4 && ((N == 3 && M == 4) || (N == 4 && M == 8)));
     if (cfg == 0) {
         // Cost of a tile shape = rounds over the 256 CUs x tile area x the shape's cost per
@@ -754,6 +762,8 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         // 128 x 4096 -> 1024 10.9 -> 9.3 us, 384 x 1024 -> 3072 6.1 -> 5.0 us).
         if (!U::DUAL && n96 < 128 && n64x48 <= 256) cfg = 130;
         else if (!U::DUAL && n96 < 128 && n64x96 <= 256 && count == 1) cfg = 132;
+        else if (DECODE_BOUND && count == 1 && ((M == 8 && N >= 6) ||
+                 (long long)((a.tokens + 127) / 128) * ((a.O + 127) / 128) <= 256)) cfg = 127;
         else if (pick == 122 && WIDE24) cfg = count == 1 ? 126 : (N == 3 ? 117 : 122);
         else if (pick != 0) cfg = pick;
         else if (!ODD8 && n96 >= 1024 && a.tokens >= 256 && count == 1) cfg = 112;      // many rounds: 256 x 96
@@ -767,6 +777,9 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1, true>(items, count, st);
     if (cfg == 115) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1, true>(items, count, st);
     if (cfg == 117) return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1, true>(items, count, st);
+    if constexpr (DECODE_BOUND) {
+        if (cfg == 127) return launch_dma_tile<N, M, BITS, 128, 128, 1, 8, 3, 1>(items, count, st);
+    }
     if constexpr (WIDE24) {
         if (cfg == 126) return launch_dma_tile<N, M, BITS, 256, 192, 2, 4, 3, 1>(items, count, st);
     }

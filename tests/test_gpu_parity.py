@@ -27,7 +27,7 @@ LAYOUTS = [ROWS, TILED]
 DMA_TILES = [112, 113, 115, 116, 117, 121, 122, 123, 128, 130, 132]
 DUAL_TILES = [112, 115, 116, 117]
 ODD8_SCHEMES = [(n, 8, b) for n in (3, 5, 6, 7) for b in (8, 4)]     # units of 6 .. 28 bytes, also two operands per unit
-ODD8_TILES = [115, 116, 117]
+ODD8_TILES = [115, 116, 117, 127]
 
 
 def say(*a):
@@ -255,7 +255,7 @@ def test_gemm_decoded_patterns_on_the_tiled_kernels(N, M, bits, tile):
     _gemm_small(N, M, bits, tile, TILED, shapes=[(520, 768, 400), (200, 256, 136), (300, 1536, 200)], seed=3)
 
 
-@pytest.mark.parametrize("tile", [0] + DUAL_TILES + [121, 122, 126, 128])
+@pytest.mark.parametrize("tile", [0] + DUAL_TILES + [121, 122, 126, 127, 128])
 @pytest.mark.parametrize("N,M,bits", DUAL_SCHEMES + [(8, 8, 8)])
 def test_gemm_two_operand_patterns_on_the_matrix_pipe(N, M, bits, tile):
     """3:4, 4:8 and dense matrices (more than two kept entries per subgroup of four): each unit is
