@@ -359,6 +359,12 @@ __device__ __forceinline__ void store16_through(void* dst, v4i v)
     asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(dst), "v"(v) : "memory");
 }
 
+typedef int v2i_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store8_through(void* dst, v2i_t v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1\n\ts_nop 1" : : "v"(dst), "v"(v) : "memory");
+}
+
 template <int CNT>
 __device__ __forceinline__ void wait_vm()
 {

@@ -491,7 +491,11 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& a, const int tiles
         };
         auto emit8 = [&](uint32_t da, uint32_t db, int row, int col) __attribute__((always_inline)) {
             const v2u x = __builtin_amdgcn_permlane16_swap(da, db, false, false);
-            if (row < a.tokens) *reinterpret_cast<uint2*>(out + (size_t)row * a.ldo + col) = make_uint2(x[0], x[1]);
+            if (row < a.tokens) {
+                uint8_t* dst = out + (size_t)row * a.ldo + col;
+                if (a.store_through) store8_through(dst, v2i_t{(int)x[0], (int)x[1]});
+                else *reinterpret_cast<uint2*>(dst) = make_uint2(x[0], x[1]);
+            }
         };
         // Four fragments side by side go one step further (v_permlane32_swap: upper half of the
         // first operand against lower half of the second): lane row lg ends up with all 16 columns
@@ -510,8 +514,12 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& a, const int tiles
                     const v2u pq = __builtin_amdgcn_permlane32_swap(ab[0], cd2[0], false, false);
                     const v2u rs = __builtin_amdgcn_permlane32_swap(ab[1], cd2[1], false, false);
                     const int row = row0 + ft * 16;
-                    if (row < a.tokens)
-                        *reinterpret_cast<v4i*>(out + (size_t)row * a.ldo + col0 + (fo + lg) * 16) = v4i{(int)pq[0], (int)rs[0], (int)pq[1], (int)rs[1]};
+                    if (row < a.tokens) {
+                        uint8_t* dst = out + (size_t)row * a.ldo + col0 + (fo + lg) * 16;
+                        const v4i v = v4i{(int)pq[0], (int)rs[0], (int)pq[1], (int)rs[1]};
+                        if (a.store_through) store16_through(dst, v);
+                        else *reinterpret_cast<v4i*>(dst) = v;
+                    }
                 });
             } else {
                 int_for<2 * Q4>([&](auto h) __attribute__((always_inline)) {
@@ -653,7 +661,7 @@ bool launch_dma_tile(const GemmArgs* items, int count, hipStream_t st)
         if ((long long)b.first_tile[i] + (long long)tiles_t * b.tiles_o[i] > 0x7FFFFFF0ll) return false;
         b.first_tile[i + 1] = b.first_tile[i] + tiles_t * b.tiles_o[i];
         b.item[i] = a;
-        out_bytes += (long long)a.tokens * a.O * 2;
+        out_bytes += (long long)a.tokens * a.O * (a.out_dtype == 3 ? 1 : 2);
     }
     for (int i = count; i < GEMM_BATCH_MAX; ++i) {      // unused slots: defined values
         b.item[i] = items[0];
@@ -663,10 +671,11 @@ bool launch_dma_tile(const GemmArgs* items, int count, hipStream_t st)
     const int n_tiles = b.first_tile[count];
     const int grid = 8 * ((n_tiles + 7) / 8);
     // bf16 outputs of 14 MB and more (all items of the launch together) are written through
-    // (measured at 4096 tokens: equal at 12.6 MB, 17 % faster at 18.9 MB, slower below); fp32
-    // always is, in the kernel.
+    // (measured at 4096 tokens: equal at 12.6 MB, 17 % faster at 18.9 MB, slower below), int8
+    // codes from 8 MB (9.4 MB: 11.4 -> 10.4 us, 12.6 MB: 12.5 -> 11.8 us, 50 MB: 56.9 -> 52.9 us);
+    // fp32 always is, in the kernel.
     for (int i = 0; i < count; ++i) {
-        b.item[i].store_through = out_bytes >= (14ll << 20);
+        b.item[i].store_through = out_bytes >= ((items[0].out_dtype == 3 ? 8ll : 14ll) << 20);
         b.item[i].k_rotate = n_tiles > 256;     // more tiles than CUs: see the kernel
     }
     if constexpr (BATCHABLE) {
