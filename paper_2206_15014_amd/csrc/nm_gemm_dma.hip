@@ -725,11 +725,14 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     // 3:4 and the N:8 patterns with N >= 3 spend more time decoding a weight fragment than multiplying
     // it, and every wavefront that shares the fragment decodes it again.  128 x 128 with the eight
     // wavefronts side by side along the outputs (wave tiles of 128 tokens x 16 outputs) decodes every
-    // fragment once, at the price of every wavefront reading the whole token tile: better wherever
-    // the launch is one round of such tiles (4:8 int8 FFN-down 24.1 -> 19.8 us, attention output
-    // 9.3 -> 8.1; 7:8 int8 34.7 -> 26.1) and, for six or seven kept of eight, everywhere
-    // (7:8 int8 FFN-up 45.9 -> 32.1 us).
+    // fragment once, at the price of every wavefront reading the whole token tile: better for every
+    // such pattern on outputs up to 1024 wide (4:8 int8 FFN-down 24.1 -> 19.8 us, attention output
+    // 9.3 -> 8.1; 3:4 int8 12288 x 1024 -> 1024 35.4 -> 28.5; 5:8 int4 there 66.9 -> 36.4), and at any
+    // width for 4:8 int8, five of eight at 8 bits and six or seven of eight (5:8 int8 FFN-up
+    // 39.6 -> 30.4 us, 7:8 int8 45.9 -> 32.1); the other patterns keep 256 x 192 / 128 x 96 on wide
+    // outputs, where those measure equal or better.
     constexpr bool DECODE_BOUND = U::DUAL && N != M;
+    constexpr bool ALWAYS_ONCE = M == 8 && (N >= 6 || (N >= 4 && BITS == 8));
     constexpr bool WIDE24 = (BITS == 4 && ((N == 3 && M == 4) || (N == 4 && M == 8)));
     if (cfg == 0) {
         // Cost of a tile shape = rounds over the 256 CUs x tile area x the shape's cost per
@@ -771,8 +774,7 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         // 128 x 4096 -> 1024 10.9 -> 9.3 us, 384 x 1024 -> 3072 6.1 -> 5.0 us).
         if (!U::DUAL && n96 < 128 && n64x48 <= 256) cfg = 130;
         else if (!U::DUAL && n96 < 128 && n64x96 <= 256 && count == 1) cfg = 132;
-        else if (DECODE_BOUND && count == 1 && ((M == 8 && N >= 6) ||
-                 (long long)((a.tokens + 127) / 128) * ((a.O + 127) / 128) <= 256)) cfg = 127;
+        else if (DECODE_BOUND && count == 1 && (ALWAYS_ONCE || a.O <= 1024)) cfg = 127;
         else if (pick == 122 && WIDE24) cfg = count == 1 ? 126 : (N == 3 ? 117 : 122);
         else if (pick != 0) cfg = pick;
         else if (!ODD8 && n96 >= 1024 && a.tokens >= 256 && count == 1) cfg = 112;      // many rounds: 256 x 96
