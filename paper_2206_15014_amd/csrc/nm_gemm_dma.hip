@@ -733,6 +733,10 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     // outputs, where those measure equal or better.
     constexpr bool DECODE_BOUND = U::DUAL && N != M;
     constexpr bool ALWAYS_ONCE = M == 8 && (N >= 6 || (N >= 4 && BITS == 8));
+    // The cheaper decodes gain from the same arrangement on outputs up to 1024 wide too (FFN-down at
+    // 4096 tokens: 2:4 int4 14.6 -> 13.0 us, 2:8 int8 15.0 -> 13.0, dense int4 18.7 -> 15.7); 1:4 int8
+    // and dense int8 measure equal either way and keep 128 x 96.
+    constexpr bool NARROW_ONCE = !U::IDENTITY && !(N == 1 && M == 4 && BITS == 8) && !(N == M && BITS == 8);
     constexpr bool WIDE24 = (BITS == 4 && ((N == 3 && M == 4) || (N == 4 && M == 8)));
     if (cfg == 0) {
         // Cost of a tile shape = rounds over the 256 CUs x tile area x the shape's cost per
@@ -774,7 +778,7 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         // 128 x 4096 -> 1024 10.9 -> 9.3 us, 384 x 1024 -> 3072 6.1 -> 5.0 us).
         if (!U::DUAL && n96 < 128 && n64x48 <= 256) cfg = 130;
         else if (!U::DUAL && n96 < 128 && n64x96 <= 256 && count == 1) cfg = 132;
-        else if (DECODE_BOUND && count == 1 && (ALWAYS_ONCE || a.O <= 1024)) cfg = 127;
+        else if (NARROW_ONCE && count == 1 && ((DECODE_BOUND && ALWAYS_ONCE) || a.O <= 1024)) cfg = 127;
         else if (pick == 122 && WIDE24) cfg = count == 1 ? 126 : (N == 3 ? 117 : 122);
         else if (pick != 0) cfg = pick;
         else if (!ODD8 && n96 >= 1024 && a.tokens >= 256 && count == 1) cfg = 112;      // many rounds: 256 x 96
@@ -788,7 +792,7 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     if (cfg == 116) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 1, true>(items, count, st);
     if (cfg == 115) return launch_dma_tile<N, M, BITS, 128, 96, 2, 2, 3, 1, true>(items, count, st);
     if (cfg == 117) return launch_dma_tile<N, M, BITS, 128, 128, 4, 2, 3, 1, true>(items, count, st);
-    if constexpr (DECODE_BOUND) {
+    if constexpr (NARROW_ONCE) {
         if (cfg == 127) return launch_dma_tile<N, M, BITS, 128, 128, 1, 8, 3, 1>(items, count, st);
     }
     if constexpr (WIDE24) {

@@ -247,7 +247,7 @@ def test_gemm_tiled_layout_every_tile_shape(tile):
     _gemm_small(2, 4, 8, tile, TILED)
 
 
-@pytest.mark.parametrize("tile", [0, 113, 115, 117, 121, 122, 128, 130, 132])
+@pytest.mark.parametrize("tile", [0, 113, 115, 117, 121, 122, 127, 128, 130, 132])
 @pytest.mark.parametrize("N,M,bits", FAST_SCHEMES[1:])
 def test_gemm_decoded_patterns_on_the_tiled_kernels(N, M, bits, tile):
     """The patterns that are re-encoded in registers, on the tile shapes the launcher picks for
