@@ -783,7 +783,7 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         else if (pick != 0) cfg = pick;
         else if (!ODD8 && n96 >= 1024 && a.tokens >= 256 && count == 1) cfg = 112;      // many rounds: 256 x 96
         else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
-        else if (a.K >= 2048 && (a.K / 128) % 2 == 0 && count == 1) cfg = 113;   // long reductions: two slices per stage, half the barriers (1 % at K = 3072, 5 % at 4096)
+        else if (a.K >= 2048 && (a.K / 128) % 2 == 0 && count == 1 && n96 <= 256) cfg = 113;   // long reductions in one round of tiles: two slices per stage, half the barriers (4 % at K = 3072; slower with two rounds)
         else cfg = 116;                                          // 128 x 96, eight wavefronts
     }
     if constexpr (!ODD8) {
