@@ -433,10 +433,19 @@ __device__ __forceinline__ uint32_t requant4(const v4i c, const float (&g)[4], c
 // product of the largest).
 __device__ __forceinline__ void absmax_commit(float m, float out_scale, float* dst)
 {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+    // in-register lane moves (DPP within rows of 16, then across the rows): lane 63 ends up with the
+    // maximum of all 64; six round trips through the LDS crossbar cost a microsecond of latency
+#define NM_MAX_STEP(ctrl, row_mask) \
+    m = fmaxf(m, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(m), ctrl, row_mask, 0xF, false)))
+    NM_MAX_STEP(0x111, 0xF);   // row_shr:1
+    NM_MAX_STEP(0x112, 0xF);   // row_shr:2
+    NM_MAX_STEP(0x114, 0xF);   // row_shr:4
+    NM_MAX_STEP(0x118, 0xF);   // row_shr:8
+    NM_MAX_STEP(0x142, 0xA);   // row_bcast:15 -> rows 1 and 3
+    NM_MAX_STEP(0x143, 0xC);   // row_bcast:31 -> rows 2 and 3
+#undef NM_MAX_STEP
     m = m * out_scale;
-    if ((threadIdx.x & 63) == 0 && dst != nullptr) {
+    if ((threadIdx.x & 63) == 63 && dst != nullptr) {
         unsigned int* u = reinterpret_cast<unsigned int*>(dst);
         if (__float_as_uint(m) > __hip_atomic_load(u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
             atomicMax(u, __float_as_uint(m));
