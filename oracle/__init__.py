@@ -242,6 +242,18 @@ def requant(acc, act_scale, scales, out_scale, bias=None):
     return q, float(amax.value)
 
 
+def quantize_act(X, scale=None):
+    """(int8 codes [tokens, K], float32 scale): the per-tensor 8-bit activation quantiser; scale None =
+    the largest magnitude / 127 (1 for an all-zero tensor)."""
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    tokens, K = X.shape
+    Q = np.empty((tokens, K), np.int8)
+    s = ctypes.c_float(0.0)
+    _check(_load().nmo_quantize_act(_p(X), tokens, K, K, ctypes.c_float(0.0 if scale is None else float(np.float32(scale))),
+                                    _p(Q), K, ctypes.byref(s)))
+    return Q, np.float32(s.value)
+
+
 def admm_project(W, U, N, M, bits, rows_per_scale):
     """(Z, U_out, scales): the Z-update Z = Pi(W + U) with both constraints and the dual update
     U + W - Z; bits = 0 leaves the quantisation constraint out (scales is then None)."""

@@ -39,6 +39,9 @@
  *   nmo_requant        Sec. 5.3 (activations are 8-bit integers) with the scalar
  *                      quantiser of Sec. 3.3, Eq. 5 (o = 0) applied to a layer's
  *                      output, so that the next layer reads int8 again.
+ *   nmo_quantize_act   the same quantiser on a floating-point activation tensor (the
+ *                      input of the first compressed layer): one scale for the whole
+ *                      tensor by the largest-magnitude rule of Sec. 3.3.1, 8 bits.
  *
  * Readings where the paper is silent (all listed in the design notes):
  *   - "largest" means largest magnitude; equal magnitudes keep the lower column.
@@ -483,6 +486,34 @@ int nmo_dequant(const int32_t *acc, int tokens, int O, int ldacc, float act_scal
             if (out_f32) out_f32[(size_t)t * ldo + o] = yf;
             if (out_bf16) out_bf16[(size_t)t * ldo + o] = bf16_rne(yf);
         }
+    return NMO_OK;
+}
+
+/*
+ * A floating-point activation tensor as 8-bit integers (Sec. 5.3: the layers take
+ * 8-bit activations; the paper says no more): one scale for the whole tensor,
+ * s = max|x| / 127 (Sec. 3.3.1's largest-magnitude rule; 1 for an all-zero tensor),
+ * or the caller's when scale_in > 0, then Eq. 5 (o = 0) per element exactly as
+ * for the weights.  *scale_out receives the scale used.
+ */
+int nmo_quantize_act(const float *X, int tokens, int K, int ldx, float scale_in,
+                     int8_t *Q, int ldq, float *scale_out)
+{
+    if (!X || !Q) return NMO_ERR_NULL;
+    if (tokens <= 0 || K <= 0 || ldx < K || ldq < K) return NMO_ERR_DIM;
+    float amax = 0.0f;
+    for (int t = 0; t < tokens; ++t)
+        for (int k = 0; k < K; ++k) {
+            float x = X[(size_t)t * ldx + k];
+            if (!isfinite(x)) return NMO_ERR_NONFINITE;
+            if (fabsf(x) > amax) amax = fabsf(x);
+        }
+    volatile float smax = amax / 127.0f;   /* one fp32 division */
+    float s = scale_in > 0.0f ? scale_in : (amax == 0.0f ? 1.0f : smax);
+    for (int t = 0; t < tokens; ++t)
+        for (int k = 0; k < K; ++k)
+            Q[(size_t)t * ldq + k] = (int8_t)nmo_quantize_one(X[(size_t)t * ldx + k], s, 8);
+    if (scale_out) *scale_out = s;
     return NMO_OK;
 }
 
