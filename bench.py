@@ -665,6 +665,27 @@ def main():
             "us_back_to_back": round(us, 2), "algorithmic_bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1),
             "dense_equiv_tops": round(gs.dense_ops / us / 1e6, 1)}
 
+    # ---- fp32 activations of the first layer's shape -> int8 codes (statistic, scale, codes; all on the device) ----
+    if args.workload in ("bert_base", "bert_large") and args.only is None:
+        g0 = gemms[0]
+        Xf = torch.randn((g0.T, g0.K), dtype=torch.float32, device=dev)
+        Xq8 = torch.empty((g0.T, g0.K), dtype=torch.int8, device=dev)
+        amax = torch.zeros(1, dtype=torch.float32, device=dev)
+        s_x = torch.ones(1, dtype=torch.float32, device=dev)
+
+        def act_chain(X, T, K, am, sc, Q, st):
+            return (lib.nm_absmax_to_scale(am, sc, 1, st) or lib.nm_absmax_f32(X, T, K, K, am, st)
+                    or lib.nm_absmax_to_scale(am, sc, 0, st) or lib.nm_quantize_act(X, T, K, K, 0.0, sc, Q, K, st))
+        a_chain = (Xf.data_ptr(), g0.T, g0.K, amax.data_ptr(), s_x.data_ptr(), Xq8.data_ptr(), stream)
+        us_chain = timed_launches(act_chain, a_chain, 20)
+        us_q = timed_launches(lib.nm_quantize_act, (Xf.data_ptr(), g0.T, g0.K, g0.K, 0.0, s_x.data_ptr(), Xq8.data_ptr(), g0.K, stream), 20)
+        result["kernels"]["act_quantize_%dx%d" % (g0.T, g0.K)] = {
+            "us_statistic_scale_codes": round(us_chain, 2), "algorithmic_bytes": 9 * g0.T * g0.K,
+            "GBps": round(9 * g0.T * g0.K / us_chain / 1e3, 1),
+            "us_codes_only": round(us_q, 2), "GBps_codes_only": round(5 * g0.T * g0.K / us_q / 1e3, 1),
+            "note": "fp32 -> int8 with the tensor's own max|x|/127: the statistic is reset and recomputed in every repetition "
+                    "(four launches); back to back, the tensor stays in the Infinity Cache"}
+
     # ---- CPU oracle on a bounded sample of the same workload --------------------------------
     if not args.no_cpu_baseline:
         import oracle

@@ -383,6 +383,46 @@ int nm_gemm_q8(const int8_t *X_dev, int tokens, int K, int ldx, float act_scale,
  */
 int nm_absmax_to_scale(float *absmax_dev, float *scale_dev, int reset, void *hip_stream);
 
+/*
+ * The largest magnitude of a floating-point activation tensor (the statistic of the
+ * largest-magnitude rule, Sec. 3.3.1, for the 8-bit activations of Sec. 5.3): on the stream,
+ * *absmax_dev = max(*absmax_dev, max over t < tokens, k < K of |X[t][k]|), combined atomically.
+ * The caller sets *absmax_dev (to 0, or to a running maximum >= 0) before the call; several
+ * tensors may share one statistic.  One pass that reads 4 bytes per element.
+ *
+ *   X_dev       fp32 [tokens][ldx], row-major, device, 4-byte aligned; read only.  Finite values
+ *               (not checked: a NaN is ignored, an infinity becomes the maximum).  16-byte
+ *               aligned with K % 4 == 0 and ldx % 4 == 0 (or ldx == K and tokens * K % 4 == 0)
+ *               is read fastest.
+ *   tokens, K   > 0; ldx >= K  (NM_ERR_DIM otherwise).
+ *   absmax_dev  one device float, 4-byte aligned.
+ */
+int nm_absmax_f32(const float *X_dev, int tokens, int K, int ldx, float *absmax_dev, void *hip_stream);
+
+/*
+ * A floating-point activation tensor as the 8-bit integers nm_gemm takes (Sec. 5.3; the
+ * quantiser is Eq. 5 of Sec. 3.3 with offset 0 at 8 bits, exactly as nm_compress applies it to
+ * the weights):
+ *
+ *   Xq[t][k] = clamp(rne(X[t][k] / s), -127, 127),   the quotient correctly rounded in fp32,
+ *
+ * with one scale s for the whole tensor: `scale`, or the device float `scale_dev` when that is
+ * not NULL - read when the kernel runs, e.g. what nm_absmax_to_scale wrote after nm_absmax_f32,
+ * which makes s = max|X| / 127, the rule of Sec. 3.3.1.  One pass that reads 4 bytes and writes
+ * 1 byte per element.  The same s is the act_scale (act_scale_dev) of the nm_gemm that follows.
+ *
+ *   X_dev       as for nm_absmax_f32.  Finite values (not checked; the code of a NaN is
+ *               unspecified, an infinity takes the clamp's +-127).
+ *   scale       > 0, finite when scale_dev is NULL (NM_ERR_SCALE otherwise); a device scale
+ *               must be positive and finite too (not checked: the host cannot see it).
+ *   Xq_dev      int8 [tokens][ldq], ldq >= K, device; written for k < K only.  4-byte aligned
+ *               with ldq % 4 == 0 (or ldq == ldx == K) next to the alignment named for X_dev is
+ *               written fastest; any other alignment takes a kernel of one element per lane.
+ *   X_dev and Xq_dev must not overlap.
+ */
+int nm_quantize_act(const float *X_dev, int tokens, int K, int ldx, float scale, const float *scale_dev,
+                    int8_t *Xq_dev, int ldq, void *hip_stream);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char *nm_status_string(int status);
 

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     NM_LAYOUT_TILED,
     NMError,
     library_path,
+    nm_absmax_f32,
     nm_absmax_to_scale,
     nm_compress,
     nm_compress_batch,
@@ -20,6 +21,7 @@ from .binding import (  # noqa: F401
     nm_gemm_q8,
     nm_packed_sizes,
     nm_project,
+    nm_quantize_act,
     nm_repack,
     nm_scale_search,
     nm_scale_search_static,

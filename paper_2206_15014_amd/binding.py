@@ -90,6 +90,10 @@ def _load():
                                c_int, c_int, c_int, c_int, c_int, c_vp, c_f, c_vp, c_vp, c_int, c_vp, c_vp]
     lib.nm_absmax_to_scale.restype = c_int
     lib.nm_absmax_to_scale.argtypes = [c_vp, c_vp, c_int, c_vp]
+    lib.nm_absmax_f32.restype = c_int
+    lib.nm_absmax_f32.argtypes = [c_vp, c_int, c_int, c_int, c_vp, c_vp]
+    lib.nm_quantize_act.restype = c_int
+    lib.nm_quantize_act.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_int, c_vp]
     lib.nm_test_force_gemm_tile.restype = c_int
     lib.nm_test_force_gemm_tile.argtypes = [c_int]
     lib.nm_bench_smfmac_probe.restype = c_int
@@ -327,6 +331,33 @@ def nm_absmax_to_scale(absmax, scale, reset: bool = False, stream=None):
     if rc:
         raise NMError(rc, "nm_absmax_to_scale")
     return scale
+
+
+def nm_absmax_f32(X, absmax, stream=None):
+    """X: float32 CUDA tensor [tokens, K] (row stride >= K); absmax: float32 tensor of one element
+    that the caller has set (0, or a running maximum): max |X| is max-combined into it.  Returns
+    absmax."""
+    tokens, K = X.shape
+    rc = _load().nm_absmax_f32(_ptr(X), tokens, K, X.stride(0), _ptr(absmax), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_absmax_f32")
+    return absmax
+
+
+def nm_quantize_act(X, scale: float = 0.0, out=None, scale_dev=None, stream=None):
+    """X: float32 CUDA tensor [tokens, K] -> int8 codes clamp(rne(X / s), -127, 127) with the
+    tensor's one scale s: `scale`, or the float32 tensor of one element `scale_dev` that
+    replaces it.  `out` (int8 [tokens, >= K] by row stride) is allocated here when not passed.
+    Returns out."""
+    import torch
+    tokens, K = X.shape
+    if out is None:
+        out = torch.empty((tokens, K), dtype=torch.int8, device=X.device)
+    rc = _load().nm_quantize_act(_ptr(X), tokens, K, X.stride(0), float(scale), _ptr(scale_dev),
+                                 _ptr(out), out.stride(0), _stream(stream))
+    if rc:
+        raise NMError(rc, "nm_quantize_act")
+    return out
 
 
 def nm_project(W, U, N: int, M: int, bits: int, rows_per_scale: int, Z=None, U_out=None, scales=None, stream=None):

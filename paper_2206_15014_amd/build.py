@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "libnm.so")
 # set of N:M patterns, so that their many instantiations build in parallel.
 DMA_SETS = 11
 SOURCES = [("nm_gemm_dma.hip", ["-DNM_DMA_SET=%d" % k], "nm_gemm_dma_%d.o" % k) for k in range(DMA_SETS)] + \
-          [(s, [], s.replace(".hip", ".o")) for s in ["nm_api.hip", "nm_compress.hip", "nm_gemm.hip", "nm_project.hip", "nm_scale_search.hip"]]
+          [(s, [], s.replace(".hip", ".o")) for s in ["nm_api.hip", "nm_compress.hip", "nm_gemm.hip", "nm_project.hip", "nm_quantize_act.hip", "nm_scale_search.hip"]]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -283,6 +283,24 @@ int nm_absmax_to_scale(float* absmax_dev, float* scale_dev, int reset, void* hip
     return nm::launch_absmax_to_scale(absmax_dev, scale_dev, reset, static_cast<hipStream_t>(hip_stream));
 }
 
+int nm_absmax_f32(const float* X_dev, int tokens, int K, int ldx, float* absmax_dev, void* hip_stream)
+{
+    if (!X_dev || !absmax_dev) return NM_ERR_NULL;
+    if (tokens <= 0 || K <= 0 || ldx < K) return NM_ERR_DIM;
+    if ((uintptr_t)X_dev % 4 || (uintptr_t)absmax_dev % 4) return NM_ERR_ALIGN;
+    return nm::launch_absmax_f32(X_dev, tokens, K, ldx, absmax_dev, static_cast<hipStream_t>(hip_stream));
+}
+
+int nm_quantize_act(const float* X_dev, int tokens, int K, int ldx, float scale, const float* scale_dev,
+                    int8_t* Xq_dev, int ldq, void* hip_stream)
+{
+    if (!X_dev || !Xq_dev) return NM_ERR_NULL;
+    if (tokens <= 0 || K <= 0 || ldx < K || ldq < K) return NM_ERR_DIM;
+    if (!scale_dev && (!(scale > 0.0f) || !(scale <= 3.402823466e38f))) return NM_ERR_SCALE;
+    if ((uintptr_t)X_dev % 4 || (uintptr_t)scale_dev % 4) return NM_ERR_ALIGN;
+    return nm::launch_quantize_act(X_dev, tokens, K, ldx, scale, scale_dev, Xq_dev, ldq, static_cast<hipStream_t>(hip_stream));
+}
+
 const char* nm_status_string(int status)
 {
     switch (status) {

@@ -8,6 +8,7 @@
 #include <stdint.h>
 
 #include "nm_internal.h"
+#include "nm_quantize.h"
 
 namespace nm {
 
@@ -47,41 +48,6 @@ __device__ __forceinline__ uint32_t group_or(uint32_t v)
     if constexpr (LANES >= 8) v |= dpp_u32<0x141>(v);
     if constexpr (LANES >= 16) v |= dpp_u32<0x140>(v);
     return v;
-}
-
-// The correctly rounded fp32 quotient w / s for many w and one s.  RECIP = false: the division
-// operator.  RECIP = true: the same value from y = RN(1 / s), computed once per row: q0 = RN(w y)
-// is within 1.5 ulp of w / s (y and the product each carry half an ulp of their own); one
-// residual step, q1 = RN(q0 + RN(w - s q0) y), lands within half an ulp plus a 2^-24th of an ulp,
-// i.e. on one of the two neighbours of w / s; and for such a q1 the residual w - s q1 is exact in
-// one fused multiply-add and q2 = RN(q1 + (w - s q1) y) is RN(w / s) itself when y is the
-// correctly rounded reciprocal (Markstein's theorem on fused-multiply-add division) - five
-// operations in place of the eleven of the division sequence.  Valid without overflow, underflow
-// or subnormal y; the caller takes this route only for 2^-60 <= s <= 2^60, where |w| <= 127 s
-// keeps every intermediate normal or, for quotients far below one half, irrelevant to the code.
-template <bool RECIP>
-struct Divisor {
-    float s, y;
-    __device__ __forceinline__ float quotient(float w) const
-    {
-        if constexpr (RECIP) {
-            const float q0 = __fmul_rn(w, y);
-            const float q1 = __fmaf_rn(__fmaf_rn(-s, q0, w), y, q0);
-            return __fmaf_rn(__fmaf_rn(-s, q1, w), y, q1);
-        } else {
-            return __fdiv_rn(w, s);
-        }
-    }
-};
-
-// Eq. 5 with offset 0: correctly rounded fp32 quotient, round half to even, symmetric clamp.
-template <int BITS, bool RECIP>
-__device__ __forceinline__ int quantize(float w, const Divisor<RECIP>& d)
-{
-    constexpr float QMAX = (float)((1 << (BITS - 1)) - 1);
-    float r = rintf(d.quotient(w));
-    r = fminf(fmaxf(r, -QMAX), QMAX);
-    return (int)r;
 }
 
 // Eq. 3 on one group held in registers.  Returns a bit mask of the kept columns: an entry is

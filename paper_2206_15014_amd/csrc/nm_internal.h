@@ -139,6 +139,9 @@ int launch_scale_search(const float* W, int rows, int cols, int ldw, int N, int 
 int launch_scale_search_static(const float* W, int rows, int cols, int ldw, int N, int M, int bits, int rows_per_scale,
                                int candidates, float* scales, hipStream_t st);
 int launch_absmax_to_scale(float* absmax, float* scale, int reset, hipStream_t st);
+int launch_absmax_f32(const float* X, int tokens, int K, int ldx, float* absmax, hipStream_t st);
+int launch_quantize_act(const float* X, int tokens, int K, int ldx, float scale, const float* scale_dev, int8_t* Q, int ldq,
+                        hipStream_t st);
 int launch_smfmac_probe(int blocks, int iters, unsigned long long* counters, hipStream_t st);
 int launch_gemm(const GemmArgs& a, hipStream_t st);
 // `count` (1 .. GEMM_BATCH_MAX) GEMMs of one pattern, layout and output type: one launch where the

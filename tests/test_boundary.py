@@ -18,7 +18,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(nm_[a-z0-9_]+)\s*\(", header))
     assert names >= {"nm_packed_sizes", "nm_compress", "nm_compress_grouped", "nm_compress_batch", "nm_decompress_i8", "nm_gemm", "nm_gemm_q8",
-                     "nm_gemm_batch", "nm_project", "nm_absmax_to_scale", "nm_scale_search", "nm_scale_search_workspace_bytes", "nm_scale_search_static", "nm_compress_scaled", "nm_repack",
+                     "nm_gemm_batch", "nm_project", "nm_absmax_to_scale", "nm_absmax_f32", "nm_quantize_act", "nm_scale_search", "nm_scale_search_workspace_bytes", "nm_scale_search_static", "nm_compress_scaled", "nm_repack",
                      "nm_status_string"}
     lib = ctypes.CDLL(binding.library_path())
     for n in names:
@@ -137,6 +137,16 @@ def test_entry_points_validate_before_launch():
     assert lib.nm_absmax_to_scale(None, P, 0, None) == -1 and lib.nm_absmax_to_scale(P, None, 0, None) == -1
     assert lib.nm_absmax_to_scale(P, P + 2, 0, None) == -6
     assert lib.nm_absmax_to_scale(P, P, 0, None) == -2
+    assert lib.nm_absmax_f32(None, 4, 8, 8, P, None) == -1 and lib.nm_absmax_f32(P, 4, 8, 8, None, None) == -1
+    assert lib.nm_absmax_f32(P, 0, 8, 8, P, None) == -2 and lib.nm_absmax_f32(P, 4, 0, 8, P, None) == -2 and lib.nm_absmax_f32(P, 4, 8, 7, P, None) == -2
+    assert lib.nm_absmax_f32(P + 2, 4, 8, 8, P, None) == -6 and lib.nm_absmax_f32(P, 4, 8, 8, P + 1, None) == -6
+    qa = lambda **k: lib.nm_quantize_act(*[k.get(n, d) for n, d in [
+        ("X", P), ("T", 4), ("K", 8), ("ldx", 8), ("s", ctypes.c_float(0.5)), ("sd", None), ("Q", P), ("ldq", 8), ("st", None)]])
+    assert qa(X=None) == -1 and qa(Q=None) == -1
+    assert qa(T=0) == -2 and qa(K=-1) == -2 and qa(ldx=7) == -2 and qa(ldq=7) == -2
+    for bad in (0.0, -1.0, float("inf"), float("nan")):
+        assert qa(s=ctypes.c_float(bad)) == -9
+    assert qa(X=P + 1) == -6 and qa(sd=P + 2) == -6
 
 
 def test_status_strings():

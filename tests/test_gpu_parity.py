@@ -1009,3 +1009,144 @@ def test_compress_batch_and_gemm_replayed_from_a_graph():
         ref = oracle.compress(Ws[0], N, M, bits)
         acc_ref = oracle.gemm_sparse(Xq, ref[0], ref[1], O, N, M, bits)
         check_outputs(acc_ref, sx, ref[2], None, acc.cpu().numpy(), y.cpu().numpy(), None, what="replay %d" % rep)
+
+
+# ---- floating-point activations -> 8-bit codes (nm_absmax_f32, nm_quantize_act) ----
+
+def _act_buffers(X, ldx, ldq, x_off=0, q_off=0):
+    """Device copies of X with row stride ldx starting x_off floats into a 16-byte aligned allocation, and an
+    int8 output of row stride ldq starting q_off bytes in, pre-filled with 77 so that stray writes show."""
+    T, K = X.shape
+    xbuf = torch.zeros(x_off + T * ldx, dtype=torch.float32, device=DEV)
+    Xd = xbuf[x_off:x_off + T * ldx].view(T, ldx)[:, :K]
+    Xd.copy_(torch.from_numpy(X))
+    qbuf = torch.full((q_off + T * ldq,), 77, dtype=torch.int8, device=DEV)
+    Qd = qbuf[q_off:q_off + T * ldq].view(T, ldq)[:, :K]
+    return Xd, Qd, qbuf
+
+
+ACT_SHAPES = [
+    # tokens, K, ldx, ldq, x_off, q_off
+    (384, 768, 768, 768, 0, 0),          # a layer's input, one long row of 16-byte pieces
+    (7, 36, 36, 36, 0, 0),               # far less than one workgroup
+    (4, 33, 33, 33, 0, 0),               # rows are not whole pieces, the tensor is
+    (5, 33, 33, 33, 0, 0),               # nothing is: one element per lane
+    (130, 4100, 4104, 4112, 0, 0),       # padded rows of whole pieces, ragged against the block width
+    (130, 4100, 4104, 4112, 4, 8),       # ... starting a piece further in
+    (61, 250, 253, 251, 1, 3),           # odd strides and offsets
+    (70000, 8, 12, 8, 0, 0),             # more rows than the grid has: the row loop
+    (1, 1, 1, 1, 0, 0),
+]
+
+
+@pytest.mark.parametrize("T,K,ldx,ldq,x_off,q_off", ACT_SHAPES)
+def test_quantize_act_matches_oracle(T, K, ldx, ldq, x_off, q_off):
+    """max |x| -> scale -> codes, every scale on the device, against the oracle's quantiser: scale and codes bit-exact,
+    padding of the output untouched."""
+    say("quantize_act", T, K, ldx, ldq, x_off, q_off)
+    rng = np.random.default_rng(T * 131 + K)
+    X = (rng.standard_normal((T, K)) * rng.choice([0.01, 1.0, 40.0])).astype(np.float32)
+    X[rng.integers(T), rng.integers(K)] *= 3.0                               # one clear maximum somewhere
+    Q_ref, s_ref = oracle.quantize_act(X)
+    Xd, Qd, qbuf = _act_buffers(X, ldx, ldq, x_off, q_off)
+    amax = torch.zeros(1, dtype=torch.float32, device=DEV)
+    s_dev = torch.zeros(1, dtype=torch.float32, device=DEV)
+    nm.nm_absmax_f32(Xd, amax)
+    nm.nm_absmax_to_scale(amax, s_dev)
+    nm.nm_quantize_act(Xd, out=Qd, scale_dev=s_dev)
+    torch.cuda.synchronize()
+    assert float(amax.item()) == float(np.abs(X).max())
+    assert np.float32(s_dev.item()) == s_ref
+    assert np.array_equal(Qd.cpu().numpy(), Q_ref)
+    full = qbuf.cpu().numpy()
+    assert np.all(full[:q_off] == 77)
+    pad = full[q_off:].reshape(T, ldq)[:, K:]
+    assert np.all(pad == 77)
+    # the host scale takes the same decisions as the device one
+    Q2 = nm.nm_quantize_act(Xd, scale=float(s_ref))
+    assert np.array_equal(Q2.cpu().numpy(), Q_ref)
+
+
+@pytest.mark.parametrize("scale", [0.5, 2.0 ** -50, 2.0 ** -61, 1e-30, 3.0e-39, 1e30, 2.0 ** 60, 2.0 ** 61, 0.1, 1.0 / 3.0])
+@pytest.mark.parametrize("aligned", [True, False])
+def test_quantize_act_with_a_caller_scale(scale, aligned):
+    """A caller's scale (both division routes of the kernel and the scales between them): half-way quotients, values
+    far outside the representable range and tiny ones, against the oracle."""
+    say("quantize_act caller scale", scale, aligned)
+    s = np.float32(scale)
+    rng = np.random.default_rng(9)
+    K = 64 if aligned else 63
+    steps = np.concatenate([np.arange(-130, 131) + 0.5, np.arange(-130, 131), rng.uniform(-140, 140, 3 * K)]).astype(np.float32)
+    with np.errstate(over="ignore", under="ignore"):
+        body = (steps * s).astype(np.float32)                                   # exact where s is a power of two
+        extremes = np.array([3.0e38, -3.0e38, 1e30, -1e30, 1e-30, -1e-30, 1e-44, 0.0, -0.0, 127.49, -127.51], np.float32)
+        flat = np.concatenate([body[np.isfinite(body)], extremes, (extremes * s).astype(np.float32)])
+    flat = flat[np.isfinite(flat)]
+    flat = np.resize(flat, (len(flat) + K - 1) // K * K)
+    X = flat.reshape(-1, K)
+    Q_ref, s_used = oracle.quantize_act(X, scale=s)
+    assert s_used == s
+    Xd, Qd, _ = _act_buffers(X, K, K, 0, 0)
+    nm.nm_quantize_act(Xd, scale=float(s), out=Qd)
+    torch.cuda.synchronize()
+    got = Qd.cpu().numpy()
+    bad = np.argwhere(got != Q_ref)
+    assert bad.size == 0, "first differences (t, k, x, got, want): %r" % [
+        (int(t), int(k), float(X[t, k]), int(got[t, k]), int(Q_ref[t, k])) for t, k in bad[:5]]
+
+
+def test_absmax_f32_degenerate_and_running_maximum():
+    say("absmax_f32 zero tensor / running maximum")
+    X = np.zeros((9, 40), np.float32)
+    Xd, Qd, _ = _act_buffers(X, 40, 40)
+    amax = torch.zeros(1, dtype=torch.float32, device=DEV)
+    s_dev = torch.zeros(1, dtype=torch.float32, device=DEV)
+    nm.nm_absmax_f32(Xd, amax)
+    nm.nm_absmax_to_scale(amax, s_dev)
+    nm.nm_quantize_act(Xd, out=Qd, scale_dev=s_dev)
+    torch.cuda.synchronize()
+    Q_ref, s_ref = oracle.quantize_act(X)
+    assert float(amax.item()) == 0.0 and np.float32(s_dev.item()) == s_ref == np.float32(1.0)
+    assert np.array_equal(Qd.cpu().numpy(), Q_ref)
+    # a statistic shared by two tensors, and one that is already larger than both
+    rng = np.random.default_rng(3)
+    A = rng.standard_normal((33, 128)).astype(np.float32)
+    B = (rng.standard_normal((17, 57)) * 2).astype(np.float32)
+    amax.zero_()
+    nm.nm_absmax_f32(torch.from_numpy(A).to(DEV), amax)
+    nm.nm_absmax_f32(torch.from_numpy(B).to(DEV), amax)
+    torch.cuda.synchronize()
+    assert float(amax.item()) == float(max(np.abs(A).max(), np.abs(B).max()))
+    amax.fill_(1e6)
+    nm.nm_absmax_f32(torch.from_numpy(A).to(DEV), amax)
+    torch.cuda.synchronize()
+    assert float(amax.item()) == float(np.float32(1e6))
+
+
+def test_quantize_act_feeds_the_sparse_gemm():
+    """fp32 activations -> codes and scale on the device -> nm_gemm reading that device scale, against the oracle's
+    quantiser, sparse product and dequantisation."""
+    say("quantize_act -> nm_gemm")
+    N, M, bits = 2, 4, 8
+    T, K, O = 200, 256, 320
+    rng = np.random.default_rng(77)
+    X = rng.standard_normal((T, K)).astype(np.float32)
+    W = (rng.standard_normal((O, K)) * 0.02).astype(np.float32)
+    ref = oracle.compress(W, N, M, bits)
+    Q_ref, s_ref = oracle.quantize_act(X)
+    acc_ref = oracle.gemm_sparse(Q_ref, ref[0], ref[1], O, N, M, bits)
+    y_ref, _ = oracle.dequant(acc_ref, s_ref, ref[2], None)
+    packed = nm.nm_compress(torch.from_numpy(W).to(DEV), N, M, bits, layout=TILED)
+    Xd = torch.from_numpy(X).to(DEV)
+    amax = torch.zeros(1, dtype=torch.float32, device=DEV)
+    s_dev = torch.zeros(1, dtype=torch.float32, device=DEV)
+    nm.nm_absmax_f32(Xd, amax)
+    nm.nm_absmax_to_scale(amax, s_dev)
+    Xq = nm.nm_quantize_act(Xd, scale_dev=s_dev)
+    acc = torch.zeros((T, O), dtype=torch.int32, device=DEV)
+    y = torch.zeros((T, O), dtype=torch.float32, device=DEV)
+    nm.nm_gemm(Xq, 0.0, *packed, O, N, M, bits, acc=acc, out=y, out_dtype=NM_OUT_F32, layout=TILED, act_scale_dev=s_dev)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), acc_ref)
+    tol = 1e-5 * np.abs(acc_ref) * float(s_ref) * ref[2][None, :]
+    assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - y_ref) <= tol + 1e-30)
