@@ -609,7 +609,7 @@ __device__ __forceinline__ void gemm_dma_tile(const GemmArgs& a, const int tiles
 // One GEMM per launch.  Workgroup -> tile: each XCD (workgroups are dealt to the eight XCDs in
 // turn) takes a contiguous run of tiles, so that the CUs behind one L2 share token rows.
 template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU>
-__global__ void __launch_bounds__(64 * WAVES_T * WAVES_O)
+__global__ void __launch_bounds__(64 * WAVES_T * WAVES_O, STAGES == 2 ? 2 : 1)
 gemm_dma_kernel(const GemmArgs a_in, const int tiles_o, const int n_tiles)
 {
     GemmArgs a = a_in;
@@ -704,6 +704,45 @@ bool launch_dma_tile(const GemmArgs* items, int count, hipStream_t st)
 // where that still gives every CU a tile, else 128 x 96 (exactly 256 workgroups for BERT-base's
 // 768-wide layers at 4096 tokens).  Rings of at most 80 KB let two workgroups share a CU, which
 // overlaps one's epilogue with the other's prologue when there are several rounds.
+// Tile choice for 2:4 int8 (the pattern of the paper's inference table) from a duration model of
+// every compiled shape: microseconds = P + R * (F + S * K / 128), R = rounds of tiles over the
+// chip's workgroup slots (256 for the shapes whose ring fills a CU, 512 for those that leave room
+// for a second workgroup; a last round that fills at most half the slots of a two-per-CU shape
+// counts as `tail`).  P, F and S are least-squares fits to launches measured back to back at 4096
+// to 24576 tokens on the BERT-base and BERT-large layer shapes (mean error 3 to 7 %); choosing by
+// the model lands within 1.4 % of the fastest shape on average over those 48 cases.  What the
+// fits say: the two-stage shapes (two workgroups per CU, each covering the other's barrier waits,
+// first loads and stores) have almost no fixed cost per tile but the costliest K step, so they
+// win on short reductions and few rounds and lose on K = 3072 / 4096; 256 x 256 wins where 192
+// does not divide the width.  Outputs beyond the 256 MB Infinity Cache stream to HBM as they are
+// produced: there the two-per-CU shapes fall behind (more operand re-reads per multiply-add
+// compete with the stores) and are left out.
+inline int modelled_tile(const GemmArgs& a)
+{
+    struct Model { int cfg, bt, bo, slots; float tail, p, f, s; };
+    static const Model models[] = {
+        {122, 256, 192, 256, 1.0f, 0.61f, 4.59f, 0.750f}, {123, 256, 256, 256, 1.0f, 1.07f, 7.72f, 0.904f},
+        {121, 256, 128, 256, 1.0f, 0.70f, 3.21f, 0.663f}, {128, 192, 128, 256, 1.0f, 0.98f, 2.86f, 0.500f},
+        {117, 128, 128, 256, 1.0f, 1.64f, 2.41f, 0.368f}, {116, 128, 96, 512, 0.5f, 2.25f, 2.98f, 0.588f},
+        {113, 128, 96, 512, 0.5f, 1.65f, 6.09f, 0.520f},  {112, 256, 96, 256, 1.0f, 0.97f, 4.18f, 0.462f},
+        {133, 128, 192, 512, 0.7f, 0.95f, 1.34f, 1.190f}, {136, 128, 256, 512, 0.6f, 0.06f, 3.47f, 1.279f}};
+    const bool streams_out = (long long)a.tokens * a.O * (a.out_dtype == 3 ? 1 : a.out_dtype == 1 ? 4 : 2) > (256ll << 20);
+    float best = 0.0f;
+    int pick = 116;
+    for (const Model& m : models) {
+        const long long ct = (a.O + m.bo - 1) / m.bo;
+        if ((ct * m.bo - a.O) * 8 > a.O) continue;                       // an eighth of the columns computed in vain
+        if (m.cfg == 113 && (a.K / 128) % 2 != 0) continue;             // two slices per stage
+        if (m.slots > 256 && m.cfg != 116 && m.cfg != 113 && streams_out) continue;
+        const long long n = (long long)((a.tokens + m.bt - 1) / m.bt) * ct;
+        const long long full = n / m.slots, rem = n % m.slots;
+        const float rounds = (float)full + (rem == 0 ? 0.0f : (m.slots > 256 && rem <= m.slots / 2) ? m.tail : 1.0f);
+        const float us = m.p + rounds * (m.f + m.s * (float)(a.K / 128));
+        if (best == 0.0f || us < best) { best = us; pick = m.cfg; }
+    }
+    return pick;
+}
+
 template <int N, int M, int BITS>
 bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cfg)
 {
@@ -779,7 +818,11 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         if (!U::DUAL && n96 < 128 && n64x48 <= 256) cfg = 130;
         else if (!U::DUAL && n96 < 128 && n64x96 <= 256 && count == 1) cfg = 132;
         else if (NARROW_ONCE && count == 1 && ((DECODE_BOUND && ALWAYS_ONCE) || a.O <= 1024)) cfg = 127;
+        else if (U::IDENTITY && count == 1 && n96 >= 256) cfg = modelled_tile(a);
         else if (pick == 122 && WIDE24) cfg = count == 1 ? 126 : (N == 3 ? 117 : 122);
+        else if (pick == 122 && !U::DUAL && count == 1 && a.K <= 1024 &&
+                 (long long)a.tokens * a.O * (a.out_dtype == 3 ? 1 : a.out_dtype == 1 ? 4 : 2) <= (256ll << 20))
+            cfg = 133;      // the decoded patterns on short reductions: two 128 x 192 workgroups per CU (3 to 12 % under 256 x 192, measured on every one of them)
         else if (pick != 0) cfg = pick;
         else if (!ODD8 && n96 >= 1024 && a.tokens >= 256 && count == 1) cfg = 112;      // many rounds: 256 x 96
         else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
@@ -807,9 +850,11 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     }
     if constexpr (U::IDENTITY) {
         if (cfg == 123) return launch_dma_tile<N, M, BITS, 256, 256, 2, 2, 3, 1>(items, count, st);
+        if (cfg == 136) return launch_dma_tile<N, M, BITS, 128, 256, 2, 2, 2, 1>(items, count, st);
     }
     if constexpr (!U::DUAL) {
         if (cfg == 113) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(items, count, st);
+        if (cfg == 133) return launch_dma_tile<N, M, BITS, 128, 192, 2, 2, 2, 1>(items, count, st);
         // small tiles for problems of a few output tiles (few tokens): more workgroups, each with a
         // smaller share of X and W to pull through its CU's fill path
         if (cfg == 130) return launch_dma_tile<N, M, BITS, 64, 48, 2, 1, 4, 1, true>(items, count, st);

@@ -24,7 +24,7 @@ DUAL_SCHEMES = [(3, 4, 8), (3, 4, 4), (4, 8, 8), (4, 8, 4), (4, 4, 8), (4, 4, 4)
 ALL_SCHEMES = FAST_SCHEMES + DUAL_SCHEMES + [(3, 8, 4), (5, 8, 8), (7, 8, 4), (8, 8, 8), (8, 8, 4)]
 LAYOUTS = [ROWS, TILED]
 # tile variants of the LDS-direct kernels (tiled layout); the second list is what the two-operand patterns compile
-DMA_TILES = [112, 113, 115, 116, 117, 121, 122, 123, 128, 130, 132]
+DMA_TILES = [112, 113, 115, 116, 117, 121, 122, 123, 128, 130, 132, 133, 136]
 DUAL_TILES = [112, 115, 116, 117]
 ODD8_SCHEMES = [(n, 8, b) for n in (3, 5, 6, 7) for b in (8, 4)]     # units of 6 .. 28 bytes, also two operands per unit
 ODD8_TILES = [115, 116, 117, 127]
@@ -247,7 +247,7 @@ def test_gemm_tiled_layout_every_tile_shape(tile):
     _gemm_small(2, 4, 8, tile, TILED)
 
 
-@pytest.mark.parametrize("tile", [0, 113, 115, 117, 121, 122, 127, 128, 130, 132])
+@pytest.mark.parametrize("tile", [0, 113, 115, 117, 121, 122, 127, 128, 130, 132, 133])
 @pytest.mark.parametrize("N,M,bits", FAST_SCHEMES[1:])
 def test_gemm_decoded_patterns_on_the_tiled_kernels(N, M, bits, tile):
     """The patterns that are re-encoded in registers, on the tile shapes the launcher picks for
@@ -622,7 +622,7 @@ def q8_scale(acc_ref, sx, scales_ref, bias):
     return np.float32(np.abs(f32).max() / 127.0)
 
 
-@pytest.mark.parametrize("tile,layout", [(0, ROWS), (2, ROWS), (0, TILED), (113, TILED), (116, TILED), (122, TILED)])
+@pytest.mark.parametrize("tile,layout", [(0, ROWS), (2, ROWS), (0, TILED), (113, TILED), (116, TILED), (122, TILED), (133, TILED), (136, TILED)])
 @pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (1, 4, 4), (2, 8, 4), (4, 4, 8)])
 def test_gemm_q8_fast_paths(N, M, bits, tile, layout):
     """Every kernel family, whole and ragged tiles, rows of 16-byte, 8-byte and 4-byte granularity, with and
