@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # cannot be read from inside this process: the figures are those of the file named here and go stale with
 # any change of the tiling (the file states the commit it was measured at).
 TRAFFIC_PROFILE = "profiles/bert_base_2of4_int8_counters.txt"
-MEASURED_HBM_BYTES_BF16 = {"qkv": 31.28e6, "attn_out": 12.62e6, "ffn_up": 40.57e6, "ffn_down": 30.91e6}
+MEASURED_HBM_BYTES_BF16 = {"qkv": 31.25e6, "attn_out": 12.59e6, "ffn_up": 40.54e6, "ffn_down": 30.88e6}
 
 
 def parse():
@@ -357,9 +357,10 @@ def main():
     # The GEMM launches of a step: one nm_gemm per layer, except that the query / key / value layers of an
     # attention block that share a scheme (and their input) go through one nm_gemm_batch call.
     units = [(gemm_fn, ga[:-1]) for ga in gargs]
+    unit_members = [[k] for k in range(len(gargs))]          # which layers each launch of the step computes
     grouped_launches = 0
     if args.workload == "table4" and args.qkv == "grouped" and args.out_dtype != "i8":
-        units, keep_items, i = [], [], 0
+        units, unit_members, keep_items, i = [], [], [], 0
         scheme = lambda j: (j["g"].N, j["g"].M, j["g"].bits, j["g"].K, j["X"].data_ptr())
         while i < len(jobs):
             block = [i]
@@ -379,9 +380,11 @@ def main():
                                                 for m in run])
                     keep_items.append(items)
                     units.append((lib.nm_gemm_batch, (items, len(run), g.N, g.M, g.bits, layout, out_code)))
+                    unit_members.append(list(run))
                     grouped_launches += 1
                 else:
                     units.append((gemm_fn, gargs[k][:-1]))
+                    unit_members.append([k])
             i += len(block)
 
     def run_step(st, mode=None):
@@ -446,13 +449,28 @@ def main():
     per_gemm_us = [timed_launches(gemm_fn, a, 40) for a in gargs]
     per_comp_us = [timed_launches(lib.nm_compress, a, 40) for a in cargs]
     batch_comp_us = sum(timed_launches(lib.nm_compress_batch, b + (stream,), 40) for b in batches)
-    # The dominant GEMM: the longest launch; among launches within 5 % of it (FFN-up and FFN-down of a BERT layer take
-    # turns from run to run) the one that moves the most bytes, so that the roofline names the same kernel every run.
+    # The dominant kernel: a kernel trace lists the step's launches by kernel name, i.e. by the tile variant the
+    # library chose for each launch (a measurement hook of the library reports it).  The dominant kernel is the
+    # variant whose launches take the largest share of the step's GEMM time; the roofline is priced on the longest
+    # of its launches (a launch of nm_gemm_batch counts with all the layers it computes).
     def moved_bytes(g):
         kc = g.K // g.M * g.N
         return g.T * g.K + g.O * kc * (g.bits + synth.index_bits(g.N, g.M)) // 8 + 8 * g.O + g.T * g.O * out_bytes
-    longest = max(per_gemm_us)
-    dom = max((i for i, u in enumerate(per_gemm_us) if u >= 0.95 * longest), key=lambda i: (moved_bytes(gemms[i]), per_gemm_us[i]))
+    unit_us, unit_variant = [], []
+    for (fn, ua), mem in zip(units, unit_members):
+        check(fn(*(ua + (stream,))))
+        g = gemms[mem[0]]
+        unit_variant.append((lib.nm_bench_last_gemm_tile(), g.N, g.M, g.bits, len(mem)))
+        unit_us.append(per_gemm_us[mem[0]] if len(mem) == 1 else timed_launches(fn, ua + (stream,), 40))
+    torch.cuda.synchronize()
+    share = {}
+    for v, u in zip(unit_variant, unit_us):
+        share[v] = share.get(v, 0.0) + u
+    top = max(share, key=lambda v: share[v])
+    dom_unit = max((i for i, v in enumerate(unit_variant) if v == top),
+                   key=lambda i: (unit_us[i], sum(moved_bytes(gemms[m]) for m in unit_members[i])))
+    dom_members = unit_members[dom_unit]
+    dom = dom_members[0]
 
     # ---- timed region -----------------------------------------------------------------------
     # The launches of a step are short (4-20 us each), so they are captured once into a HIP
@@ -505,7 +523,7 @@ def main():
     # Launch duration of the dominant kernel: HIP events around back-to-back (graph-replayed) launches
     # of that same kernel, right after the timed steps; a rocprofv3 kernel trace of this command
     # reports the same kernel about a microsecond shorter (the gap between two launches).
-    dom_us = timed_launches(gemm_fn, gargs[dom], 40)
+    dom_us = timed_launches(units[dom_unit][0], units[dom_unit][1] + (stream,), 40)
 
     # ---- second timed leg: the same step over buffer sets rotated through more than the Infinity Cache holds ----
     # Every set has its own weights, packed buffers, activations and outputs (copies of the first set), so
@@ -583,10 +601,16 @@ def main():
     names = [g.name for g in gemms]
     if len(set(names)) < len(names):       # several layers: say which layer and scheme
         names = ["L%02d.%s %d:%d i%d" % (g.seed[1], g.name, g.N, g.M, g.bits) for g in gemms]
-    achieved = gd.dense_ops / (dom_us * 1e-6) / 1e12
-    kc = gd.K // gd.M * gd.N
-    real_ops = 2 * gd.T * gd.O * kc                         # int8 operations the method performs (pruned products never formed)
-    alg_bytes = gd.T * gd.K + gd.O * kc * (gd.bits + synth.index_bits(gd.N, gd.M)) // 8 + 8 * gd.O + gd.T * gd.O * out_bytes
+    achieved = sum(gemms[m].dense_ops for m in dom_members) / (dom_us * 1e-6) / 1e12
+    # int8 operations the method performs (pruned products never formed), and the bytes one launch has to move
+    # (layers of one nm_gemm_batch launch that read the same activations read them once)
+    real_ops = sum(2 * gemms[m].T * gemms[m].O * (gemms[m].K // gemms[m].M * gemms[m].N) for m in dom_members)
+    alg_bytes = sum(moved_bytes(gemms[m]) for m in dom_members)
+    seen_x = set()
+    for m in dom_members:
+        if jobs[m]["X"].data_ptr() in seen_x:
+            alg_bytes -= gemms[m].T * gemms[m].K
+        seen_x.add(jobs[m]["X"].data_ptr())
     frac_real = real_ops / (dom_us * 1e-6) / 1e12 / INT8_DENSE_PEAK_TOPS
     frac_hbm = alg_bytes / (dom_us * 1e-6) / 1e9 / HBM_PEAK_GBS
     hbm_bound = frac_hbm >= frac_real
@@ -613,6 +637,10 @@ def main():
         "streaming_leg": streaming,
         "k_loop_leg": k_loop,
         "gemm_launches_per_step": len(units),
+        "dominant_kernel": {"tile_variant": top[0], "pattern": "%d:%d int%d" % top[1:4], "layers_per_launch": top[4], "launches_per_step": sum(1 for v in unit_variant if v == top),
+                            "us_of_gemm_us": [round(share[top], 2), round(sum(unit_us), 2)],
+                            "note": "the step's nm_gemm launches grouped by the kernel variant the library chose for them (as a kernel trace groups "
+                                    "them by name); the group with the largest share of the time; `roofline` is its longest launch"},
         "grouped_qkv_launches": grouped_launches,
         "roofline": {
             # the roof that binds this kernel: the larger of its two fractions, both from the method's own work
@@ -629,7 +657,8 @@ def main():
             "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, calibrated on a copy); a stored figure from " + TRAFFIC_PROFILE,
             "algorithmic_bytes": alg_bytes,
             "real_int8_ops": real_ops,
-            "kernel": "nm_gemm %s %dx%d->%d %d:%d int%d" % (gd.name, gd.T, gd.K, gd.O, gd.N, gd.M, gd.bits),
+            "kernel": "%s %s %dx%d->%s %d:%d int%d" % ("nm_gemm" if len(dom_members) == 1 else "nm_gemm_batch", "+".join(gemms[m].name for m in dom_members),
+                                                       gd.T, gd.K, "+".join(str(gemms[m].O) for m in dom_members), gd.N, gd.M, gd.bits),
             "note": "duration = HIP events around 200 back-to-back launches of this kernel (5 replays of a 40-launch graph) after "
                     "the timed steps; operands cache-hot (one buffer set)",
             "duration_us": round(dom_us, 2),

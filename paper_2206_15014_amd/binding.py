@@ -96,6 +96,8 @@ def _load():
     lib.nm_quantize_act.argtypes = [c_vp, c_int, c_int, c_int, c_f, c_vp, c_vp, c_int, c_vp]
     lib.nm_test_force_gemm_tile.restype = c_int
     lib.nm_test_force_gemm_tile.argtypes = [c_int]
+    lib.nm_bench_last_gemm_tile.restype = c_int
+    lib.nm_bench_last_gemm_tile.argtypes = []
     lib.nm_bench_smfmac_probe.restype = c_int
     lib.nm_bench_smfmac_probe.argtypes = [c_int, c_int, c_vp, c_vp]
     lib.nm_status_string.restype = ctypes.c_char_p

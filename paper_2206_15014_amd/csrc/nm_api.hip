@@ -30,16 +30,20 @@ void canonical_dense(int& N, int& M)
 }
 
 std::atomic<int> g_forced_tile{0};
+std::atomic<int> g_last_tile{0};
 
 }  // namespace
 
 namespace nm {
 int forced_gemm_tile() { return g_forced_tile.load(std::memory_order_relaxed); }
+void note_gemm_tile(int cfg) { g_last_tile.store(cfg, std::memory_order_relaxed); }
 }
 
 extern "C" {
 
 int nm_test_force_gemm_tile(int cfg) { return g_forced_tile.exchange(cfg, std::memory_order_relaxed); }
+
+int nm_bench_last_gemm_tile(void) { return g_last_tile.load(std::memory_order_relaxed); }
 
 int nm_bench_smfmac_probe(int blocks, int iters, unsigned long long* counters_dev, void* hip_stream)
 {

@@ -323,6 +323,7 @@ void launch_pattern(const GemmArgs& a, hipStream_t st, int tile_cfg)
     // small ones keep narrow layers (few output rows) from leaving CUs idle.
     const long long big = (long long)((a.tokens + 127) / 128) * ((a.O + 127) / 128);
     if (tile_cfg < 1 || tile_cfg > 3) tile_cfg = (big >= 384) ? 1 : 2;
+    note_gemm_tile(tile_cfg);
     switch (tile_cfg) {
         case 1: launch_depth<N, M, BITS, 128, 128, 2, 2, 2>(a, st); break;
         case 2: launch_depth<N, M, BITS, 128, 64, 2, 2, 2>(a, st); break;
@@ -415,6 +416,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t st)
     }
     const long long total = (long long)a.tokens * a.O;
     hipLaunchKernelGGL(gemm_generic_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
+    note_gemm_tile(-1);
     return launch_status();
 }
 

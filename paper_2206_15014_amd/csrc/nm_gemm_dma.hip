@@ -829,6 +829,7 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         else if (a.K >= 2048 && (a.K / 128) % 2 == 0 && count == 1 && n96 <= 256) cfg = 113;   // long reductions in one round of tiles: two slices per stage, half the barriers (4 % at K = 3072; slower with two rounds)
         else cfg = 116;                                          // 128 x 96, eight wavefronts
     }
+    note_gemm_tile(cfg);
     if constexpr (!ODD8) {
         if (cfg == 112) return launch_dma_tile<N, M, BITS, 256, 96, 4, 2, 3, 1>(items, count, st);
     }

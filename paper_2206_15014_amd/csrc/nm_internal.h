@@ -153,6 +153,10 @@ bool launch_gemm_dma(const GemmArgs* items, int count, hipStream_t st, int cfg);
 
 // Tile variant forced by the tests (0 = automatic), see nm_test_hooks.h.
 int forced_gemm_tile();
+// Records which kernel variant the last nm_gemm / nm_gemm_q8 / nm_gemm_batch call launched (the tile ids
+// of the LDS-direct kernels, 1 .. 3 for the register-staged shapes, -1 for the one-thread-per-output
+// kernel): read back by bench.py to group a step's launches by kernel.
+void note_gemm_tile(int cfg);
 
 }  // namespace nm
 

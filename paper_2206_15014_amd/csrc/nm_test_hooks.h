@@ -23,6 +23,16 @@ int nm_test_force_gemm_tile(int cfg);
  * 2 * 16 * 16 * 128 dense-equivalent operations each.
  */
 int nm_bench_smfmac_probe(int blocks, int iters, unsigned long long *counters_dev, void *hip_stream);
+
+/*
+ * Measurement hook of bench.py: the kernel variant that the most recent nm_gemm, nm_gemm_q8 or
+ * nm_gemm_batch call of this process launched - the tile id of the LDS-direct kernels (>= 100),
+ * 1 .. 3 for the register-staged kernel of the row layout, -1 for the one-thread-per-output
+ * kernel, 0 before the first call.  bench.py groups the launches of a step by it, as a kernel
+ * trace groups them by kernel name.  One process-wide atomic integer: meaningful only while one
+ * thread issues the calls.
+ */
+int nm_bench_last_gemm_tile(void);
 #ifdef __cplusplus
 }
 #endif
