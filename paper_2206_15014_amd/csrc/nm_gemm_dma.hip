@@ -624,7 +624,7 @@ gemm_dma_kernel(const GemmArgs a_in, const int tiles_o, const int n_tiles)
 // to - a second, dependent round trip to the argument memory before the first loads, which a
 // launch of one GEMM does without (it costs that launch 0.1 to 0.5 us), hence a kernel of its own.
 template <int N, int M, int BITS, int BT, int BO, int WAVES_T, int WAVES_O, int STAGES, int KU>
-__global__ void __launch_bounds__(64 * WAVES_T * WAVES_O)
+__global__ void __launch_bounds__(64 * WAVES_T * WAVES_O, STAGES == 2 ? 2 : 1)
 gemm_dma_batch_kernel(const GemmBatch p)
 {
     const int n_tiles = p.first_tile[p.count];
@@ -820,9 +820,9 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
         else if (NARROW_ONCE && count == 1 && ((DECODE_BOUND && ALWAYS_ONCE) || a.O <= 1024)) cfg = 127;
         else if (U::IDENTITY && count == 1 && n96 >= 256) cfg = modelled_tile(a);
         else if (pick == 122 && WIDE24) cfg = count == 1 ? 126 : (N == 3 ? 117 : 122);
-        else if (pick == 122 && !U::DUAL && count == 1 && a.K <= 1024 &&
+        else if (pick == 122 && (!U::DUAL || (N == M && BITS == 4)) && a.K <= 1024 &&
                  (long long)a.tokens * a.O * (a.out_dtype == 3 ? 1 : a.out_dtype == 1 ? 4 : 2) <= (256ll << 20))
-            cfg = 133;      // the decoded patterns on short reductions: two 128 x 192 workgroups per CU (3 to 12 % under 256 x 192, measured on every one of them)
+            cfg = 133;      // the decoded patterns and dense int4 on short reductions: two 128 x 192 workgroups per CU (3 to 13 % under 256 x 192, measured on every one of them)
         else if (pick != 0) cfg = pick;
         else if (!ODD8 && n96 >= 1024 && a.tokens >= 256 && count == 1) cfg = 112;      // many rounds: 256 x 96
         else if (!U::IDENTITY) cfg = 115;                        // decode work: four wavefronts of 64 x 48 decode each weight fragment twice, eight of 32 x 48 four times
@@ -844,6 +844,7 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     }
     if constexpr (!U::DUAL || (BITS == 4 && N != 3 && !ODD8)) {      // (3:4 needs a few registers more for its index bits: it would spill)
         if (cfg == 122) return launch_dma_tile<N, M, BITS, 256, 192, 4, 2, 3, 1, true>(items, count, st);
+        if (cfg == 133) return launch_dma_tile<N, M, BITS, 128, 192, 2, 2, 2, 1, true>(items, count, st);
     }
     if constexpr (!U::DUAL || (BITS == 4 && !ODD8)) {
         if (cfg == 128) return launch_dma_tile<N, M, BITS, 192, 128, 4, 2, 3, 1>(items, count, st);
@@ -855,7 +856,6 @@ bool launch_dma_pattern(const GemmArgs* items, int count, hipStream_t st, int cf
     }
     if constexpr (!U::DUAL) {
         if (cfg == 113) return launch_dma_tile<N, M, BITS, 128, 96, 4, 2, 3, 2>(items, count, st);
-        if (cfg == 133) return launch_dma_tile<N, M, BITS, 128, 192, 2, 2, 2, 1>(items, count, st);
         // small tiles for problems of a few output tiles (few tokens): more workgroups, each with a
         // smaller share of X and W to pull through its CU's fill path
         if (cfg == 130) return launch_dma_tile<N, M, BITS, 64, 48, 2, 1, 4, 1, true>(items, count, st);

@@ -255,7 +255,7 @@ def test_gemm_decoded_patterns_on_the_tiled_kernels(N, M, bits, tile):
     _gemm_small(N, M, bits, tile, TILED, shapes=[(520, 768, 400), (200, 256, 136), (300, 1536, 200)], seed=3)
 
 
-@pytest.mark.parametrize("tile", [0] + DUAL_TILES + [121, 122, 126, 127, 128])
+@pytest.mark.parametrize("tile", [0] + DUAL_TILES + [121, 122, 126, 127, 128, 133])
 @pytest.mark.parametrize("N,M,bits", DUAL_SCHEMES + [(8, 8, 8)])
 def test_gemm_two_operand_patterns_on_the_matrix_pipe(N, M, bits, tile):
     """3:4, 4:8 and dense matrices (more than two kept entries per subgroup of four): each unit is
@@ -307,7 +307,7 @@ def _gemm_batch(N, M, bits, layout, tile, shapes, seed, shared_x=False):
                     check_outputs(acc_ref, sx, ref[2], bias, None, None, b16[:, :O], what=what)
 
 
-@pytest.mark.parametrize("tile", [0, 116, 122, 130])
+@pytest.mark.parametrize("tile", [0, 116, 122, 130, 133])
 @pytest.mark.parametrize("N,M,bits", [(2, 4, 8), (2, 4, 4), (1, 8, 8), (4, 4, 4), (4, 8, 8), (3, 4, 8)])
 def test_gemm_batch_one_launch_for_several_layers(N, M, bits, tile):
     """Items of different shapes (ragged tiles, K of 1 to 6 slices) whose tiles share one launch of a
