@@ -1150,3 +1150,40 @@ def test_quantize_act_feeds_the_sparse_gemm():
     assert np.array_equal(acc.cpu().numpy(), acc_ref)
     tol = 1e-5 * np.abs(acc_ref) * float(s_ref) * ref[2][None, :]
     assert np.all(np.abs(y.cpu().numpy().astype(np.float64) - y_ref) <= tol + 1e-30)
+
+
+# ---- which kernel variant a call launches -------------------------------------------------------
+
+@pytest.mark.parametrize("T,K,O,N,M,bits,dtype,expect", [
+    (4096, 768, 3072, 2, 4, 8, torch.bfloat16, {133}),          # BERT-base FFN-up and QKV: two 128 x 192 workgroups per CU
+    (4096, 768, 2304, 2, 4, 8, torch.bfloat16, {133}),
+    (4096, 768, 768, 2, 4, 8, torch.bfloat16, {116, 113}),      # the narrow outputs: 128 x 96
+    (4096, 3072, 768, 2, 4, 8, torch.bfloat16, {116, 113}),
+    (12288, 1024, 4096, 2, 4, 8, torch.bfloat16, {136}),        # BERT-large FFN-up: two 128 x 256 workgroups per CU
+    (12288, 4096, 1024, 2, 4, 8, torch.bfloat16, {123}),        # long reduction: 256 x 256
+    (49152, 768, 3072, 2, 4, 8, torch.bfloat16, {122, 123}),    # output larger than the Infinity Cache: no two-per-CU shape
+    (4096, 768, 3072, 2, 8, 4, torch.bfloat16, {133}),          # a decoded pattern on a short reduction
+    (4096, 768, 3072, 4, 4, 4, torch.bfloat16, {133}),          # dense int4
+    (4096, 768, 3072, 4, 8, 4, torch.bfloat16, {126}),          # 4:8 int4 keeps 256 x 192 with the wavefronts 2 x 4
+    (128, 768, 768, 2, 4, 8, torch.bfloat16, {130}),            # few tokens: the smallest tile
+])
+def test_tile_choice_on_the_paper_shapes(T, K, O, N, M, bits, dtype, expect):
+    """The launcher's tile choice on the layer shapes the benchmarks run, read back through the measurement hook
+    (timing-derived, so a change of it should be a decision, not an accident), and that the chosen kernel's output
+    equals that of another tile variant on the same operands."""
+    say("tile choice", T, K, O, N, M, bits)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(T + K + O)
+    W = torch.randn((O, K), generator=gen, device=DEV, dtype=torch.float32) * 0.02
+    X = torch.randint(-127, 128, (T, K), generator=gen, device=DEV, dtype=torch.int8)
+    packed = nm.nm_compress(W, N, M, bits, layout=TILED)
+    out = torch.zeros((T, O), dtype=dtype, device=DEV)
+    nm.nm_gemm(X, 0.05, *packed, O, N, M, bits, out=out, out_dtype=NM_OUT_BF16, layout=TILED)
+    tile = binding.raw().nm_bench_last_gemm_tile()
+    torch.cuda.synchronize()
+    assert tile in expect, "tile %d, expected one of %s" % (tile, sorted(expect))
+    other = torch.zeros((T, O), dtype=dtype, device=DEV)
+    with forced_tile(117 if tile != 117 else 116):
+        nm.nm_gemm(X, 0.05, *packed, O, N, M, bits, out=other, out_dtype=NM_OUT_BF16, layout=TILED)
+        torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), other.view(torch.int16))
