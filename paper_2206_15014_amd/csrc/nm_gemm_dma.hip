@@ -4,12 +4,14 @@
 //
 // Why: at these layer shapes one workgroup per CU streams its X tile (first touch from HBM,
 // about a microsecond away) and its slice of the packed weights (from L2) at the CU's L1 fill
-// rate; that, the LDS traffic of the fragment reads and - with every CU busy - the board's power
-// limit (the clock is pulled down) bound the kernel, not the MFMA pipe.  Keeping several stages
-// of loads in flight without spending registers or LDS-store issue slots is what the
-// direct-to-LDS load is for; the packed weight bytes travel in their compact form and are
-// widened / re-encoded to the MFMA operand in registers (Sec. 5.3: low-bit weights are widened
-// for the ALUs).
+// rate; that, the LDS traffic of the fragment reads and - in a K loop that keeps every CU busy
+// for long - the board's power limit (the clock is pulled down) bound the loop, not the MFMA
+// pipe.  Keeping several stages of loads in flight without spending registers or LDS-store
+// issue slots is what the direct-to-LDS load is for; the packed weight bytes travel in their
+// compact form and are widened / re-encoded to the MFMA operand in registers (Sec. 5.3: low-bit
+// weights are widened for the ALUs).  On short reductions (K up to 1024) most of a launch is
+// spent outside the loop - first loads, barrier waits, stores - and the tile shapes with a ring
+// of two stages exist so that two workgroups share a CU and each works through the other's waits.
 //
 // The packed weights are read in the tiled layout of include/nm.h: what one 16-row x 128-column
 // fragment consumes is one contiguous run of memory, so a direct load asks the L2 for eight whole
