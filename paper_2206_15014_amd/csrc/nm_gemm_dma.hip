@@ -735,10 +735,12 @@ inline int modelled_tile(const GemmArgs& a)
         const long long ct = (a.O + m.bo - 1) / m.bo;
         if ((ct * m.bo - a.O) * 8 > a.O) continue;                       // an eighth of the columns computed in vain
         if (m.cfg == 113 && (a.K / 128) % 2 != 0) continue;             // two slices per stage
-        if (m.slots > 256 && m.cfg != 116 && m.cfg != 113 && streams_out) continue;
+        if ((m.cfg == 133 || m.cfg == 136) && streams_out) continue;
         const long long n = (long long)((a.tokens + m.bt - 1) / m.bt) * ct;
         const long long full = n / m.slots, rem = n % m.slots;
-        const float rounds = (float)full + (rem == 0 ? 0.0f : (m.slots > 256 && rem <= m.slots / 2) ? m.tail : 1.0f);
+        // (a two-stage shape whose only round leaves every workgroup alone on its CU: 0.9, measured at 2048 tokens)
+        const bool two_stage = m.cfg == 133 || m.cfg == 136;
+        const float rounds = (float)full + (rem == 0 ? 0.0f : (m.slots > 256 && rem <= m.slots / 2) ? (two_stage && full == 0 ? 0.9f : m.tail) : 1.0f);
         const float us = m.p + rounds * (m.f + m.s * (float)(a.K / 128));
         if (best == 0.0f || us < best) { best = us; pick = m.cfg; }
     }
